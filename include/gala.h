@@ -1,0 +1,156 @@
+/*
+ * gala.h -- C ABI of the MI355X (gfx950) GALA-A2C hot path.
+ *
+ * One context holds N independent A2C actor-learners that share one GPU
+ * (Sec. 3 of "Gossip-based Actor-Learner Architectures for Deep Reinforcement
+ * Learning").  A training round is Algorithm 1 for all agents at once:
+ *     gala_learner_step   returns/advantages + one A2C optimisation step per agent
+ *     gala_gossip         broadcast + parameter averaging over the peer topology
+ * Every step of both calls runs in HIP kernels on the stream given at creation.
+ *
+ * Conventions
+ *   - "dev" pointers are device memory on the GPU that was current when the
+ *     context was created; "host" pointers are ordinary host memory.
+ *   - Input buffers are borrowed: the caller keeps them alive and unmodified until
+ *     the work enqueued by the call has completed on the context's stream.
+ *     gala_learner_step and gala_gossip only enqueue; they never synchronise.
+ *     Calls that copy to a host pointer synchronise the stream before returning.
+ *   - All memory the library needs is allocated in gala_create and released in
+ *     gala_destroy; the hot calls allocate nothing.
+ *   - Every function returns 0 on success or a negative GALA_E* code;
+ *     gala_last_error() gives a text for the most recent failure of a context
+ *     (or of gala_create when passed NULL).  No exceptions cross this boundary.
+ *   - Parameter vectors use the canonical per-agent order
+ *         conv1.w conv1.b conv2.w conv2.b conv3.w conv3.b fc.w fc.b pi.w pi.b v.w v.b
+ *     with convolution weights OIHW row-major, dense weights (out, in) row-major and
+ *     the hidden layer's inputs ordered channel, row, column.  [N][d] means agent-major.
+ *     The library keeps its own internal ordering; get/set convert.
+ */
+#ifndef GALA_H
+#define GALA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define GALA_OK       0
+#define GALA_EINVAL  -1   /* bad argument, unsupported shape, invalid topology      */
+#define GALA_ENOMEM  -2   /* device or host allocation failed                       */
+#define GALA_EHIP    -3   /* a HIP runtime call failed (text in gala_last_error)    */
+#define GALA_ESTATE  -4   /* call order violated (e.g. gossip round went backwards) */
+
+typedef struct gala_ctx gala_ctx;   /* opaque, owned by the library */
+
+/* The network of App. C.2: three unpadded convolutions with ReLU (8x8 stride 4,
+ * 4x4 stride 2, 3x3 stride 1), one hidden layer with ReLU, a linear policy head and
+ * a linear value head.  Kernel sizes and strides are fixed; this build accepts
+ * in_c=4, in_h=in_w=84, c1=32, c2=64, c3=64, fc=512 and 1 <= n_actions <= 64. */
+typedef struct {
+    int in_c, in_h, in_w;
+    int c1, c2, c3;
+    int fc;
+    int n_actions;
+} gala_net_dims;
+
+/* Table 2 of the paper plus the rollout shape.  T = horizon N (5), B = simulators
+ * per learner (16).  RMSprop: v <- rms_alpha v + (1-rms_alpha) g^2,
+ * x <- x - lr g / (sqrt(v) + rms_eps), momentum 0.  Gradients are rescaled per
+ * agent by min(1, max_grad_norm / (||g||_2 + 1e-6)) first. */
+typedef struct {
+    int   T, B;
+    float gamma, vf_coef, ent_coef;
+    float lr, rms_alpha, rms_eps;
+    float max_grad_norm;
+    int   compute_dtype;       /* 0 = fp32 (the only value accepted by this build) */
+} gala_hparams;
+
+#define GALA_TOPO_RING      0   /* directed ring v1->v2->...->vn->v1: agent i receives from i-1 (Fig. 5) */
+#define GALA_TOPO_EXP       1   /* 1-peer exponential graph: at round r agent i mixes with
+                                   (i + 2^(r mod log2 N)) mod N; N must be a power of two       */
+#define GALA_TOPO_EXPLICIT  2   /* caller-supplied peers and weights, n_phases tables cycled by round */
+
+/* Mixing weights follow Algorithm 1: 1/(1+|N_in|) for ring and exponential graphs.
+ * max_delay = tau bounds message staleness; each edge (phase, receiver[, in-peer slot])
+ * gets a fixed delay splitmix64(delay_seed + edge_index) mod (tau+1) rounds, where
+ * edge_index = (phase * N + receiver) * max_in + slot.  An agent whose delayed message
+ * was never sent (round - delay < 0) skips averaging that round.
+ * For GALA_TOPO_EXPLICIT: peers is host int32 [n_phases][N][max_in] (-1 = unused slot),
+ * weights is host float [n_phases][N][max_in+1] with the self weight first; rows must be
+ * non-negative and sum to 1 within 1e-5 (row-stochastic, Sec. 2). */
+typedef struct {
+    int            kind;
+    int            max_delay;
+    uint64_t       delay_seed;
+    const int32_t *peers;
+    const float   *weights;
+    int            n_phases;
+    int            max_in;
+} gala_topology;
+
+/* Create a context for n_agents agents.  hip_stream is a hipStream_t (NULL = the
+ * default stream) on which all work is enqueued.  Parameters start at zero and the
+ * RMSprop state at zero; call gala_set_params before the first learner step. */
+int gala_create(gala_ctx **out, int n_agents, const gala_topology *topo,
+                const gala_net_dims *net, const gala_hparams *hp, void *hip_stream);
+int gala_destroy(gala_ctx *ctx);
+
+/* Parameters per agent (d), for sizing [N][d] buffers. */
+size_t gala_param_count(const gala_ctx *ctx);
+const char *gala_last_error(const gala_ctx *ctx);
+
+/* [N][d] float, canonical order; is_device says whether the pointer is dev or host. */
+int gala_set_params(gala_ctx *ctx, const float *src, int src_is_device);
+int gala_get_params(gala_ctx *ctx, float *dst, int dst_is_device);
+/* RMSprop second-moment estimates v, same shape and order. */
+int gala_set_opt_state(gala_ctx *ctx, const float *src, int src_is_device);
+int gala_get_opt_state(gala_ctx *ctx, float *dst, int dst_is_device);
+
+/* One A2C learner step for every agent (Algorithm 1: compute returns and advantages,
+ * then one optimisation step on the TD loss Eq. (1) and the batched policy gradient with
+ * entropy Eq. (4)).  All pointers dev:
+ *   obs_u8        uint8 [N][T][B][4][84][84]  states s_t (scaled by 1/255 inside)
+ *   actions       int32 [N][T][B]             in [0, n_actions); out-of-range is undefined
+ *   rewards       float [N][T][B]
+ *   dones         uint8 [N][T][B]             1 = the transition at t ended the episode
+ *   bootstrap_obs uint8 [N][B][4][84][84]     state reached after the last action */
+int gala_learner_step(gala_ctx *ctx, const uint8_t *obs_u8, const int32_t *actions,
+                      const float *rewards, const uint8_t *dones, const uint8_t *bootstrap_obs);
+
+/* One gossip iteration x_i <- sum_j p_ij x_j over the topology's table for this round
+ * (Sec. 2 "Gossip algorithms"; Algorithm 1, broadcast + averaging; Eq. (6) with delays).
+ * Rounds must be passed in increasing order starting at 0 when max_delay > 0. */
+int gala_gossip(gala_ctx *ctx, int64_t round);
+
+/* ---- diagnostics used by tests and logging -------------------------------------- */
+
+/* Pre-clip gradients of the last learner step, [N][d] canonical. */
+int gala_get_grads(gala_ctx *ctx, float *dst, int dst_is_device);
+/* host float [N][5]: policy-gradient term, TD term, entropy, pre-clip gradient norm,
+ * clip factor of the last learner step. */
+int gala_get_step_stats(gala_ctx *ctx, float *dst_host);
+/* Network outputs of the last learner step, host buffers (any may be NULL):
+ * logits [N][T*B][A], values [N][T*B+B] (rollout states, then bootstrap states),
+ * returns and advantages [N][T*B]. */
+int gala_get_outputs(gala_ctx *ctx, float *logits, float *values, float *returns, float *advantages);
+/* Distance from consensus (Prop. 1): max_i ||x_i - mean||_2 and ||X - mean||_F, host floats. */
+int gala_consensus_distance(gala_ctx *ctx, float *max_dist, float *frob);
+/* In-peer and delay tables the library will use at `round`, host int32 [N][max_in] each
+ * (max_in = 1 for ring and exponential graphs). */
+int gala_get_peer_table(gala_ctx *ctx, int64_t round, int32_t *peer, int32_t *delay);
+
+/* Per-phase timing (diagnostic).  While enabled, gala_learner_step and gala_gossip record a
+ * HIP event on the context's stream after every phase (conv1_fwd, ..., clip_rmsprop,
+ * gossip_mix).  gala_get_phase_times synchronises and returns the elapsed milliseconds
+ * between consecutive events recorded since the last learner step began: names receives
+ * the phase names joined by ';' (host, names_cap bytes), ms the durations (host, cap
+ * floats), *n_out how many. */
+int gala_set_profiling(gala_ctx *ctx, int enabled);
+int gala_get_phase_times(gala_ctx *ctx, char *names, size_t names_cap, float *ms, int cap, int *n_out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GALA_H */

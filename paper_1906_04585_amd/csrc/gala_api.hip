@@ -1,0 +1,357 @@
+// Host side of libgala: context, arena allocation, topology tables, and the C ABI
+// declared in include/gala.h.  Every numerical step is enqueued as a HIP kernel; this
+// file only validates arguments, owns memory and orders launches.
+#include "gala.h"
+#include "gala_internal.h"
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+using namespace gala;
+
+struct gala_ctx {
+    int N = 0;
+    Layout L{};
+    SegmentTable seg{};
+    HParams hp{};
+    int M = 0, F = 0;
+    int topo_kind = 0, tau = 0, n_phases = 1, max_in = 1;
+    std::vector<int32_t> h_peer, h_delay;
+    std::vector<float> h_weight;
+    Buffers b{};
+    int cur = 0;                 // which of b.x[] holds the current parameters
+    float *canon = nullptr;      // [N][d] staging for get/set through host pointers
+    int64_t last_round = -1;
+    hipStream_t stream = nullptr;
+    int device = 0;
+    std::vector<void *> allocs;
+    PhaseTimer timer;
+    char err[512] = {0};
+};
+
+static char g_create_err[512] = "";
+
+static int fail(gala_ctx *c, int code, const char *fmt, ...)
+{
+    char *dst = c ? c->err : g_create_err;
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(dst, 512, fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+#define HIP_OK(c, expr)                                                                          \
+    do {                                                                                         \
+        hipError_t e_ = (expr);                                                                  \
+        if (e_ != hipSuccess)                                                                    \
+            return fail((c), e_ == hipErrorOutOfMemory ? GALA_ENOMEM : GALA_EHIP, "%s: %s", #expr, \
+                        hipGetErrorString(e_));                                                  \
+    } while (0)
+
+static uint64_t splitmix64(uint64_t z)
+{
+    z += 0x9E3779B97F4A7C15ull;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+template <class T>
+static int dev_alloc(gala_ctx *c, T **p, size_t count, bool zero)
+{
+    void *q = nullptr;
+    const size_t bytes = (count ? count : 1) * sizeof(T);
+    HIP_OK(c, hipMalloc(&q, bytes));
+    c->allocs.push_back(q);
+    if (zero) HIP_OK(c, hipMemsetAsync(q, 0, bytes, c->stream));
+    *p = static_cast<T *>(q);
+    return GALA_OK;
+}
+
+static int build_topology(gala_ctx *c, const gala_topology *t)
+{
+    const int N = c->N;
+    c->topo_kind = t->kind;
+    c->tau = t->max_delay;
+    if (t->max_delay < 0 || t->max_delay > 16) return fail(nullptr, GALA_EINVAL, "max_delay must be in [0, 16]");
+    if (t->kind == GALA_TOPO_RING) {
+        c->n_phases = 1; c->max_in = 1;
+    } else if (t->kind == GALA_TOPO_EXP) {
+        if (N & (N - 1)) return fail(nullptr, GALA_EINVAL, "exponential graph needs a power-of-two agent count, got %d", N);
+        int m = 0;
+        while ((1 << (m + 1)) <= N) ++m;
+        c->n_phases = m > 0 ? m : 1; c->max_in = 1;
+    } else if (t->kind == GALA_TOPO_EXPLICIT) {
+        if (!t->peers || !t->weights || t->n_phases < 1 || t->max_in < 1 || t->max_in > 8)
+            return fail(nullptr, GALA_EINVAL, "explicit topology needs peers, weights, n_phases >= 1, 1 <= max_in <= 8");
+        c->n_phases = t->n_phases; c->max_in = t->max_in;
+    } else {
+        return fail(nullptr, GALA_EINVAL, "unknown topology kind %d", t->kind);
+    }
+    const int P = c->n_phases, K = c->max_in;
+    c->h_peer.assign((size_t)P * N * K, -1);
+    c->h_delay.assign((size_t)P * N * K, 0);
+    c->h_weight.assign((size_t)P * N * (K + 1), 0.f);
+    for (int ph = 0; ph < P; ++ph)
+        for (int i = 0; i < N; ++i) {
+            float *w = &c->h_weight[((size_t)ph * N + i) * (K + 1)];
+            int32_t *pr = &c->h_peer[((size_t)ph * N + i) * K];
+            if (t->kind == GALA_TOPO_EXPLICIT) {
+                double sum = 0.0;
+                for (int s = 0; s <= K; ++s) {
+                    w[s] = t->weights[((size_t)ph * N + i) * (K + 1) + s];
+                    if (!(w[s] >= 0.f)) return fail(nullptr, GALA_EINVAL, "negative mixing weight");
+                    sum += w[s];
+                }
+                for (int s = 0; s < K; ++s) {
+                    pr[s] = t->peers[((size_t)ph * N + i) * K + s];
+                    if (pr[s] >= N) return fail(nullptr, GALA_EINVAL, "peer index out of range");
+                    if (pr[s] < 0) { pr[s] = -1; sum -= w[1 + s]; w[1 + s] = 0.f; }
+                }
+                if (std::fabs(sum - 1.0) > 1e-5)
+                    return fail(nullptr, GALA_EINVAL, "mixing weights of agent %d, phase %d sum to %g, not 1", i, ph, sum);
+            } else {
+                // |N_in| = 1: uniform weights 1/(1+|N_in|) = 1/2 (Algorithm 1, footnote)
+                pr[0] = t->kind == GALA_TOPO_RING ? (i + N - 1) % N : (i + (1 << ph)) % N;
+                if (N == 1) pr[0] = 0;
+                w[0] = 0.5f; w[1] = 0.5f;
+            }
+            for (int s = 0; s < K; ++s) {
+                const uint64_t edge = ((uint64_t)ph * (uint64_t)N + (uint64_t)i) * (uint64_t)K + (uint64_t)s;
+                c->h_delay[((size_t)ph * N + i) * K + s] =
+                    c->tau > 0 ? (int32_t)(splitmix64(t->delay_seed + edge) % (uint64_t)(c->tau + 1)) : 0;
+            }
+        }
+    return GALA_OK;
+}
+
+extern "C" int gala_create(gala_ctx **out, int n_agents, const gala_topology *topo, const gala_net_dims *net,
+                           const gala_hparams *hp, void *hip_stream)
+{
+    if (!out || !topo || !net || !hp) return fail(nullptr, GALA_EINVAL, "null argument");
+    *out = nullptr;
+    if (n_agents < 1 || n_agents > 4096) return fail(nullptr, GALA_EINVAL, "n_agents must be in [1, 4096]");
+    if (net->in_c != C0 || net->in_h != H0 || net->in_w != W0 || net->c1 != C1 || net->c2 != C2 ||
+        net->c3 != C3 || net->fc != FC)
+        return fail(nullptr, GALA_EINVAL, "only the 4x84x84 -> 32/64/64 -> 512 network is supported");
+    if (net->n_actions < 1 || net->n_actions > 64) return fail(nullptr, GALA_EINVAL, "n_actions must be in [1, 64]");
+    if (hp->T < 1 || hp->B < 1 || (long)hp->T * hp->B > 4096) return fail(nullptr, GALA_EINVAL, "need T, B >= 1 and T*B <= 4096");
+    if (hp->compute_dtype != 0) return fail(nullptr, GALA_EINVAL, "compute_dtype %d not available (0 = fp32)", hp->compute_dtype);
+    if (!(hp->rms_eps > 0.f) || !(hp->rms_alpha >= 0.f && hp->rms_alpha < 1.f) || !(hp->max_grad_norm > 0.f))
+        return fail(nullptr, GALA_EINVAL, "need rms_eps > 0, 0 <= rms_alpha < 1, max_grad_norm > 0");
+
+    gala_ctx *c = new (std::nothrow) gala_ctx();
+    if (!c) return fail(nullptr, GALA_ENOMEM, "out of host memory");
+    c->N = n_agents;
+    c->L = make_layout(net->n_actions);
+    c->seg = make_segments(c->L);
+    c->hp = HParams{hp->T, hp->B, hp->gamma, hp->vf_coef, hp->ent_coef, hp->lr, hp->rms_alpha, hp->rms_eps,
+                    hp->max_grad_norm};
+    c->M = hp->T * hp->B;
+    c->F = c->M + hp->B;
+    c->stream = static_cast<hipStream_t>(hip_stream);
+    c->timer.stream = c->stream;
+    int rc = build_topology(c, topo);
+    if (rc != GALA_OK) { delete c; return rc; }
+
+    auto bail = [&](int code) { snprintf(g_create_err, 512, "%s", c->err); gala_destroy(c); return code; };
+    hipError_t he = hipGetDevice(&c->device);
+    if (he != hipSuccess) { fail(c, GALA_EHIP, "hipGetDevice: %s", hipGetErrorString(he)); return bail(GALA_EHIP); }
+
+    const size_t N = c->N, M = c->M, F = c->F, A = net->n_actions, dp = c->L.d_pad;
+    Buffers &b = c->b;
+#define ALLOC(ptr, count, zero) do { rc = dev_alloc(c, &(ptr), (count), (zero)); if (rc != GALA_OK) return bail(rc); } while (0)
+    ALLOC(b.x[0], N * dp, true); ALLOC(b.x[1], N * dp, true);
+    ALLOC(b.g, N * dp, true); ALLOC(b.v, N * dp, true);
+    if (c->tau > 0) ALLOC(b.hist, (size_t)(c->tau + 1) * N * dp, true);
+    ALLOC(b.a1, N * F * A1SZ, false); ALLOC(b.a2, N * F * A2SZ, false);
+    ALLOC(b.a3, N * F * A3SZ, false); ALLOC(b.h, N * F * FC, false);
+    ALLOC(b.logits, N * M * A, true); ALLOC(b.values, N * F, true);
+    ALLOC(b.ret, N * M, true); ALLOC(b.adv, N * M, true);
+    ALLOC(b.dlogits, N * M * A, false); ALLOC(b.dvalues, N * M, false);
+    ALLOC(b.dzh, N * M * FC, false); ALLOC(b.dz3, N * M * A3SZ, false);
+    ALLOC(b.dz2, N * M * A2SZ, false); ALLOC(b.dz1, N * M * A1SZ, false);
+    ALLOC(b.ws, workspace_floats(c->N, c->M, c->F), false);
+    ALLOC(b.norm_part, N * NORM_BLOCKS, true);
+    ALLOC(b.stats, N * 5, true);
+    ALLOC(b.cons_part, N * ((dp + CONS_COLS - 1) / CONS_COLS) + 2, true);
+    ALLOC(b.peer, c->h_peer.size(), false); ALLOC(b.delay, c->h_delay.size(), false);
+    ALLOC(b.weight, c->h_weight.size(), false);
+    ALLOC(c->canon, N * c->L.d, false);
+#undef ALLOC
+    he = hipMemcpyAsync(b.peer, c->h_peer.data(), c->h_peer.size() * 4, hipMemcpyHostToDevice, c->stream);
+    if (he == hipSuccess) he = hipMemcpyAsync(b.delay, c->h_delay.data(), c->h_delay.size() * 4, hipMemcpyHostToDevice, c->stream);
+    if (he == hipSuccess) he = hipMemcpyAsync(b.weight, c->h_weight.data(), c->h_weight.size() * 4, hipMemcpyHostToDevice, c->stream);
+    if (he == hipSuccess) he = hipStreamSynchronize(c->stream);
+    if (he != hipSuccess) { fail(c, GALA_EHIP, "table upload: %s", hipGetErrorString(he)); return bail(GALA_EHIP); }
+    *out = c;
+    return GALA_OK;
+}
+
+extern "C" int gala_destroy(gala_ctx *c)
+{
+    if (!c) return GALA_OK;
+    if (c->stream || !c->allocs.empty()) (void)hipStreamSynchronize(c->stream);
+    for (void *p : c->allocs) (void)hipFree(p);
+    for (hipEvent_t e : c->timer.ev) (void)hipEventDestroy(e);
+    delete c;
+    return GALA_OK;
+}
+
+extern "C" size_t gala_param_count(const gala_ctx *c) { return c ? (size_t)c->L.d : 0; }
+
+extern "C" const char *gala_last_error(const gala_ctx *c) { return c ? c->err : g_create_err; }
+
+// canonical [N][d] <-> an internal arena
+static int export_arena(gala_ctx *c, const float *arena, float *dst, int dst_is_device)
+{
+    if (!c || !dst) return fail(c, GALA_EINVAL, "null argument");
+    float *stage = dst_is_device ? dst : c->canon;
+    HIP_OK(c, launch_permute(c->N, c->L, c->seg, stage, const_cast<float *>(arena), 0, c->stream));
+    if (!dst_is_device) {
+        HIP_OK(c, hipMemcpyAsync(dst, stage, (size_t)c->N * c->L.d * 4, hipMemcpyDeviceToHost, c->stream));
+        HIP_OK(c, hipStreamSynchronize(c->stream));
+    }
+    return GALA_OK;
+}
+
+static int import_arena(gala_ctx *c, float *arena, const float *src, int src_is_device)
+{
+    if (!c || !src) return fail(c, GALA_EINVAL, "null argument");
+    const float *stage = src;
+    if (!src_is_device) {
+        HIP_OK(c, hipMemcpyAsync(c->canon, src, (size_t)c->N * c->L.d * 4, hipMemcpyHostToDevice, c->stream));
+        stage = c->canon;
+    }
+    HIP_OK(c, launch_permute(c->N, c->L, c->seg, const_cast<float *>(stage), arena, 1, c->stream));
+    if (!src_is_device) HIP_OK(c, hipStreamSynchronize(c->stream));
+    return GALA_OK;
+}
+
+extern "C" int gala_set_params(gala_ctx *c, const float *src, int dev) { return c ? import_arena(c, c->b.x[c->cur], src, dev) : GALA_EINVAL; }
+extern "C" int gala_get_params(gala_ctx *c, float *dst, int dev) { return c ? export_arena(c, c->b.x[c->cur], dst, dev) : GALA_EINVAL; }
+extern "C" int gala_set_opt_state(gala_ctx *c, const float *src, int dev) { return c ? import_arena(c, c->b.v, src, dev) : GALA_EINVAL; }
+extern "C" int gala_get_opt_state(gala_ctx *c, float *dst, int dev) { return c ? export_arena(c, c->b.v, dst, dev) : GALA_EINVAL; }
+extern "C" int gala_get_grads(gala_ctx *c, float *dst, int dev) { return c ? export_arena(c, c->b.g, dst, dev) : GALA_EINVAL; }
+
+extern "C" int gala_learner_step(gala_ctx *c, const uint8_t *obs_u8, const int32_t *actions, const float *rewards,
+                                 const uint8_t *dones, const uint8_t *bootstrap_obs)
+{
+    if (!c) return GALA_EINVAL;
+    if (!obs_u8 || !actions || !rewards || !dones || !bootstrap_obs) return fail(c, GALA_EINVAL, "null input buffer");
+    if ((reinterpret_cast<uintptr_t>(obs_u8) | reinterpret_cast<uintptr_t>(bootstrap_obs)) & 3)
+        return fail(c, GALA_EINVAL, "observation buffers must be 4-byte aligned");
+    NetArgs a{};
+    a.N = c->N; a.M = c->M; a.F = c->F; a.Bn = c->hp.B; a.L = c->L;
+    a.x = c->b.x[c->cur]; a.b = c->b; a.obs = obs_u8; a.boot = bootstrap_obs;
+    PhaseTimer *pt = &c->timer;
+    pt->begin();
+    HIP_OK(c, launch_forward(a, c->stream, pt));
+    HIP_OK(c, launch_loss(a, c->hp, actions, rewards, dones, c->stream));
+    pt->mark("returns_loss");
+    HIP_OK(c, launch_backward(a, c->stream, pt));
+    HIP_OK(c, launch_optimizer(c->N, c->L, c->hp, c->b.x[c->cur], c->b.v, c->b.g, c->b.norm_part, c->b.stats, c->stream, pt));
+    return GALA_OK;
+}
+
+extern "C" int gala_gossip(gala_ctx *c, int64_t round)
+{
+    if (!c) return GALA_EINVAL;
+    if (round < 0) return fail(c, GALA_EINVAL, "negative round");
+    if (c->tau > 0) {
+        // delayed messages are read from the history of consecutive rounds
+        if (round != c->last_round + 1)
+            return fail(c, GALA_ESTATE, "with max_delay > 0 rounds must be consecutive from 0: got %lld after %lld",
+                        (long long)round, (long long)c->last_round);
+        float *slot = c->b.hist + (size_t)(round % (c->tau + 1)) * c->N * c->L.d_pad;
+        HIP_OK(c, launch_publish(c->N, c->L, c->b.x[c->cur], slot, c->stream));
+        c->timer.mark("gossip_publish");
+    } else if (round < c->last_round) {
+        return fail(c, GALA_ESTATE, "gossip round went backwards: %lld after %lld", (long long)round, (long long)c->last_round);
+    }
+    const int phase = (int)(round % c->n_phases);
+    HIP_OK(c, launch_mix(c->N, c->L, c->b.x[c->cur], c->b.x[c->cur ^ 1], c->b.hist, c->tau, (long)round, phase,
+                         c->max_in, c->b.peer, c->b.delay, c->b.weight, c->stream));
+    c->timer.mark("gossip_mix");
+    c->cur ^= 1;
+    c->last_round = round;
+    return GALA_OK;
+}
+
+extern "C" int gala_get_step_stats(gala_ctx *c, float *dst_host)
+{
+    if (!c || !dst_host) return fail(c, GALA_EINVAL, "null argument");
+    HIP_OK(c, hipMemcpyAsync(dst_host, c->b.stats, (size_t)c->N * 5 * 4, hipMemcpyDeviceToHost, c->stream));
+    HIP_OK(c, hipStreamSynchronize(c->stream));
+    return GALA_OK;
+}
+
+extern "C" int gala_get_outputs(gala_ctx *c, float *logits, float *values, float *returns, float *advantages)
+{
+    if (!c) return GALA_EINVAL;
+    const size_t N = c->N, M = c->M, F = c->F, A = c->L.n_actions;
+    if (logits) HIP_OK(c, hipMemcpyAsync(logits, c->b.logits, N * M * A * 4, hipMemcpyDeviceToHost, c->stream));
+    if (values) HIP_OK(c, hipMemcpyAsync(values, c->b.values, N * F * 4, hipMemcpyDeviceToHost, c->stream));
+    if (returns) HIP_OK(c, hipMemcpyAsync(returns, c->b.ret, N * M * 4, hipMemcpyDeviceToHost, c->stream));
+    if (advantages) HIP_OK(c, hipMemcpyAsync(advantages, c->b.adv, N * M * 4, hipMemcpyDeviceToHost, c->stream));
+    HIP_OK(c, hipStreamSynchronize(c->stream));
+    return GALA_OK;
+}
+
+extern "C" int gala_consensus_distance(gala_ctx *c, float *max_dist, float *frob)
+{
+    if (!c || !max_dist || !frob) return fail(c, GALA_EINVAL, "null argument");
+    const size_t chunks = (c->L.d_pad + CONS_COLS - 1) / CONS_COLS;
+    float *result = c->b.cons_part + (size_t)c->N * chunks;
+    HIP_OK(c, launch_consensus(c->N, c->L, c->b.x[c->cur], c->b.cons_part, result, c->stream));
+    float r[2];
+    HIP_OK(c, hipMemcpyAsync(r, result, 8, hipMemcpyDeviceToHost, c->stream));
+    HIP_OK(c, hipStreamSynchronize(c->stream));
+    *max_dist = r[0]; *frob = r[1];
+    return GALA_OK;
+}
+
+extern "C" int gala_get_peer_table(gala_ctx *c, int64_t round, int32_t *peer, int32_t *delay)
+{
+    if (!c || round < 0 || (!peer && !delay)) return fail(c, GALA_EINVAL, "bad argument");
+    const int phase = (int)(round % c->n_phases);
+    const size_t n = (size_t)c->N * c->max_in, off = (size_t)phase * n;
+    if (peer) memcpy(peer, c->h_peer.data() + off, n * 4);
+    if (delay) memcpy(delay, c->h_delay.data() + off, n * 4);
+    return GALA_OK;
+}
+
+extern "C" int gala_set_profiling(gala_ctx *c, int enabled)
+{
+    if (!c) return GALA_EINVAL;
+    c->timer.on = enabled != 0;
+    c->timer.n = 0;
+    return GALA_OK;
+}
+
+extern "C" int gala_get_phase_times(gala_ctx *c, char *names, size_t names_cap, float *ms, int cap, int *n_out)
+{
+    if (!c || !names || !ms || !n_out || names_cap == 0) return fail(c, GALA_EINVAL, "null argument");
+    HIP_OK(c, hipStreamSynchronize(c->stream));
+    names[0] = 0;
+    int n = 0;
+    size_t used = 0;
+    for (int i = 1; i < c->timer.n && n < cap; ++i) {
+        float t = 0.f;
+        HIP_OK(c, hipEventElapsedTime(&t, c->timer.ev[i - 1], c->timer.ev[i]));
+        const size_t len = strlen(c->timer.names[i]);
+        if (used + len + 2 > names_cap) break;
+        memcpy(names + used, c->timer.names[i], len);
+        used += len;
+        names[used++] = ';';
+        names[used] = 0;
+        ms[n++] = t;
+    }
+    *n_out = n;
+    return GALA_OK;
+}

@@ -1,0 +1,142 @@
+// Internal declarations shared by the host side and the kernel files of libgala.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include <vector>
+
+namespace gala {
+
+// Fixed geometry of the network (App. C.2 of the paper: three convolutions, one hidden
+// layer, two linear heads) on 4 x 84 x 84 byte frames.
+constexpr int C0 = 4, H0 = 84, W0 = 84, FRAME = C0 * H0 * W0;            // 28224 bytes
+constexpr int C1 = 32, H1 = 20, W1 = 20, K1 = 8, S1 = 4, P1 = H1 * W1;    // conv1 out
+constexpr int C2 = 64, H2 = 9, W2 = 9, K2 = 4, S2 = 2, P2 = H2 * W2;      // conv2 out
+constexpr int C3 = 64, H3 = 7, W3 = 7, K3 = 3, S3 = 1, P3 = H3 * W3;      // conv3 out
+constexpr int FLAT = C3 * P3;                                            // 3136
+constexpr int FC = 512;
+constexpr int A1SZ = P1 * C1, A2SZ = P2 * C2, A3SZ = FLAT;                // floats per frame
+constexpr int KW1 = C0 * K1 * K1, KW2 = K2 * K2 * C1, KW3 = K3 * K3 * C2; // 256, 512, 576
+
+// Offsets (in floats) of every tensor inside one agent's slice of a parameter-shaped
+// arena (parameters, gradients, RMSprop state and history all use the same map).
+// Internal orderings, chosen for the kernels that read them:
+//   w1  [k = (c, kh, kw)][o]          256 x 32
+//   w2  [k = (kh, kw, c)][o]          512 x 64
+//   w3  [k = (kh, kw, c)][o]          576 x 64
+//   fcw [j][k = (h, w, c)]            512 x 3136   (activations are channels-last)
+//   piw [a][j], vw [j]
+struct Layout {
+    int n_actions;
+    long w1, b1, w2, b2, w3, b3, fcw, fcb, piw, pib, vw, vb;
+    long d;       // canonical parameter count
+    long d_pad;   // slice stride, multiple of 256 floats; the tail stays zero
+};
+
+inline Layout make_layout(int n_actions)
+{
+    Layout L{};
+    L.n_actions = n_actions;
+    long off = 0;
+    auto take = [&](long n) { long o = off; off += (n + 63) / 64 * 64; return o; };
+    L.w1 = take((long)KW1 * C1); L.b1 = take(C1);
+    L.w2 = take((long)KW2 * C2); L.b2 = take(C2);
+    L.w3 = take((long)KW3 * C3); L.b3 = take(C3);
+    L.fcw = take((long)FC * FLAT); L.fcb = take(FC);
+    L.piw = take((long)n_actions * FC); L.pib = take(n_actions);
+    L.vw = take(FC); L.vb = take(1);
+    L.d_pad = (off + 255) / 256 * 256;
+    L.d = (long)KW1 * C1 + C1 + (long)KW2 * C2 + C2 + (long)KW3 * C3 + C3 + (long)FC * FLAT + FC +
+          (long)n_actions * FC + n_actions + FC + 1;
+    return L;
+}
+
+// One tensor of the canonical parameter vector viewed as a 4-d row-major array, with
+// the strides of the same element inside the internal slice.
+struct Segment {
+    long canon_off, intern_off;
+    int dim[4];
+    long stride[4];
+    long count;
+};
+constexpr int N_SEGMENTS = 12;
+struct SegmentTable { Segment s[N_SEGMENTS]; };
+SegmentTable make_segments(const Layout &L);
+
+struct HParams {
+    int T, B;
+    float gamma, vf_coef, ent_coef, lr, rms_alpha, rms_eps, max_grad_norm;
+};
+
+// Device buffers of one context.  M = T*B rollout frames, F = M + B frames incl. bootstrap.
+struct Buffers {
+    float *x[2];      // [N][d_pad] parameters, ping-pong for the mixing step
+    float *g;         // [N][d_pad] gradients
+    float *v;         // [N][d_pad] RMSprop second moments
+    float *hist;      // [tau+1][N][d_pad] broadcast history (tau > 0 only)
+    float *a1, *a2, *a3, *h;          // [N][F][..] activations, channels-last
+    float *logits, *values;           // [N][M][A], [N][F]
+    float *ret, *adv;                 // [N][M]
+    float *dlogits, *dvalues;         // [N][M][A], [N][M]
+    float *dzh, *dz3, *dz2, *dz1;     // [N][M][..] pre-activation gradients
+    float *ws;                        // split-K partial sums
+    float *norm_part;                 // [N][NORM_BLOCKS]
+    float *stats;                     // [N][5]
+    float *cons_part;                 // [N][CONS_CHUNKS] + 2 results
+    int32_t *peer, *delay;            // [phases][N][max_in]
+    float *weight;                    // [phases][N][max_in+1]
+};
+
+constexpr int NORM_BLOCKS = 64;
+
+// Optional per-phase timing with HIP events on the context's stream (diagnostic).
+struct PhaseTimer {
+    bool on = false;
+    hipStream_t stream = nullptr;
+    std::vector<hipEvent_t> ev;
+    std::vector<const char *> names;
+    int n = 0;
+    void begin() { n = 0; mark("start"); }
+    void mark(const char *name)
+    {
+        if (!on) return;
+        if (n >= (int)ev.size()) {
+            hipEvent_t e;
+            if (hipEventCreate(&e) != hipSuccess) return;
+            ev.push_back(e);
+            names.push_back(name);
+        }
+        names[n] = name;
+        (void)hipEventRecord(ev[n], stream);
+        ++n;
+    }
+};
+
+// ---- launchers (each enqueues on `s` and returns hipGetLastError()) ---------------------
+struct NetArgs {
+    int N, M, F, Bn;              // agents, rollout frames, all frames, bootstrap frames
+    Layout L;
+    const float *x;              // current parameters
+    Buffers b;
+    const uint8_t *obs, *boot;
+    int cu_count;
+};
+
+hipError_t launch_forward(const NetArgs &a, hipStream_t s, PhaseTimer *pt);
+hipError_t launch_loss(const NetArgs &a, const HParams &hp, const int32_t *actions, const float *rewards,
+                       const uint8_t *dones, hipStream_t s);
+hipError_t launch_backward(const NetArgs &a, hipStream_t s, PhaseTimer *pt);
+size_t workspace_floats(int N, int M, int F);
+
+hipError_t launch_optimizer(int N, const Layout &L, const HParams &hp, float *x, float *v, const float *g,
+                            float *norm_part, float *stats, hipStream_t s, PhaseTimer *pt);
+hipError_t launch_publish(int N, const Layout &L, const float *x, float *hist_slot, hipStream_t s);
+hipError_t launch_mix(int N, const Layout &L, const float *x_in, float *x_out, const float *hist, int tau,
+                      long round, int phase, int max_in, const int32_t *peer, const int32_t *delay,
+                      const float *weight, hipStream_t s);
+constexpr int CONS_COLS = 1024;   // columns per workgroup of the consensus kernel
+hipError_t launch_consensus(int N, const Layout &L, const float *x, float *part, float *result, hipStream_t s);
+hipError_t launch_permute(int N, const Layout &L, const SegmentTable &tab, float *canon, float *intern,
+                          int to_internal, hipStream_t s);
+
+}  // namespace gala

@@ -1,0 +1,347 @@
+// Returns/advantages and the A2C loss with its head gradients (wavefront reductions),
+// per-agent global-norm clipping fused with RMSprop, the gossip mixing pass, the
+// distance-from-consensus reduction, and the canonical <-> internal parameter permutation.
+#include "gala_internal.h"
+
+namespace gala {
+
+static __device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+// Block-wide sum over 256 threads (4 wavefronts), result valid in every thread.
+static __device__ __forceinline__ float block_sum_256(float v, float *red)
+{
+    v = wave_sum(v);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return (red[0] + red[1]) + (red[2] + red[3]);
+}
+
+// ---- Algorithm 1, "compute returns and advantages" + loss of Eq. (1) and Eq. (4) -------------
+// One workgroup per agent.
+//   G_t = r_t + gamma (1 - done_t) G_{t+1},  G_T = V(state after the last action);  A_t = G_t - V_t
+//   loss = mean(-log pi(a_t|s_t) A_t) + c_v mean((G_t - V_t)^2) - eta mean(H_t),  G and A constants
+//   dloss/dz_k = [A (pi_k - 1[k = a]) + eta pi_k (log pi_k + H)] / M,   dloss/dV = -2 c_v (G - V) / M
+constexpr int MAX_ACTIONS = 64;
+
+__global__ __launch_bounds__(256) void loss_kernel(int T, int Bn, int A, float gamma, float vf_coef, float ent_coef,
+                                                   const float *__restrict__ logits, const float *__restrict__ values,
+                                                   const int32_t *__restrict__ actions,
+                                                   const float *__restrict__ rewards, const uint8_t *__restrict__ dones,
+                                                   float *ret, float *adv, float *dlogits, float *dvalues, float *stats)
+{
+    __shared__ float red[4];
+    const int agent = blockIdx.x;
+    const int M = T * Bn, F = M + Bn;
+    const float *V = values + (long)agent * F;
+    float *G = ret + (long)agent * M, *Ad = adv + (long)agent * M;
+    for (int b = threadIdx.x; b < Bn; b += blockDim.x) {
+        float next = V[M + b];
+        for (int t = T - 1; t >= 0; --t) {
+            const long i = (long)agent * M + t * Bn + b;
+            const float keep = dones[i] ? 0.f : 1.f;
+            next = rewards[i] + gamma * keep * next;
+            G[t * Bn + b] = next;
+            Ad[t * Bn + b] = next - V[t * Bn + b];
+        }
+    }
+    __syncthreads();
+    float pg = 0.f, td = 0.f, ent = 0.f;
+    const float inv_m = 1.0f / (float)M;
+    for (int m = threadIdx.x; m < M; m += blockDim.x) {
+        const float *z = logits + ((long)agent * M + m) * A;
+        float lp[MAX_ACTIONS];
+        float zmax = z[0];
+        for (int a = 1; a < A; ++a) zmax = fmaxf(zmax, z[a]);
+        float se = 0.f;
+        for (int a = 0; a < A; ++a) se += expf(z[a] - zmax);
+        const float lse = zmax + logf(se);
+        float H = 0.f;
+        for (int a = 0; a < A; ++a) { lp[a] = z[a] - lse; H -= expf(lp[a]) * lp[a]; }
+        const int act = actions[(long)agent * M + m];      // integer gather of the taken action
+        const float Am = Ad[m], Gm = G[m], Vm = V[m];
+        pg += -lp[act] * Am;
+        td += (Gm - Vm) * (Gm - Vm);
+        ent += H;
+        float *dz = dlogits + ((long)agent * M + m) * A;
+        for (int a = 0; a < A; ++a) {
+            const float p = expf(lp[a]);
+            dz[a] = (Am * (p - (a == act ? 1.f : 0.f)) + ent_coef * p * (lp[a] + H)) * inv_m;
+        }
+        dvalues[(long)agent * M + m] = -2.f * vf_coef * (Gm - Vm) * inv_m;
+    }
+    pg = block_sum_256(pg, red);
+    td = block_sum_256(td, red);
+    ent = block_sum_256(ent, red);
+    if (threadIdx.x == 0) {
+        stats[agent * 5 + 0] = pg * inv_m;
+        stats[agent * 5 + 1] = td * inv_m;
+        stats[agent * 5 + 2] = ent * inv_m;
+    }
+}
+
+hipError_t launch_loss(const NetArgs &a, const HParams &hp, const int32_t *actions, const float *rewards,
+                       const uint8_t *dones, hipStream_t s)
+{
+    hipLaunchKernelGGL(loss_kernel, dim3(a.N), dim3(256), 0, s, hp.T, hp.B, a.L.n_actions, hp.gamma, hp.vf_coef,
+                       hp.ent_coef, a.b.logits, a.b.values, actions, rewards, dones, a.b.ret, a.b.adv,
+                       a.b.dlogits, a.b.dvalues, a.b.stats);
+    return hipGetLastError();
+}
+
+// ---- global gradient norm per agent (Table 2: clip global gradient norm) -------------------------
+__global__ __launch_bounds__(256) void sumsq_kernel(const float *__restrict__ g, long d_pad, float *part)
+{
+    __shared__ float red[4];
+    const int agent = blockIdx.y;
+    const float4 *p = reinterpret_cast<const float4 *>(g + agent * d_pad);
+    const long n4 = d_pad / 4;
+    float acc = 0.f;
+    for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < n4; i += (long)gridDim.x * 256) {
+        const float4 v = p[i];
+        acc += (v.x * v.x + v.y * v.y) + (v.z * v.z + v.w * v.w);
+    }
+    acc = block_sum_256(acc, red);
+    if (threadIdx.x == 0) part[agent * NORM_BLOCKS + blockIdx.x] = acc;
+}
+
+// ---- clip + RMSprop (Table 2; momentum 0) ---------------------------------------------------------------
+//   c = min(1, max_norm / (||g|| + 1e-6));  g <- c g;  v <- a v + (1 - a) g^2;  x <- x - lr g / (sqrt(v) + eps)
+__global__ __launch_bounds__(256) void rmsprop_kernel(float *x, float *v, const float *__restrict__ g, long d_pad,
+                                                      const float *__restrict__ part, float max_norm, float lr,
+                                                      float alpha, float eps, float *stats)
+{
+    const int agent = blockIdx.y;
+    float ss = 0.f;
+    if (threadIdx.x < 64) {
+        ss = part[agent * NORM_BLOCKS + threadIdx.x];
+        ss = wave_sum(ss);
+    }
+    __shared__ float sh;
+    if (threadIdx.x == 0) sh = ss;
+    __syncthreads();
+    const float norm = sqrtf(sh);
+    const float c = fminf(1.f, max_norm / (norm + 1e-6f));
+    if (blockIdx.x == 0 && threadIdx.x == 0) { stats[agent * 5 + 3] = norm; stats[agent * 5 + 4] = c; }
+    const long n4 = d_pad / 4;
+    float4 *x4 = reinterpret_cast<float4 *>(x + agent * d_pad);
+    float4 *v4 = reinterpret_cast<float4 *>(v + agent * d_pad);
+    const float4 *g4 = reinterpret_cast<const float4 *>(g + agent * d_pad);
+    const float om = 1.f - alpha;
+    for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < n4; i += (long)gridDim.x * 256) {
+        float4 gg = g4[i], vv = v4[i], xx = x4[i];
+        gg.x *= c; gg.y *= c; gg.z *= c; gg.w *= c;
+        vv.x = alpha * vv.x + om * gg.x * gg.x; vv.y = alpha * vv.y + om * gg.y * gg.y;
+        vv.z = alpha * vv.z + om * gg.z * gg.z; vv.w = alpha * vv.w + om * gg.w * gg.w;
+        xx.x -= lr * gg.x / (sqrtf(vv.x) + eps); xx.y -= lr * gg.y / (sqrtf(vv.y) + eps);
+        xx.z -= lr * gg.z / (sqrtf(vv.z) + eps); xx.w -= lr * gg.w / (sqrtf(vv.w) + eps);
+        v4[i] = vv; x4[i] = xx;
+    }
+}
+
+hipError_t launch_optimizer(int N, const Layout &L, const HParams &hp, float *x, float *v, const float *g,
+                            float *norm_part, float *stats, hipStream_t s, PhaseTimer *pt)
+{
+    hipLaunchKernelGGL(sumsq_kernel, dim3(NORM_BLOCKS, N), dim3(256), 0, s, g, L.d_pad, norm_part);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    pt->mark("grad_norm");
+    const int blocks = 128;
+    hipLaunchKernelGGL(rmsprop_kernel, dim3(blocks, N), dim3(256), 0, s, x, v, g, L.d_pad, norm_part,
+                       hp.max_grad_norm, hp.lr, hp.rms_alpha, hp.rms_eps, stats);
+    pt->mark("clip_rmsprop");
+    return hipGetLastError();
+}
+
+// ---- gossip ------------------------------------------------------------------------------------------------
+// Broadcast (Algorithm 1): keep the post-update parameters of this round for later readers.
+__global__ __launch_bounds__(256) void copy_kernel(const float4 *__restrict__ src, float4 *dst, long n4)
+{
+    for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < n4; i += (long)gridDim.x * 256) dst[i] = src[i];
+}
+
+hipError_t launch_publish(int N, const Layout &L, const float *x, float *hist_slot, hipStream_t s)
+{
+    const long n4 = (long)N * L.d_pad / 4;
+    const int blocks = (int)((n4 + 256 * 8 - 1) / (256 * 8));
+    hipLaunchKernelGGL(copy_kernel, dim3(blocks), dim3(256), 0, s, reinterpret_cast<const float4 *>(x),
+                       reinterpret_cast<float4 *>(hist_slot), n4);
+    return hipGetLastError();
+}
+
+// Mixing step x_i <- p_ii x_i + sum_j p_ij x_j^(round - delay_ij)  (Sec. 2; Eq. (6)).  Reads
+// the pre-mix arena (and the broadcast history for delayed messages), writes the other arena,
+// so every agent mixes the same snapshot.  If a delayed message was never sent the agent
+// keeps its own parameters (Algorithm 1: average only when every in-peer's message is there).
+constexpr int MIX_MAX_IN = 8;
+
+__global__ __launch_bounds__(256) void mix_kernel(const float *__restrict__ x_in, float *x_out,
+                                                  const float *__restrict__ hist, int N, long d_pad, int tau,
+                                                  long round, int phase, int max_in,
+                                                  const int32_t *__restrict__ peer, const int32_t *__restrict__ delay,
+                                                  const float *__restrict__ weight)
+{
+    const int i = blockIdx.y;
+    const long tab = ((long)phase * N + i) * max_in;
+    const float *src[MIX_MAX_IN];
+    float w[MIX_MAX_IN];
+    int n_in = 0;
+    bool complete = true;
+    for (int s = 0; s < max_in; ++s) {
+        const int j = peer[tab + s];
+        if (j < 0) continue;
+        const int dl = delay[tab + s];
+        const long sent = round - dl;
+        if (sent < 0) { complete = false; continue; }
+        src[n_in] = (dl == 0 ? x_in : hist + (sent % (tau + 1)) * (long)N * d_pad) + (long)j * d_pad;
+        w[n_in] = weight[((long)phase * N + i) * (max_in + 1) + 1 + s];
+        ++n_in;
+    }
+    const float w_self = complete ? weight[((long)phase * N + i) * (max_in + 1)] : 1.f;
+    if (!complete) n_in = 0;
+    const float4 *xi = reinterpret_cast<const float4 *>(x_in + (long)i * d_pad);
+    float4 *xo = reinterpret_cast<float4 *>(x_out + (long)i * d_pad);
+    const long n4 = d_pad / 4;
+    for (long e = (long)blockIdx.x * 256 + threadIdx.x; e < n4; e += (long)gridDim.x * 256) {
+        float4 a = xi[e];
+        a.x *= w_self; a.y *= w_self; a.z *= w_self; a.w *= w_self;
+        for (int s = 0; s < n_in; ++s) {
+            const float4 m = reinterpret_cast<const float4 *>(src[s])[e];
+            a.x += w[s] * m.x; a.y += w[s] * m.y; a.z += w[s] * m.z; a.w += w[s] * m.w;
+        }
+        xo[e] = a;
+    }
+}
+
+hipError_t launch_mix(int N, const Layout &L, const float *x_in, float *x_out, const float *hist, int tau,
+                      long round, int phase, int max_in, const int32_t *peer, const int32_t *delay,
+                      const float *weight, hipStream_t s)
+{
+    hipLaunchKernelGGL(mix_kernel, dim3(128, N), dim3(256), 0, s, x_in, x_out, hist, N, L.d_pad, tau, round,
+                       phase, max_in, peer, delay, weight);
+    return hipGetLastError();
+}
+
+// ---- distance from consensus (Prop. 1) --------------------------------------------------------------------
+// Each workgroup owns CONS_COLS element columns: the mean over agents is formed in registers,
+// then every agent's squared deviation over those columns is block-reduced into
+// part[agent][chunk].  The second pass over the agents hits L2.
+__global__ __launch_bounds__(256) void consensus_kernel(const float *__restrict__ x, int N, long d_pad, int chunks,
+                                                        float *part)
+{
+    __shared__ float red[4];
+    const int chunk = blockIdx.x;
+    const long e = ((long)chunk * 256 + threadIdx.x) * 4;
+    const bool in = e < d_pad;
+    float4 mean = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (in)
+        for (int i = 0; i < N; ++i) {
+            const float4 v = *reinterpret_cast<const float4 *>(x + (long)i * d_pad + e);
+            mean.x += v.x; mean.y += v.y; mean.z += v.z; mean.w += v.w;
+        }
+    const float inv = 1.f / (float)N;
+    mean.x *= inv; mean.y *= inv; mean.z *= inv; mean.w *= inv;
+    for (int i = 0; i < N; ++i) {
+        float ss = 0.f;
+        if (in) {
+            const float4 v = *reinterpret_cast<const float4 *>(x + (long)i * d_pad + e);
+            const float a = v.x - mean.x, b = v.y - mean.y, c = v.z - mean.z, d = v.w - mean.w;
+            ss = (a * a + b * b) + (c * c + d * d);
+        }
+        ss = block_sum_256(ss, red);
+        if (threadIdx.x == 0) part[(long)i * chunks + chunk] = ss;
+    }
+}
+
+__global__ __launch_bounds__(256) void consensus_final_kernel(const float *__restrict__ part, int N, int chunks,
+                                                              float *result)
+{
+    __shared__ float red[4];
+    float mx = 0.f, tot = 0.f;
+    for (int i = 0; i < N; ++i) {
+        float acc = 0.f;
+        for (int c = threadIdx.x; c < chunks; c += 256) acc += part[(long)i * chunks + c];
+        acc = block_sum_256(acc, red);
+        mx = fmaxf(mx, acc);
+        tot += acc;
+    }
+    if (threadIdx.x == 0) { result[0] = sqrtf(mx); result[1] = sqrtf(tot); }
+}
+
+hipError_t launch_consensus(int N, const Layout &L, const float *x, float *part, float *result, hipStream_t s)
+{
+    const int chunks = (int)((L.d_pad + CONS_COLS - 1) / CONS_COLS);
+    hipLaunchKernelGGL(consensus_kernel, dim3(chunks), dim3(256), 0, s, x, N, L.d_pad, chunks, part);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(consensus_final_kernel, dim3(1), dim3(256), 0, s, part, N, chunks, result);
+    return hipGetLastError();
+}
+
+// ---- canonical <-> internal order --------------------------------------------------------------------------
+SegmentTable make_segments(const Layout &L)
+{
+    SegmentTable t{};
+    long canon = 0;
+    int n = 0;
+    auto add = [&](long intern, int d0, int d1, int d2, int d3, long s0, long s1, long s2, long s3) {
+        Segment &g = t.s[n++];
+        g.canon_off = canon; g.intern_off = intern;
+        g.dim[0] = d0; g.dim[1] = d1; g.dim[2] = d2; g.dim[3] = d3;
+        g.stride[0] = s0; g.stride[1] = s1; g.stride[2] = s2; g.stride[3] = s3;
+        g.count = (long)d0 * d1 * d2 * d3;
+        canon += g.count;
+    };
+    // canonical OIHW -> w1 [(c, kh, kw)][o]
+    add(L.w1, C1, C0, K1, K1, 1, (long)K1 * K1 * C1, (long)K1 * C1, C1);
+    add(L.b1, 1, 1, 1, C1, 0, 0, 0, 1);
+    // canonical OIHW -> w2 [(kh, kw, c)][o]
+    add(L.w2, C2, C1, K2, K2, 1, C2, (long)K2 * C1 * C2, (long)C1 * C2);
+    add(L.b2, 1, 1, 1, C2, 0, 0, 0, 1);
+    add(L.w3, C3, C2, K3, K3, 1, C3, (long)K3 * C2 * C3, (long)C2 * C3);
+    add(L.b3, 1, 1, 1, C3, 0, 0, 0, 1);
+    // canonical [j][c][hw] -> fcw [j][hw][c]
+    add(L.fcw, FC, C3, P3, 1, FLAT, 1, C3, 0);
+    add(L.fcb, 1, 1, 1, FC, 0, 0, 0, 1);
+    add(L.piw, 1, 1, L.n_actions, FC, 0, 0, FC, 1);
+    add(L.pib, 1, 1, 1, L.n_actions, 0, 0, 0, 1);
+    add(L.vw, 1, 1, 1, FC, 0, 0, 0, 1);
+    add(L.vb, 1, 1, 1, 1, 0, 0, 0, 1);
+    return t;
+}
+
+__global__ __launch_bounds__(256) void permute_kernel(SegmentTable tab, long d, long d_pad, float *canon,
+                                                      float *intern, int to_internal)
+{
+    const int agent = blockIdx.y;
+    const long c = (long)blockIdx.x * 256 + threadIdx.x;
+    if (c >= d) return;
+    int si = 0;
+#pragma unroll
+    for (int k = 1; k < N_SEGMENTS; ++k) if (c >= tab.s[k].canon_off) si = k;
+    const Segment &g = tab.s[si];
+    long r = c - g.canon_off;
+    const int i3 = (int)(r % g.dim[3]); r /= g.dim[3];
+    const int i2 = (int)(r % g.dim[2]); r /= g.dim[2];
+    const int i1 = (int)(r % g.dim[1]); r /= g.dim[1];
+    const int i0 = (int)r;
+    const long ii = g.intern_off + i0 * g.stride[0] + i1 * g.stride[1] + i2 * g.stride[2] + i3 * g.stride[3];
+    if (to_internal) intern[agent * d_pad + ii] = canon[agent * d + c];
+    else canon[agent * d + c] = intern[agent * d_pad + ii];
+}
+
+hipError_t launch_permute(int N, const Layout &L, const SegmentTable &tab, float *canon, float *intern,
+                          int to_internal, hipStream_t s)
+{
+    const int blocks = (int)((L.d + 255) / 256);
+    hipLaunchKernelGGL(permute_kernel, dim3(blocks, N), dim3(256), 0, s, tab, L.d, L.d_pad, canon, intern,
+                       to_internal);
+    return hipGetLastError();
+}
+
+}  // namespace gala

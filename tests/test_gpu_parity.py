@@ -1,0 +1,190 @@
+"""GPU parity: the HIP path through the C ABI against the CPU oracle on identical seeded
+inputs.  Integer work (action gather, peer and delay tables) bit-exact; floating point
+within the norm-wise tolerance of parity_util.RTOL per tensor."""
+import os
+
+import numpy as np
+import pytest
+
+import gala_synth as gs
+from oracle import gala_oracle as orc
+from parity_util import RTOL, compare_learner_step, compare_params, rel_err, step_both, upload
+
+pytestmark = pytest.mark.gpu
+
+HP = gs.HPARAMS
+
+
+def _make(cfg_id, shared=False, rounds_seed=None, **over):
+    from paper_1906_04585_amd import Gala
+    cfg = dict(gs.CONFIGS[cfg_id], **over)
+    net = gs.make_net(cfg["n_actions"])
+    N, T, B = cfg["n_agents"], cfg["T"], cfg["B"]
+    seed = 7 + cfg_id
+    gpu = Gala(N, cfg["n_actions"], T, B, HP, cfg["topology"], max_delay=cfg["max_delay"], delay_seed=seed)
+    om = orc.OracleGala(net, N, T, B, HP, cfg["topology"], max_delay=cfg["max_delay"], delay_seed=seed)
+    X0 = gs.init_params(net, N, seed=gs.BASE_SEED + cfg_id, shared=shared, bias_scale=0.05)
+    gpu.set_params(X0)
+    om.set_params(X0)
+    return cfg, net, gpu, om, X0
+
+
+def test_set_get_roundtrip_is_bit_exact():
+    cfg, net, gpu, om, X0 = _make(1)
+    np.testing.assert_array_equal(gpu.get_params(), X0)
+    V0 = np.abs(gs.init_params(net, cfg["n_agents"], seed=3)) * 1e-3
+    gpu.set_opt_state(V0)
+    np.testing.assert_array_equal(gpu.get_opt_state(), V0)
+    import torch
+    xd = torch.from_numpy(X0[::-1].copy()).cuda()
+    gpu.set_params(xd)
+    out = torch.empty_like(xd)
+    gpu.get_params(out)
+    assert torch.equal(out, xd)
+
+
+def test_config1_forward_outputs_and_returns():
+    cfg, net, gpu, om, X0 = _make(1)
+    N, T, B = cfg["n_agents"], cfg["T"], cfg["B"]
+    ro = gs.rollout(net, N, T, B, gs.round_seed(1, 0))
+    step_both(gpu, om, ro)
+    out = gpu.get_outputs()
+    for i in range(N):
+        g, terms, ex = orc.agent_gradient(net, T, B, HP, X0[i], ro["obs"][i], ro["actions"][i],
+                                          ro["rewards"][i], ro["dones"][i], ro["boot_obs"][i], extras=True)
+        assert rel_err(out["logits"][i], ex["logits"]) <= RTOL
+        assert rel_err(out["values"][i], ex["values"]) <= RTOL
+        assert rel_err(out["returns"][i], ex["G"]) <= RTOL
+        assert np.abs(out["advantages"][i] - ex["Adv"]).max() <= RTOL * np.abs(ex["G"]).max()
+
+
+def test_config1_one_round_ring():
+    cfg, net, gpu, om, X0 = _make(1)
+    ro = gs.rollout(net, cfg["n_agents"], cfg["T"], cfg["B"], gs.round_seed(1, 0))
+    step_both(gpu, om, ro)
+    worst = compare_learner_step(gpu, om, net, "cfg1")
+    print("worst per-tensor gradient errors:", {k: f"{v:.2e}" for k, v in worst.items()})
+    gpu.gossip(0)
+    om.gossip(0)
+    x = compare_params(gpu, om, net, "cfg1 after gossip")
+    # two agents on a ring: one round is the exact average, both rows identical bits
+    np.testing.assert_array_equal(x[0], x[1])
+    mx, fr = gpu.consensus_distance()
+    assert mx == 0.0 and fr == 0.0
+
+
+def test_action_gather_is_exact():
+    """With zero advantage weight removed (ent_coef = 0) the policy gradient row of a
+    sample is A_m (pi - onehot(a_m)): flipping one action moves exactly that sample's
+    contribution; compare against the oracle under both action sets."""
+    from paper_1906_04585_amd import Gala
+    net = gs.make_net(6)
+    N, T, B = 2, 5, 4
+    hp = dict(HP, ent_coef=0.0)
+    X0 = gs.init_params(net, N, seed=99, bias_scale=0.05)
+    ro = gs.rollout(net, N, T, B, 1234)
+    for flip in (False, True):
+        r2 = dict(ro)
+        if flip:
+            a = ro["actions"].copy()
+            a[1, 3, 2] = (a[1, 3, 2] + 1) % 6
+            r2["actions"] = a
+        gpu = Gala(N, 6, T, B, hp, "ring")
+        om = orc.OracleGala(net, N, T, B, hp, "ring")
+        gpu.set_params(X0)
+        om.set_params(X0)
+        step_both(gpu, om, r2)
+        compare_learner_step(gpu, om, net, f"flip={flip}")
+
+
+@pytest.mark.parametrize("topology,N", [("ring", 2), ("ring", 4), ("exp", 4), ("exp", 8), ("exp", 32)])
+def test_peer_tables_bit_exact(topology, N):
+    from paper_1906_04585_amd import Gala
+    gpu = Gala(N, 6, 1, 1, HP, topology, max_delay=2, delay_seed=4242)
+    for r in range(12):
+        peer, delay = gpu.get_peer_table(r)
+        opeer, odelay = orc.peer_table(topology, N, r, 2, 4242)
+        np.testing.assert_array_equal(peer[:, 0], opeer)
+        np.testing.assert_array_equal(delay[:, 0], odelay)
+
+
+@pytest.mark.parametrize("topology,N,tau", [("ring", 4, 0), ("exp", 8, 0), ("exp", 32, 0), ("exp", 8, 2), ("ring", 4, 1)])
+def test_gossip_only_matches_oracle(topology, N, tau):
+    from paper_1906_04585_amd import Gala
+    net = gs.make_net(6)
+    gpu = Gala(N, 6, 1, 1, HP, topology, max_delay=tau, delay_seed=11)
+    om = orc.OracleGala(net, N, 1, 1, HP, topology, max_delay=tau, delay_seed=11)
+    X0 = gs.init_params(net, N, seed=5, bias_scale=0.1)
+    gpu.set_params(X0)
+    om.set_params(X0)
+    for r in range(7):
+        if tau:   # perturb between rounds so that stale and fresh messages differ
+            X = gpu.get_params()
+            X = (X * (1.0 + 0.01 * (r + 1))).astype(np.float32)
+            gpu.set_params(X)
+            om.set_params(X)
+        gpu.gossip(r)
+        om.gossip(r)
+        x = gpu.get_params()
+        assert np.abs(x - om.X).max() <= 2.0 ** -22 * np.abs(om.X).max(), f"round {r}"
+        mx, fr = gpu.consensus_distance()
+        omx, ofr = om.consensus_distance()
+        # fp32 mixing leaves rounding noise of a few ulp of the parameters themselves
+        floor = 4e-7 * float(np.linalg.norm(om.X))
+        assert abs(mx - omx) <= 1e-4 * omx + floor and abs(fr - ofr) <= 1e-4 * ofr + floor
+
+
+def test_exponential_graph_exact_average_after_log2_rounds():
+    from paper_1906_04585_amd import Gala
+    N = 8
+    gpu = Gala(N, 6, 1, 1, HP, "exp")
+    X0 = gs.init_params(gs.make_net(6), N, seed=6, bias_scale=0.1)
+    gpu.set_params(X0)
+    for r in range(3):
+        gpu.gossip(r)
+    x = gpu.get_params()
+    mean = X0.astype(np.float64).mean(0)
+    assert np.abs(x - mean).max() <= 4e-7 * np.abs(mean).max() + 1e-9
+    mx, _ = gpu.consensus_distance()
+    assert mx <= 1e-4 * np.linalg.norm(mean)
+
+
+def test_config2_lockstep_rounds():
+    """Four agents, exponential graph, 18 actions, 5 x 16 rollouts: every round is checked
+    against the oracle restarted from the GPU's own state (lock-step).  GALA_TEST_ROUNDS
+    sets the number of rounds (100 for the full configuration)."""
+    rounds = int(os.environ.get("GALA_TEST_ROUNDS", "6"))
+    cfg, net, gpu, om, X0 = _make(2)
+    N, T, B = cfg["n_agents"], cfg["T"], cfg["B"]
+    for r in range(rounds):
+        om.set_params(gpu.get_params())
+        om.set_opt_state(gpu.get_opt_state())
+        ro = gs.rollout(net, N, T, B, gs.round_seed(2, r))
+        step_both(gpu, om, ro)
+        compare_learner_step(gpu, om, net, f"cfg2 round {r}")
+        om.set_params(gpu.get_params())
+        gpu.gossip(r)
+        om.gossip(r)
+        compare_params(gpu, om, net, f"cfg2 gossip {r}")
+
+
+def test_config3_delayed_gossip_lockstep():
+    """Eight agents with per-edge message delays of 0..2 rounds read from the broadcast
+    history.  GALA_TEST_ROUNDS_DELAY sets the number of rounds (200 for the full run)."""
+    rounds = int(os.environ.get("GALA_TEST_ROUNDS_DELAY", "7"))
+    cfg, net, gpu, om, X0 = _make(3)
+    N, T, B = cfg["n_agents"], cfg["T"], cfg["B"]
+    seen = set()
+    for r in range(rounds):
+        om.set_params(gpu.get_params())
+        om.set_opt_state(gpu.get_opt_state())
+        ro = gs.rollout(net, N, T, B, gs.round_seed(3, r))
+        step_both(gpu, om, ro)
+        compare_learner_step(gpu, om, net, f"cfg3 round {r}")
+        # the oracle's message history must hold what the GPU actually broadcast
+        om.set_params(gpu.get_params())
+        gpu.gossip(r)
+        om.gossip(r)
+        compare_params(gpu, om, net, f"cfg3 gossip {r}")
+        seen |= set(gpu.get_peer_table(r)[1][:, 0].tolist())
+    assert seen == {0, 1, 2}

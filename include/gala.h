@@ -141,6 +141,12 @@ int gala_consensus_distance(gala_ctx *ctx, float *max_dist, float *frob);
  * (max_in = 1 for ring and exponential graphs). */
 int gala_get_peer_table(gala_ctx *ctx, int64_t round, int32_t *peer, int32_t *delay);
 
+/* Activations of the last learner step, host float, channels-last as the kernels keep
+ * them: layer 1 -> [N][F][20][20][32], 2 -> [N][F][9][9][64], 3 -> [N][F][7][7][64],
+ * 4 -> hidden [N][F][512]; F = T*B + B frames (rollout states, then bootstrap states),
+ * values after ReLU. */
+int gala_get_activations(gala_ctx *ctx, int layer, float *dst_host);
+
 /* Per-phase timing (diagnostic).  While enabled, gala_learner_step and gala_gossip record a
  * HIP event on the context's stream after every phase (conv1_fwd, ..., clip_rmsprop,
  * gossip_mix).  gala_get_phase_times synchronises and returns the elapsed milliseconds

@@ -100,9 +100,10 @@ long orc_act_size(const orc_net *n) { orc_shape s; shape_of(n, &s); return s.act
 /* ---- network, one frame ------------------------------------------------- */
 
 /* Forward pass of one frame.  rec receives: scaled input, every conv output
- * (after ReLU), hidden (after ReLU).  logits[A], *value. */
+ * (after ReLU), hidden (after ReLU).  pre (may be NULL) receives, at the same
+ * offsets, the values before each ReLU.  logits[A], *value. */
 static void forward_frame(const orc_net *n, const orc_shape *s, const double *x,
-                          const uint8_t *obs, double *rec, double *logits, double *value)
+                          const uint8_t *obs, double *rec, double *pre, double *logits, double *value)
 {
     for (long i = 0; i < s->in_size; ++i) rec[i] = (double)obs[i] / 255.0;
 
@@ -123,6 +124,7 @@ static void forward_frame(const orc_net *n, const orc_shape *s, const double *x,
                                 acc += w[(((long)o * C + c) * K + ky) * K + kx] *
                                        in[((long)c * H + (oy * S + ky)) * W + (ox * S + kx)];
                     out[((long)o * OH + oy) * OW + ox] = acc > 0.0 ? acc : 0.0;
+                    if (pre) pre[s->act_off[l + 1] + ((long)o * OH + oy) * OW + ox] = acc;
                 }
         in = out;
         (void)H;
@@ -135,6 +137,7 @@ static void forward_frame(const orc_net *n, const orc_shape *s, const double *x,
         double acc = fb[j];
         for (long k = 0; k < s->flat; ++k) acc += fw[(long)j * s->flat + k] * in[k];
         hid[j] = acc > 0.0 ? acc : 0.0;
+        if (pre) pre[s->act_off[L + 1] + j] = acc;
     }
     const double *pw = x + s->piw_off, *pb = x + s->pib_off;
     for (int a = 0; a < n->n_actions; ++a) {
@@ -147,12 +150,24 @@ static void forward_frame(const orc_net *n, const orc_shape *s, const double *x,
     *value = acc;
 }
 
+/* Whether a ReLU unit passes gradient.  The unit's own sign decides, unless the
+ * caller marks it (gate 1 = pass, 2 = block).  Tests use the marks only for units
+ * whose pre-activation lies within single-precision rounding of zero, where the
+ * derivative of max(z, 0) is decided by rounding and both answers are valid. */
+static int relu_open(double act, const uint8_t *gate, long i)
+{
+    if (gate && gate[i] == 1) return 1;
+    if (gate && gate[i] == 2) return 0;
+    return act > 0.0;
+}
+
 /* Reverse pass of one frame down to the pre-activation gradients of every
  * layer.  dz receives, at the same offsets as the activations in rec, the loss
  * gradient w.r.t. the value *before* each ReLU (conv outputs and hidden).
- * The input needs no gradient. */
+ * The input needs no gradient.  gate: NULL or act_size bytes, see relu_open. */
 static void backward_frame(const orc_net *n, const orc_shape *s, const double *x,
-                           const double *rec, const double *dlogits, double dvalue, double *dz)
+                           const double *rec, const double *dlogits, double dvalue, double *dz,
+                           const uint8_t *gate)
 {
     const int L = n->n_conv;
     const double *hid = rec + s->act_off[L + 1];
@@ -161,7 +176,7 @@ static void backward_frame(const orc_net *n, const orc_shape *s, const double *x
     for (int j = 0; j < n->fc; ++j) {
         double g = x[s->vw_off + j] * dvalue;
         for (int a = 0; a < n->n_actions; ++a) g += pw[(long)a * n->fc + j] * dlogits[a];
-        dzh[j] = hid[j] > 0.0 ? g : 0.0;
+        dzh[j] = relu_open(hid[j], gate, s->act_off[L + 1] + j) ? g : 0.0;
     }
     /* hidden layer -> flattened last conv output */
     {
@@ -171,7 +186,7 @@ static void backward_frame(const orc_net *n, const orc_shape *s, const double *x
         for (long k = 0; k < s->flat; ++k) {
             double g = 0.0;
             for (int j = 0; j < n->fc; ++j) g += fw[(long)j * s->flat + k] * dzh[j];
-            dzl[k] = act[k] > 0.0 ? g : 0.0;
+            dzl[k] = relu_open(act[k], gate, s->act_off[L] + k) ? g : 0.0;
         }
     }
     /* conv l (1-based l+1) output gradient -> conv l-1 output gradient */
@@ -195,7 +210,7 @@ static void backward_frame(const orc_net *n, const orc_shape *s, const double *x
                                 din[((long)c * H + (oy * S + ky)) * W + (ox * S + kx)] +=
                                     w[(((long)o * C + c) * K + ky) * K + kx] * g;
                 }
-        for (long i = 0; i < (long)C * H * W; ++i) if (!(act[i] > 0.0)) din[i] = 0.0;
+        for (long i = 0; i < (long)C * H * W; ++i) if (!relu_open(act[i], gate, s->act_off[l] + i)) din[i] = 0.0;
     }
 }
 
@@ -278,9 +293,11 @@ static void param_gradients(const orc_net *n, const orc_shape *s, int F,
 /* ---- exported pieces ---------------------------------------------------- */
 
 /* Forward pass of F frames (obs: F consecutive C*H*W byte frames).
- * acts may be NULL; otherwise it receives F records of orc_act_size doubles. */
+ * acts may be NULL; otherwise it receives F records of orc_act_size doubles
+ * (scaled input, conv outputs after ReLU, hidden after ReLU).  pre may be NULL;
+ * otherwise it receives the values before each ReLU at the same offsets. */
 void orc_forward(const orc_net *n, const double *x, const uint8_t *obs, int F,
-                 double *logits, double *values, double *acts)
+                 double *logits, double *values, double *acts, double *pre)
 {
     orc_shape s; shape_of(n, &s);
     double *own = NULL;
@@ -288,7 +305,7 @@ void orc_forward(const orc_net *n, const double *x, const uint8_t *obs, int F,
     #pragma omp parallel for schedule(dynamic, 1)
     for (int f = 0; f < F; ++f)
         forward_frame(n, &s, x, obs + (long)f * s.in_size, acts + (long)f * s.act_size,
-                      logits + (long)f * n->n_actions, values + f);
+                      pre ? pre + (long)f * s.act_size : NULL, logits + (long)f * n->n_actions, values + f);
     free(own);
 }
 
@@ -348,12 +365,14 @@ void orc_a2c_loss(int M, int A, const double *logits, const double *values, cons
 /* Gradient of one agent's A2C loss w.r.t. all of its parameters.
  * obs [T][B][C][H][W] bytes, boot_obs [B][C][H][W], actions/rewards/dones [T][B].
  * grads[d]; terms[3] as in orc_a2c_loss.  Optional outputs (may be NULL):
- * out_G, out_Adv [T*B]; out_logits [T*B][A]; out_values [T*B + B] (rollout then bootstrap). */
+ * out_G, out_Adv [T*B]; out_logits [T*B][A]; out_values [T*B + B] (rollout then bootstrap).
+ * gate: NULL, or [T*B][orc_act_size] bytes of ReLU-derivative marks (see relu_open). */
 void orc_agent_gradient(const orc_net *n, const orc_hparams *hp, const double *x,
                         const uint8_t *obs, const int32_t *actions, const double *rewards,
                         const uint8_t *dones, const uint8_t *boot_obs,
                         double *grads, double *terms,
-                        double *out_G, double *out_Adv, double *out_logits, double *out_values)
+                        double *out_G, double *out_Adv, double *out_logits, double *out_values,
+                        const uint8_t *gate)
 {
     orc_shape s; shape_of(n, &s);
     const int M = hp->T * hp->B, Bn = hp->B, A = n->n_actions;
@@ -370,7 +389,7 @@ void orc_agent_gradient(const orc_net *n, const orc_hparams *hp, const double *x
     #pragma omp parallel for schedule(dynamic, 1)
     for (int f = 0; f < M + Bn; ++f) {
         const uint8_t *frame = f < M ? obs + (long)f * s.in_size : boot_obs + (long)(f - M) * s.in_size;
-        forward_frame(n, &s, x, frame, recs + (long)f * s.act_size, logits + (long)f * A, values + f);
+        forward_frame(n, &s, x, frame, recs + (long)f * s.act_size, NULL, logits + (long)f * A, values + f);
     }
     orc_nstep_returns(hp->T, hp->B, hp->gamma, rewards, dones, values + M, values, G, Adv);
     orc_a2c_loss(M, A, logits, values, actions, G, Adv, hp->vf_coef, hp->ent_coef, terms, dlogits, dvalues);
@@ -378,7 +397,7 @@ void orc_agent_gradient(const orc_net *n, const orc_hparams *hp, const double *x
     #pragma omp parallel for schedule(dynamic, 1)
     for (int f = 0; f < M; ++f)
         backward_frame(n, &s, x, recs + (long)f * s.act_size, dlogits + (long)f * A, dvalues[f],
-                       dzs + (long)f * s.act_size);
+                       dzs + (long)f * s.act_size, gate ? gate + (long)f * s.act_size : NULL);
     param_gradients(n, &s, M, recs, dzs, dlogits, dvalues, grads);
 
     if (out_G) memcpy(out_G, G, sizeof(double) * M);
@@ -404,7 +423,7 @@ void orc_agent_loss(const orc_net *n, const orc_hparams *hp, const double *x,
     double *G = (double *)malloc(sizeof(double) * M), *Adv = (double *)malloc(sizeof(double) * M);
     for (int f = 0; f < M + Bn; ++f) {
         const uint8_t *frame = f < M ? obs + (long)f * s.in_size : boot_obs + (long)(f - M) * s.in_size;
-        forward_frame(n, &s, x, frame, rec, logits + (long)f * A, values + f);
+        forward_frame(n, &s, x, frame, rec, NULL, logits + (long)f * A, values + f);
     }
     if (fixed_G) { memcpy(G, fixed_G, sizeof(double) * M); memcpy(Adv, fixed_Adv, sizeof(double) * M); }
     else orc_nstep_returns(hp->T, hp->B, hp->gamma, rewards, dones, values + M, values, G, Adv);
@@ -438,11 +457,12 @@ void orc_rmsprop(double *x, double *v, const double *g, long d, double lr, doubl
 /* One learner step of N independent agents (Algorithm 1: returns, then the A2C
  * optimisation step).  X, V: [N][d] parameters and RMSprop state, updated in
  * place.  grads_out [N][d] (pre-clip, may be NULL); stats [N][5] =
- * pg, td, entropy, pre-clip norm, clip scale. */
+ * pg, td, entropy, pre-clip norm, clip scale.  gates: NULL, or
+ * [N][T*B][orc_act_size] ReLU-derivative marks (see relu_open). */
 void orc_learner_step(const orc_net *n, const orc_hparams *hp, int N, double *X, double *V,
                       const uint8_t *obs, const int32_t *actions, const float *rewards,
                       const uint8_t *dones, const uint8_t *boot_obs,
-                      double *grads_out, double *stats)
+                      double *grads_out, double *stats, const uint8_t *gates)
 {
     orc_shape s; shape_of(n, &s);
     const int M = hp->T * hp->B;
@@ -453,7 +473,8 @@ void orc_learner_step(const orc_net *n, const orc_hparams *hp, int N, double *X,
         double terms[3], scale;
         orc_agent_gradient(n, hp, X + (long)i * s.d, obs + (long)i * M * s.in_size,
                            actions + (long)i * M, r, dones + (long)i * M,
-                           boot_obs + (long)i * hp->B * s.in_size, g, terms, NULL, NULL, NULL, NULL);
+                           boot_obs + (long)i * hp->B * s.in_size, g, terms, NULL, NULL, NULL, NULL,
+                           gates ? gates + (long)i * M * s.act_size : NULL);
         if (grads_out) memcpy(grads_out + (long)i * s.d, g, sizeof(double) * s.d);
         const double norm = orc_clip_grad_norm(g, s.d, hp->max_grad_norm, &scale);
         orc_rmsprop(X + (long)i * s.d, V + (long)i * s.d, g, s.d, hp->lr, hp->rms_alpha, hp->rms_eps);

@@ -60,10 +60,10 @@ def lib():
         L.orc_nstep_returns.argtypes = [C.c_int, C.c_int, C.c_double] + [C.c_void_p] * 6
         L.orc_a2c_loss.argtypes = ([C.c_int, C.c_int] + [C.c_void_p] * 5 +
                                    [C.c_double, C.c_double] + [C.c_void_p] * 3)
-        L.orc_forward.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int] + [C.c_void_p] * 3
-        L.orc_agent_gradient.argtypes = [C.c_void_p] * 14
+        L.orc_forward.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int] + [C.c_void_p] * 4
+        L.orc_agent_gradient.argtypes = [C.c_void_p] * 15
         L.orc_agent_loss.argtypes = [C.c_void_p] * 11
-        L.orc_learner_step.argtypes = [C.c_void_p, C.c_void_p, C.c_int] + [C.c_void_p] * 9
+        L.orc_learner_step.argtypes = [C.c_void_p, C.c_void_p, C.c_int] + [C.c_void_p] * 10
         L.orc_mix_uniform.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_long, C.c_void_p]
         L.orc_mix_weighted.argtypes = [C.c_void_p, C.c_double, C.c_void_p, C.c_void_p,
                                        C.c_int, C.c_long, C.c_void_p]
@@ -109,13 +109,14 @@ def forward(net: dict, x: np.ndarray, obs: np.ndarray):
     F = obs.shape[0]
     logits = np.empty((F, net["n_actions"]))
     values = np.empty(F)
-    lib().orc_forward(C.byref(n), _p(x), _p(obs), F, _p(logits), _p(values), None)
+    lib().orc_forward(C.byref(n), _p(x), _p(obs), F, _p(logits), _p(values), None, None)
     return logits, values
 
 
-def forward_acts(net: dict, x: np.ndarray, obs: np.ndarray):
+def forward_acts(net: dict, x: np.ndarray, obs: np.ndarray, with_pre: bool = False):
     """As forward(), also returning the per-frame record [F, act_size]
-    (scaled input, each conv output after ReLU, hidden after ReLU)."""
+    (scaled input, each conv output after ReLU, hidden after ReLU) and, with
+    with_pre=True, the values before each ReLU at the same offsets."""
     n = c_net(net)
     x = np.ascontiguousarray(x, dtype=np.float64)
     obs = np.ascontiguousarray(obs, dtype=np.uint8)
@@ -123,8 +124,25 @@ def forward_acts(net: dict, x: np.ndarray, obs: np.ndarray):
     logits = np.empty((F, net["n_actions"]))
     values = np.empty(F)
     acts = np.empty((F, int(lib().orc_act_size(C.byref(n)))))
-    lib().orc_forward(C.byref(n), _p(x), _p(obs), F, _p(logits), _p(values), _p(acts))
+    pre = np.zeros_like(acts) if with_pre else None
+    lib().orc_forward(C.byref(n), _p(x), _p(obs), F, _p(logits), _p(values), _p(acts), _p(pre))
+    if with_pre:
+        return logits, values, acts, pre
     return logits, values, acts
+
+
+def act_offsets(net: dict) -> dict:
+    """Offsets and CHW shapes of each layer's output inside a per-frame record."""
+    c, h, w = net["in_c"], net["in_h"], net["in_w"]
+    off = c * h * w
+    out = {}
+    for li, (o, k, s) in enumerate(net["conv"], start=1):
+        h = (h - k) // s + 1
+        w = (w - k) // s + 1
+        out[f"conv{li}"] = (off, (o, h, w))
+        off += o * h * w
+    out["fc"] = (off, (net["fc"],))
+    return out
 
 
 def nstep_returns(rewards, dones, v_boot, values, gamma):
@@ -155,7 +173,7 @@ def a2c_loss(logits, values, actions, G, Adv, vf_coef, ent_coef):
     return terms, dlogits, dvalues
 
 
-def agent_gradient(net, T, B, hp, x, obs, actions, rewards, dones, boot_obs, extras=False):
+def agent_gradient(net, T, B, hp, x, obs, actions, rewards, dones, boot_obs, extras=False, gate=None):
     """Gradient of one agent's loss.  Returns (grads[d], terms[3]) and, with
     extras=True, also a dict with G, Adv, logits, values (rollout then bootstrap)."""
     n, h = c_net(net), c_hparams(T, B, hp)
@@ -171,7 +189,8 @@ def agent_gradient(net, T, B, hp, x, obs, actions, rewards, dones, boot_obs, ext
     G = np.empty(M); Adv = np.empty(M); lg = np.empty((M, A)); vals = np.empty(M + B)
     lib().orc_agent_gradient(C.byref(n), C.byref(h), _p(x), _p(obs), _p(actions), _p(rewards),
                              _p(dones), _p(boot_obs), _p(g), _p(terms),
-                             _p(G), _p(Adv), _p(lg), _p(vals))
+                             _p(G), _p(Adv), _p(lg), _p(vals),
+                             _p(None if gate is None else np.ascontiguousarray(gate, dtype=np.uint8)))
     if extras:
         return g, terms, dict(G=G, Adv=Adv, logits=lg, values=vals)
     return g, terms
@@ -292,7 +311,7 @@ class OracleGala:
     def set_opt_state(self, V):
         self.V = np.array(V, dtype=np.float64).reshape(self.N, self.d)
 
-    def learner_step(self, obs, actions, rewards, dones, boot_obs):
+    def learner_step(self, obs, actions, rewards, dones, boot_obs, gates=None):
         n, h = c_net(self.net), c_hparams(self.T, self.B, self.hp)
         obs = np.ascontiguousarray(obs, dtype=np.uint8)
         boot_obs = np.ascontiguousarray(boot_obs, dtype=np.uint8)
@@ -303,7 +322,8 @@ class OracleGala:
         self.stats = np.empty((self.N, 5))
         lib().orc_learner_step(C.byref(n), C.byref(h), self.N, _p(self.X), _p(self.V),
                                _p(obs), _p(actions), _p(rewards), _p(dones), _p(boot_obs),
-                               _p(self.grads), _p(self.stats))
+                               _p(self.grads), _p(self.stats),
+                               _p(None if gates is None else np.ascontiguousarray(gates, dtype=np.uint8)))
 
     def gossip(self, rnd: int):
         """Broadcast the post-update parameters, then every agent that holds a

@@ -355,3 +355,20 @@ extern "C" int gala_get_phase_times(gala_ctx *c, char *names, size_t names_cap, 
     *n_out = n;
     return GALA_OK;
 }
+
+extern "C" int gala_get_activations(gala_ctx *c, int layer, float *dst_host)
+{
+    if (!c || !dst_host) return fail(c, GALA_EINVAL, "null argument");
+    const float *src = nullptr;
+    size_t per_frame = 0;
+    switch (layer) {
+    case 1: src = c->b.a1; per_frame = A1SZ; break;
+    case 2: src = c->b.a2; per_frame = A2SZ; break;
+    case 3: src = c->b.a3; per_frame = A3SZ; break;
+    case 4: src = c->b.h; per_frame = FC; break;
+    default: return fail(c, GALA_EINVAL, "layer must be 1..4");
+    }
+    HIP_OK(c, hipMemcpyAsync(dst_host, src, (size_t)c->N * c->F * per_frame * 4, hipMemcpyDeviceToHost, c->stream));
+    HIP_OK(c, hipStreamSynchronize(c->stream));
+    return GALA_OK;
+}

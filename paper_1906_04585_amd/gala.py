@@ -18,7 +18,7 @@ EXPORTS = [
     "gala_set_params", "gala_get_params", "gala_set_opt_state", "gala_get_opt_state",
     "gala_learner_step", "gala_gossip", "gala_get_grads", "gala_get_step_stats",
     "gala_get_outputs", "gala_consensus_distance", "gala_get_peer_table",
-    "gala_set_profiling", "gala_get_phase_times",
+    "gala_set_profiling", "gala_get_phase_times", "gala_get_activations",
 ]
 
 TOPOLOGY = {"ring": 0, "exp": 1, "explicit": 2}
@@ -76,6 +76,7 @@ def load_library():
         L.gala_consensus_distance.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
         L.gala_get_peer_table.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
         L.gala_set_profiling.argtypes = [C.c_void_p, C.c_int]
+        L.gala_get_activations.argtypes = [C.c_void_p, C.c_int, C.c_void_p]
         L.gala_get_phase_times.argtypes = [C.c_void_p, C.c_char_p, C.c_size_t, C.c_void_p, C.c_int, C.c_void_p]
         _lib = L
     return _lib
@@ -233,3 +234,12 @@ class Gala:
         for k, v in zip(keys, list(ms)[:n.value]):
             out[k] = out.get(k, 0.0) + float(v)
         return out
+
+    _ACT_SHAPES = {1: (20, 20, 32), 2: (9, 9, 64), 3: (7, 7, 64), 4: (512,)}
+
+    def get_activations(self, layer: int) -> np.ndarray:
+        """[N, F, H, W, C] (layer 1..3) or [N, F, 512] (layer 4), channels-last, after ReLU."""
+        F = self.T * self.B + self.B
+        a = np.empty((self.N, F) + self._ACT_SHAPES[layer], dtype=np.float32)
+        self._check(self._lib.gala_get_activations(self._h, layer, a.ctypes.data_as(C.c_void_p)))
+        return a

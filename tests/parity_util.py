@@ -24,10 +24,63 @@ def upload(ro: dict):
     return {k: torch.from_numpy(np.ascontiguousarray(v)).cuda() for k, v in ro.items()}
 
 
+# A ReLU unit whose pre-activation is within single-precision rounding of zero has its
+# derivative decided by rounding; fp32 and fp64 may legitimately disagree there.  The
+# decision is then taken in the kernel's precision: the test reads the GPU's activations,
+# requires every disagreeing unit to have |z| <= KINK * max|z| of its layer *in the oracle's
+# own forward pass*, and only for those units tells the oracle which way the GPU went.
+KINK = 1e-5
+
+
+def relu_gates(gpu, net, X, ro, agents=None):
+    """Per agent ReLU-derivative marks [len(agents), M, act_size] (0 = oracle decides) and
+    the number of marked units.  Also checks every activation tensor against the oracle."""
+    from oracle import gala_oracle as orc
+    agents = list(range(gpu.N)) if agents is None else list(agents)
+    M = gpu.T * gpu.B
+    offs = orc.act_offsets(net)
+    layers = [("conv1", 1), ("conv2", 2), ("conv3", 3), ("fc", 4)]
+    gpu_acts = {}
+    for name, li in layers:
+        a = gpu.get_activations(li)
+        if a.ndim == 5:
+            a = a.transpose(0, 1, 4, 2, 3)             # channels-last -> channel, row, column
+        gpu_acts[name] = a.reshape(gpu.N, a.shape[1], -1)
+    gates = None
+    marked = 0
+    for gi, i in enumerate(agents):
+        obs = ro["obs"][i].reshape((M,) + ro["obs"].shape[3:])
+        _, _, acts, pre = orc.forward_acts(net, np.asarray(X[i], dtype=np.float64), obs, with_pre=True)
+        if gates is None:
+            gates = np.zeros((len(agents), M, acts.shape[1]), dtype=np.uint8)
+        for name, li in layers:
+            off, shape = offs[name]
+            n = int(np.prod(shape))
+            z = pre[:, off:off + n]
+            ga = gpu_acts[name][i, :M]
+            scale = np.abs(z).max()
+            e = np.abs(ga - np.maximum(z, 0.0)).max() / scale
+            assert e <= RTOL, f"activation {name} agent {i}: rel err {e:.3e}"
+            mism = (ga > 0) != (z > 0)
+            if mism.any():
+                assert np.abs(z[mism]).max() <= KINK * scale, \
+                    f"{name} agent {i}: ReLU decision differs away from zero (|z| = {np.abs(z[mism]).max():.3e})"
+                g = gates[gi, :, off:off + n]
+                g[mism & (ga > 0)] = 1
+                g[mism & ~(ga > 0)] = 2
+                marked += int(mism.sum())
+    return gates, marked
+
+
 def step_both(gpu, orc_model, ro: dict, dev: dict | None = None):
+    """One learner step on both sides from the oracle's current state (which the caller has
+    made equal to the GPU's).  Returns the number of ReLU units decided in the GPU's precision."""
     dev = dev or upload(ro)
     gpu.learner_step(dev["obs"], dev["actions"], dev["rewards"], dev["dones"], dev["boot_obs"])
-    orc_model.learner_step(ro["obs"], ro["actions"], ro["rewards"], ro["dones"], ro["boot_obs"])
+    gates, marked = relu_gates(gpu, orc_model.net, orc_model.X, ro)
+    orc_model.learner_step(ro["obs"], ro["actions"], ro["rewards"], ro["dones"], ro["boot_obs"],
+                           gates=gates if marked else None)
+    return marked
 
 
 def compare_learner_step(gpu, orc_model, net, tag="", rtol=RTOL):

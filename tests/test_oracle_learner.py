@@ -331,3 +331,29 @@ def test_learner_step_composes_gradient_clip_and_rmsprop():
         np.testing.assert_allclose(o.X[i], x, rtol=1e-13, atol=1e-16)
         assert abs(o.stats[i, 3] - n) < 1e-12 * n and abs(o.stats[i, 4] - c) < 1e-14
     assert clipped > 0
+
+
+def test_relu_marks_only_change_the_marked_unit():
+    """Marks equal to the natural decisions change nothing; blocking one active unit
+    changes the gradient, and only for parameters at or below that unit's layer."""
+    net, T, B = MID, 2, 2
+    x, ro = _tiny_problem(net, T, B, seed=61)
+    args = (ro["obs"], ro["actions"], ro["rewards"], ro["dones"], ro["boot_obs"])
+    g0, _ = orc.agent_gradient(net, T, B, HP, x, *args)
+    M = T * B
+    obs = ro["obs"].reshape((M,) + ro["obs"].shape[2:])
+    _, _, acts = orc.forward_acts(net, x, obs)
+    natural = np.where(acts > 0, 1, 2).astype(np.uint8)
+    g1, _ = orc.agent_gradient(net, T, B, HP, x, *args, gate=natural)
+    np.testing.assert_array_equal(g0, g1)
+    off, shape = orc.act_offsets(net)["conv2"]
+    frame = 1
+    idx = off + int(np.argmax(acts[frame, off:off + int(np.prod(shape))]))
+    gate = np.zeros_like(natural)
+    gate[frame, idx] = 2
+    g2, _ = orc.agent_gradient(net, T, B, HP, x, *args, gate=gate)
+    assert np.abs(g2 - g0).max() > 1e-6 * np.abs(g0).max()
+    # blocking a unit only affects parameters at or below its layer
+    sl = gs.segment_slices(net)
+    for name in ("conv3.w", "conv3.b", "fc.w", "fc.b", "pi.w", "pi.b", "v.w", "v.b"):
+        np.testing.assert_array_equal(g2[sl[name]], g0[sl[name]])

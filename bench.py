@@ -1,0 +1,188 @@
+#!/usr/bin/env python3
+"""Throughput of the GALA-A2C hot path on one MI355X.
+
+A step is one round of Algorithm 1 for all agents: gala_learner_step (returns,
+A2C loss, forward/backward, clip, RMSprop for every agent) followed by gala_gossip
+(one mixing iteration over the 1-peer exponential graph).  Inputs are synthetic
+Atari-shaped rollouts that are resident in HBM before the timed region starts; a
+pool of four rollouts is cycled.  One JSON line is printed on stdout.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# MACs per frame of each layer (unpadded 8x8/4, 4x4/2, 3x3/1 convolutions on 4x84x84, 512 hidden)
+MACS = dict(conv1=3_276_800, conv2=2_654_208, conv3=1_806_336, fc=1_605_632)
+PEAK_MFMA_F32_TFLOPS = 157.3
+PEAK_HBM_GBS = 8000.0
+
+
+def kernel_work(N: int, M: int, F: int, d: int, tau: int) -> dict:
+    """Algorithmic work of one launch of each kernel: ('mfma', flop) or ('hbm', bytes)."""
+    w = {}
+    for layer, macs in MACS.items():
+        w[f"{layer}_fwd"] = ("mfma", 2.0 * macs * F * N)
+        w[f"{layer}_wgrad"] = ("mfma", 2.0 * macs * M * N)
+        if layer != "conv1":                     # the input needs no gradient
+            w[f"{layer}_dgrad"] = ("mfma", 2.0 * macs * M * N)
+    w["grad_norm"] = ("hbm", 4.0 * d * N)        # read g
+    w["clip_rmsprop"] = ("hbm", 20.0 * d * N)    # read g, x, v; write x, v
+    w["gossip_mix"] = ("hbm", 12.0 * d * N)      # read x_i, x_j; write x_i
+    if tau > 0:
+        w["gossip_publish"] = ("hbm", 8.0 * d * N)
+    return w
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=300)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=4, help="workload shape 1..5 (default: 32 agents)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--profile-rounds", type=int, default=20)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: N agents share a single MI355X and nothing here "
+              "uses a second device; run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    import gala_synth as gs
+    from paper_1906_04585_amd import Gala
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        return 1
+    torch.cuda.set_device(0)
+    cfg = gs.CONFIGS[args.config]
+    N, A, T, B = cfg["n_agents"], cfg["n_actions"], cfg["T"], cfg["B"]
+    M, F = T * B, T * B + B
+    net = gs.make_net(A)
+    gpu = Gala(N, A, T, B, gs.HPARAMS, cfg["topology"], max_delay=cfg["max_delay"], delay_seed=7)
+    X0 = gs.init_params(net, N, shared=True)
+    gpu.set_params(X0)
+    pool = []
+    for r in range(4):
+        ro = gs.rollout(net, N, T, B, gs.round_seed(args.config, r))
+        pool.append({k: torch.from_numpy(v).cuda() for k, v in ro.items()})
+    torch.cuda.synchronize()
+
+    def one_round(r):
+        d = pool[r % len(pool)]
+        gpu.learner_step(d["obs"], d["actions"], d["rewards"], d["dones"], d["boot_obs"])
+        gpu.gossip(r)
+
+    rnd = 0
+    for _ in range(args.warmup):
+        one_round(rnd)
+        rnd += 1
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        one_round(rnd)
+        rnd += 1
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = 1e3 * elapsed / args.steps
+    agent_steps = N * args.steps / elapsed
+    frames = agent_steps * M
+
+    # per-kernel durations from HIP events recorded on the library's stream
+    gpu.set_profiling(True)
+    acc: dict[str, float] = {}
+    for _ in range(args.profile_rounds):
+        one_round(rnd)
+        rnd += 1
+        for k, v in gpu.get_phase_times().items():
+            acc[k] = acc.get(k, 0.0) + v / args.profile_rounds
+    gpu.set_profiling(False)
+    work = kernel_work(N, M, F, gpu.d, cfg["max_delay"])
+    kernels = {}
+    for k, ms in acc.items():
+        ent = {"ms": round(ms, 5)}
+        if k in work:
+            kind, amount = work[k]
+            if kind == "mfma":
+                ent.update(bound="mfma", achieved=round(amount / (ms * 1e-3) / 1e12, 2), unit="TFLOP/s",
+                           frac=round(amount / (ms * 1e-3) / 1e12 / PEAK_MFMA_F32_TFLOPS, 4))
+            else:
+                ent.update(bound="hbm", achieved=round(amount / (ms * 1e-3) / 1e9, 1), unit="GB/s",
+                           frac=round(amount / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4))
+        kernels[k] = ent
+    dominant = max((k for k in acc if k in work), key=lambda k: acc[k])
+    kind, amount = work[dominant]
+    dur = acc[dominant] * 1e-3
+    if kind == "mfma":
+        roofline = dict(kernel=dominant, bound="mfma", achieved=amount / dur / 1e12, peak=PEAK_MFMA_F32_TFLOPS,
+                        unit="TFLOP/s", frac=amount / dur / 1e12 / PEAK_MFMA_F32_TFLOPS, traffic=None,
+                        avg_launch_ms=acc[dominant])
+    else:
+        roofline = dict(kernel=dominant, bound="hbm", achieved=amount / dur / 1e9, peak=PEAK_HBM_GBS,
+                        unit="GB/s", frac=amount / dur / 1e9 / PEAK_HBM_GBS, traffic=None,
+                        avg_launch_ms=acc[dominant])
+    mfma_ms = sum(acc[k] for k in acc if k in work and work[k][0] == "mfma")
+    mfma_flop = sum(work[k][1] for k in acc if k in work and work[k][0] == "mfma")
+    hbm_ms = sum(acc[k] for k in acc if k in work and work[k][0] == "hbm")
+    hbm_bytes = sum(work[k][1] for k in acc if k in work and work[k][0] == "hbm")
+    phase_summary = dict(
+        conv_fc=dict(ms=round(mfma_ms, 4), tflops=round(mfma_flop / (mfma_ms * 1e-3) / 1e12, 2),
+                     frac_mfma_f32=round(mfma_flop / (mfma_ms * 1e-3) / 1e12 / PEAK_MFMA_F32_TFLOPS, 4)),
+        optimizer_gossip=dict(ms=round(hbm_ms, 4), gbs=round(hbm_bytes / (hbm_ms * 1e-3) / 1e9, 1),
+                              frac_hbm=round(hbm_bytes / (hbm_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)),
+        other_ms=round(sum(acc.values()) - mfma_ms - hbm_ms, 4))
+
+    cpu_baseline = None
+    if not args.no_cpu_baseline:
+        from oracle import gala_oracle as orc
+        threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+        n_s = min(N, 16)                       # a bounded sample: one round of the first 16 agents
+        om = orc.OracleGala(net, n_s, T, B, gs.HPARAMS, cfg["topology"])
+        om.set_params(X0[:n_s])
+        ro = gs.rollout(net, n_s, T, B, gs.round_seed(args.config, 0))
+        t0 = time.perf_counter()
+        om.learner_step(ro["obs"], ro["actions"], ro["rewards"], ro["dones"], ro["boot_obs"])
+        om.gossip(0)
+        cpu_t = time.perf_counter() - t0
+        cpu_baseline = dict(value=n_s / cpu_t, unit="agent-steps/s", cores=threads, kind="oracle",
+                            sample=f"one round (learner step + gossip) of {n_s} of the {N} agents, "
+                                   f"{n_s * M} frames, fp64, {cpu_t:.2f} s")
+
+    out = {
+        "metric": "agent learner-steps/sec (one learner step + one gossip round per agent)",
+        "value": agent_steps,
+        "unit": "agent-steps/s",
+        "env_frames_per_s": frames,
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"N={N} agents, 1-peer {cfg['topology']} graph, Nature-CNN, {A} actions, "
+                               f"rollout {T}x{B} per agent ({N * M} frames/round), fp32",
+                   "n_agents": N, "T": T, "B": B, "n_actions": A, "topology": cfg["topology"],
+                   "max_delay": cfg["max_delay"]},
+        "roofline": roofline,
+        "phases": phase_summary,
+        "kernels": kernels,
+        "cpu_baseline": cpu_baseline,
+    }
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

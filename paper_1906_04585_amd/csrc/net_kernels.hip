@@ -559,9 +559,10 @@ hipError_t launch_forward(const NetArgs &a, hipStream_t s, PhaseTimer *pt)
         p.kchunk = FC_KCHUNK;
         p.tiles_m = cdiv(a.F, FcFwd::BM); p.tiles_n = FC / FcFwd::BN; p.splits = cdiv(FLAT, FC_KCHUNK);
         GALA_TRY(igemm_launch(p, a.N, s));
+        pt->mark("fc_fwd");
         GALA_TRY(reduce_splits(a.b.ws, p.splits, (long)a.F * FC, a.N, a.b.h, (long)a.F * FC,
                                a.x + L.fcb, L.d_pad, FC, s));
-        pt->mark("fc_fwd");
+        pt->mark("fc_fwd_reduce");
     }
     hipLaunchKernelGGL(heads_fwd_kernel, dim3(a.F, a.N), dim3(64), 0, s, a.b.h, a.x, L, a.M, a.F,
                        a.b.logits, a.b.values);
@@ -575,12 +576,14 @@ hipError_t launch_backward(const NetArgs &a, hipStream_t s, PhaseTimer *pt)
     hipLaunchKernelGGL(heads_dgrad_kernel, dim3(a.M, a.N), dim3(256), 0, s, a.b.h, a.x, L, a.M, a.F,
                        a.b.dlogits, a.b.dvalues, a.b.dzh);
     GALA_TRY(hipGetLastError());
+    pt->mark("heads_dgrad");
     hipLaunchKernelGGL(heads_wgrad_kernel, dim3(L.n_actions + 1, a.N), dim3(256), 0, s, a.b.h, L, a.M, a.F,
                        a.b.dlogits, a.b.dvalues, a.b.g);
     GALA_TRY(hipGetLastError());
+    pt->mark("heads_wgrad");
     hipLaunchKernelGGL(fc_bias_grad_kernel, dim3(a.N), dim3(256), 0, s, a.b.dzh, a.M, a.b.g, L.d_pad, L.fcb);
     GALA_TRY(hipGetLastError());
-    pt->mark("heads_bwd");
+    pt->mark("fc_bgrad");
     {
         FcWgrad p{};
         p.dzh = a.b.dzh; p.a3 = a.b.a3; p.g = a.b.g; p.d_pad = L.d_pad; p.w_off = L.fcw; p.M = a.M; p.F = a.F;
@@ -598,13 +601,15 @@ hipError_t launch_backward(const NetArgs &a, hipStream_t s, PhaseTimer *pt)
     }
     // conv3
     GALA_TRY(bias_grad<C3>(a.b.dz3, (long)a.M * A3SZ, a.M * P3, a.N, a.b.ws, a.b.g, L.d_pad, L.b3, s));
+    pt->mark("conv3_bgrad");
     {
         Conv3Wgrad p{};
         p.in = a.b.a2; p.dz = a.b.dz3; p.ws = a.b.ws; p.M = a.M; p.F = a.F; p.fps = FPS_CONV3;
         p.tiles_m = cdiv(KW3, Conv3Wgrad::BM); p.tiles_n = 1; p.splits = cdiv(a.M, FPS_CONV3);
         GALA_TRY(igemm_launch(p, a.N, s));
-        GALA_TRY(reduce_splits(a.b.ws, p.splits, (long)KW3 * C3, a.N, a.b.g + L.w3, L.d_pad, nullptr, 0, 1, s));
         pt->mark("conv3_wgrad");
+        GALA_TRY(reduce_splits(a.b.ws, p.splits, (long)KW3 * C3, a.N, a.b.g + L.w3, L.d_pad, nullptr, 0, 1, s));
+        pt->mark("conv3_wgrad_reduce");
     }
     {
         Conv3Dgrad p{};
@@ -616,13 +621,15 @@ hipError_t launch_backward(const NetArgs &a, hipStream_t s, PhaseTimer *pt)
     }
     // conv2
     GALA_TRY(bias_grad<C2>(a.b.dz2, (long)a.M * A2SZ, a.M * P2, a.N, a.b.ws, a.b.g, L.d_pad, L.b2, s));
+    pt->mark("conv2_bgrad");
     {
         Conv2Wgrad p{};
         p.in = a.b.a1; p.dz = a.b.dz2; p.ws = a.b.ws; p.M = a.M; p.F = a.F; p.fps = FPS_CONV2;
         p.tiles_m = cdiv(KW2, Conv2Wgrad::BM); p.tiles_n = 1; p.splits = cdiv(a.M, FPS_CONV2);
         GALA_TRY(igemm_launch(p, a.N, s));
-        GALA_TRY(reduce_splits(a.b.ws, p.splits, (long)KW2 * C2, a.N, a.b.g + L.w2, L.d_pad, nullptr, 0, 1, s));
         pt->mark("conv2_wgrad");
+        GALA_TRY(reduce_splits(a.b.ws, p.splits, (long)KW2 * C2, a.N, a.b.g + L.w2, L.d_pad, nullptr, 0, 1, s));
+        pt->mark("conv2_wgrad_reduce");
     }
     {
         Conv2Dgrad p{};
@@ -634,13 +641,15 @@ hipError_t launch_backward(const NetArgs &a, hipStream_t s, PhaseTimer *pt)
     }
     // conv1 (the input needs no gradient)
     GALA_TRY(bias_grad<C1>(a.b.dz1, (long)a.M * A1SZ, a.M * P1, a.N, a.b.ws, a.b.g, L.d_pad, L.b1, s));
+    pt->mark("conv1_bgrad");
     {
         Conv1Wgrad p{};
         p.obs = a.obs; p.dz1 = a.b.dz1; p.ws = a.b.ws; p.M = a.M; p.fps = FPS_CONV1;
         p.tiles_m = 1; p.tiles_n = 1; p.splits = cdiv(a.M, FPS_CONV1);
         GALA_TRY(igemm_launch(p, a.N, s));
-        GALA_TRY(reduce_splits(a.b.ws, p.splits, (long)KW1 * C1, a.N, a.b.g + L.w1, L.d_pad, nullptr, 0, 1, s));
         pt->mark("conv1_wgrad");
+        GALA_TRY(reduce_splits(a.b.ws, p.splits, (long)KW1 * C1, a.N, a.b.g + L.w1, L.d_pad, nullptr, 0, 1, s));
+        pt->mark("conv1_wgrad_reduce");
     }
     return hipSuccess;
 }

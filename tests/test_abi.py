@@ -1,0 +1,91 @@
+"""The C-ABI library loads, exports every function include/gala.h declares, and rejects
+bad arguments on the host before touching the GPU (no compute calls here)."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import gala_synth as gs
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "gala.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(gala_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    from paper_1906_04585_amd import load_library
+    from paper_1906_04585_amd.gala import EXPORTS
+    lib = load_library()
+    names = _declared()
+    assert "gala_create" in names and "gala_learner_step" in names and "gala_gossip" in names
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(EXPORTS) == names           # the binding covers exactly the header
+
+
+def _create(n_agents=2, n_actions=6, topology="ring", **kw):
+    from paper_1906_04585_amd import gala as g
+    lib = g.load_library()
+    net = g._NetDims(kw.get("in_c", 4), 84, 84, kw.get("c1", 32), 64, 64, kw.get("fc", 512), n_actions)
+    hp = g._HParams(kw.get("T", 5), kw.get("B", 4), 0.99, 0.5, 0.01, 7e-4, kw.get("rms_alpha", 0.99),
+                    kw.get("rms_eps", 1e-5), 0.5, kw.get("compute_dtype", 0))
+    topo = g._Topology()
+    topo.kind = g.TOPOLOGY[topology] if isinstance(topology, str) else topology
+    topo.max_delay = kw.get("max_delay", 0)
+    keep = []
+    if "peers" in kw:
+        p = np.ascontiguousarray(kw["peers"], dtype=np.int32)
+        w = np.ascontiguousarray(kw["weights"], dtype=np.float32)
+        keep += [p, w]
+        topo.peers, topo.weights = p.ctypes.data, w.ctypes.data
+        topo.n_phases, topo.max_in = p.shape[0], p.shape[2]
+    h = C.c_void_p()
+    rc = lib.gala_create(C.byref(h), n_agents, C.byref(topo), C.byref(net), C.byref(hp), None)
+    return rc, lib.gala_last_error(None).decode(), h, lib
+
+
+@pytest.mark.parametrize("kw,needle", [
+    (dict(n_agents=0), "n_agents"),
+    (dict(n_actions=0), "n_actions"),
+    (dict(n_actions=65), "n_actions"),
+    (dict(c1=16), "network"),
+    (dict(in_c=3), "network"),
+    (dict(fc=256), "network"),
+    (dict(T=0), "T, B"),
+    (dict(compute_dtype=1), "compute_dtype"),
+    (dict(rms_eps=0.0), "rms_eps"),
+    (dict(rms_alpha=1.0), "rms_alpha"),
+    (dict(topology="exp", n_agents=6), "power-of-two"),
+    (dict(topology=7), "topology kind"),
+    (dict(max_delay=-1), "max_delay"),
+    (dict(max_delay=17), "max_delay"),
+    (dict(topology="explicit", n_agents=2, peers=[[[1], [2]]], weights=[[[0.5, 0.5], [0.5, 0.5]]]), "out of range"),
+    (dict(topology="explicit", n_agents=2, peers=[[[1], [0]]], weights=[[[0.5, 0.6], [0.5, 0.5]]]), "sum to"),
+    (dict(topology="explicit", n_agents=2, peers=[[[1], [0]]], weights=[[[1.5, -0.5], [0.5, 0.5]]]), "negative"),
+])
+def test_create_rejects_bad_arguments_with_einval(kw, needle):
+    rc, text, h, _ = _create(**kw)
+    assert rc == -1 and not h.value, (rc, text)
+    assert needle in text, text
+
+
+def test_null_context_calls_fail_cleanly():
+    from paper_1906_04585_amd import load_library
+    lib = load_library()
+    assert lib.gala_gossip(None, 0) == -1
+    assert lib.gala_learner_step(None, None, None, None, None, None) == -1
+    assert lib.gala_get_params(None, None, 0) == -1
+    assert lib.gala_param_count(None) == 0
+    assert lib.gala_destroy(None) == 0
+
+
+def test_parameter_count_formula():
+    # d = 1 684 128 + 513 + 513 A  (trunk + value head + policy head)
+    assert gs.param_count(gs.make_net(6)) == 1_687_719
+    assert gs.param_count(gs.make_net(18)) == 1_693_875

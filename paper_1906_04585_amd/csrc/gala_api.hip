@@ -150,6 +150,12 @@ extern "C" int gala_create(gala_ctx **out, int n_agents, const gala_topology *to
     c->N = n_agents;
     c->L = make_layout(net->n_actions);
     c->seg = make_segments(c->L);
+    // the weight-gradient reduction writes each bias gradient right behind its weight gradient
+    if (c->L.b1 != c->L.w1 + (long)KW1 * C1 || c->L.b2 != c->L.w2 + (long)KW2 * C2 ||
+        c->L.b3 != c->L.w3 + (long)KW3 * C3 || c->L.fcb != c->L.fcw + (long)FC * FLAT) {
+        delete c;
+        return fail(nullptr, GALA_EINVAL, "internal layout: bias does not follow its weight tensor");
+    }
     c->hp = HParams{hp->T, hp->B, hp->gamma, hp->vf_coef, hp->ent_coef, hp->lr, hp->rms_alpha, hp->rms_eps,
                     hp->max_grad_norm};
     c->M = hp->T * hp->B;

@@ -16,20 +16,42 @@
 //   int tiles_m, tiles_n, splits            filled by the host
 //   void bind(int agent, int split)         per-agent pointers and the split's k-range
 //   int  k_begin(), k_end()
-//   void load_a(float (&r)[4], int m, int k)   zero-fills outside the problem
-//   void load_b(float (&r)[4], int k, int n)
-//   void store(int m, int n, float v)
+//   typedef ARaw, BRaw                      what one global load of a group returns (float4, or a
+//                                           uint32_t of four bytes)
+//   ARaw fetch_a(int m, int k, bool &ok)    ok comes in as "k is inside the k-range" and goes out
+//   BRaw fetch_b(int k, int n, bool &ok)    as "this group exists"; the load itself is always
+//                                           issued, from a clamped address when !ok, so that no
+//                                           branch or wait sits between the loads of a tile
+//   void decode_a(float (&r)[4], ARaw)      raw -> four floats (applied at staging time, after
+//   void decode_b(float (&r)[4], BRaw)      the MFMAs of the current tile were issued)
+//   float col_value(int n)                  loaded once per output column (e.g. the bias)
+//   static constexpr bool HAS_AUX; float aux(int m, int n)
+//                                           optional per-element operand of the epilogue (e.g. the
+//                                           activation whose sign masks a gradient); all are loaded,
+//                                           from clamped addresses, before the first store
+//   template <bool CHECK> void store(int m, int n, float v, float colv, float aux)
+//   bool tile_full(int m0, int n0)          uniform: the whole BM x BN tile lies inside the output.
+//                                           Full tiles run an epilogue without any per-element
+//                                           bounds branch (CHECK = false), so that loads and stores
+//                                           are issued back to back; edge tiles take the checked path.
+//   static constexpr bool SUM_A, SUM_B      optional: also produce sum_k A[m][k] (tiles with
+//                                           tn == 0) or sum_k B[k][n] (tiles with tm == 0) over
+//                                           the k-range, delivered through store_sum_a(m, v) /
+//                                           store_sum_b(n, v); needs the operand in "4 consecutive
+//                                           m (n)" mode.  Used for bias gradients, which are exactly
+//                                           these sums of an operand the weight-gradient GEMM reads.
 //
 // Workgroup ids are interleaved over the 8 XCDs by the dispatcher; the decode below
 // keeps all tiles of one agent on one XCD so that its weights and activations are
 // shared through that XCD's L2.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <type_traits>
 
 typedef float gala_f32x16 __attribute__((ext_vector_type(16)));
 
 template <class P>
-__global__ __launch_bounds__(256) void igemm_kernel(P p, int n_agents)
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void igemm_kernel(P p, int n_agents)
 {
     constexpr int BM = P::BM, BN = P::BN, BK = P::BK;
     constexpr int PAD = 4;
@@ -61,7 +83,13 @@ __global__ __launch_bounds__(256) void igemm_kernel(P p, int n_agents)
 
     constexpr int GA = BM * BK / 4, GB = BN * BK / 4;       // groups of four per tile
     constexpr int PA = (GA + 255) / 256, PB = (GB + 255) / 256;
-    float ra[PA][4], rb[PB][4];
+    typename P::ARaw ra[PA];
+    typename P::BRaw rb[PB];
+    bool oka[PA], okb[PB];
+    static_assert(!P::SUM_A || (!P::A_KC && 256 % (BM / 4) == 0), "SUM_A needs m-contiguous groups");
+    static_assert(!P::SUM_B || (!P::B_KC && 256 % (BN / 4) == 0), "SUM_B needs n-contiguous groups");
+    float sum_a[4] = {0.f, 0.f, 0.f, 0.f}, sum_b[4] = {0.f, 0.f, 0.f, 0.f};
+    const bool do_sum_a = P::SUM_A && tn == 0, do_sum_b = P::SUM_B && tm == 0;
 
     const int kb = p.k_begin(), ke = p.k_end();
 
@@ -69,28 +97,30 @@ __global__ __launch_bounds__(256) void igemm_kernel(P p, int n_agents)
 #pragma unroll
         for (int i = 0; i < PA; ++i) {
             const int g = tid + i * 256;
-            ra[i][0] = ra[i][1] = ra[i][2] = ra[i][3] = 0.f;
             if (GA % 256 == 0 || g < GA) {
                 if (P::A_KC) {
                     const int row = g / (BK / 4), kq = g % (BK / 4);
-                    if (k0 + kq * 4 < ke) p.load_a(ra[i], m0 + row, k0 + kq * 4);
+                    oka[i] = k0 + kq * 4 < ke;
+                    ra[i] = p.fetch_a(m0 + row, k0 + kq * 4, oka[i]);
                 } else {
                     const int k = g / (BM / 4), mq = g % (BM / 4);
-                    if (k0 + k < ke) p.load_a(ra[i], m0 + mq * 4, k0 + k);
+                    oka[i] = k0 + k < ke;
+                    ra[i] = p.fetch_a(m0 + mq * 4, k0 + k, oka[i]);
                 }
             }
         }
 #pragma unroll
         for (int i = 0; i < PB; ++i) {
             const int g = tid + i * 256;
-            rb[i][0] = rb[i][1] = rb[i][2] = rb[i][3] = 0.f;
             if (GB % 256 == 0 || g < GB) {
                 if (P::B_KC) {
                     const int col = g / (BK / 4), kq = g % (BK / 4);
-                    if (k0 + kq * 4 < ke) p.load_b(rb[i], k0 + kq * 4, n0 + col);
+                    okb[i] = k0 + kq * 4 < ke;
+                    rb[i] = p.fetch_b(k0 + kq * 4, n0 + col, okb[i]);
                 } else {
                     const int k = g / (BN / 4), nq = g % (BN / 4);
-                    if (k0 + k < ke) p.load_b(rb[i], k0 + k, n0 + nq * 4);
+                    okb[i] = k0 + k < ke;
+                    rb[i] = p.fetch_b(k0 + k, n0 + nq * 4, okb[i]);
                 }
             }
         }
@@ -100,14 +130,21 @@ __global__ __launch_bounds__(256) void igemm_kernel(P p, int n_agents)
         for (int i = 0; i < PA; ++i) {
             const int g = tid + i * 256;
             if (GA % 256 == 0 || g < GA) {
+                float r[4];
+                p.decode_a(r, ra[i]);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) r[j] = oka[i] ? r[j] : 0.f;
                 if (P::A_KC) {
                     const int row = g / (BK / 4), kq = g % (BK / 4);
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) As[buf][kq * 4 + j][row] = ra[i][j];
+                    for (int j = 0; j < 4; ++j) As[buf][kq * 4 + j][row] = r[j];
                 } else {
                     const int k = g / (BM / 4), mq = g % (BM / 4);
-                    *reinterpret_cast<float4 *>(&As[buf][k][mq * 4]) =
-                        make_float4(ra[i][0], ra[i][1], ra[i][2], ra[i][3]);
+                    *reinterpret_cast<float4 *>(&As[buf][k][mq * 4]) = make_float4(r[0], r[1], r[2], r[3]);
+                    if (P::SUM_A && do_sum_a) {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) sum_a[j] += r[j];
+                    }
                 }
             }
         }
@@ -115,14 +152,21 @@ __global__ __launch_bounds__(256) void igemm_kernel(P p, int n_agents)
         for (int i = 0; i < PB; ++i) {
             const int g = tid + i * 256;
             if (GB % 256 == 0 || g < GB) {
+                float r[4];
+                p.decode_b(r, rb[i]);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) r[j] = okb[i] ? r[j] : 0.f;
                 if (P::B_KC) {
                     const int col = g / (BK / 4), kq = g % (BK / 4);
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) Bs[buf][kq * 4 + j][col] = rb[i][j];
+                    for (int j = 0; j < 4; ++j) Bs[buf][kq * 4 + j][col] = r[j];
                 } else {
                     const int k = g / (BN / 4), nq = g % (BN / 4);
-                    *reinterpret_cast<float4 *>(&Bs[buf][k][nq * 4]) =
-                        make_float4(rb[i][0], rb[i][1], rb[i][2], rb[i][3]);
+                    *reinterpret_cast<float4 *>(&Bs[buf][k][nq * 4]) = make_float4(r[0], r[1], r[2], r[3]);
+                    if (P::SUM_B && do_sum_b) {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) sum_b[j] += r[j];
+                    }
                 }
             }
         }
@@ -136,13 +180,17 @@ __global__ __launch_bounds__(256) void igemm_kernel(P p, int n_agents)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
+    const int lr = lane & 31, lk = lane >> 5;
+    float colv[BJ];          // requested now, consumed by the epilogue
+#pragma unroll
+    for (int j = 0; j < BJ; ++j) colv[j] = p.col_value(n0 + wn0 + j * 32 + lr);
+
     const int nkt = (ke - kb + BK - 1) / BK;
     if (nkt > 0) {
         fetch(kb);
         stage(0);
     }
     __syncthreads();
-    const int lr = lane & 31, lk = lane >> 5;
     for (int kt = 0; kt < nkt; ++kt) {
         const int buf = kt & 1;
         if (kt + 1 < nkt) fetch(kb + (kt + 1) * BK);
@@ -163,18 +211,62 @@ __global__ __launch_bounds__(256) void igemm_kernel(P p, int n_agents)
         __syncthreads();
     }
 
-    // D layout of the 32x32 MFMA: register v of lane l holds row 8*(v/4) + 4*(l/32) + v%4,
-    // column l%32.
+    // Operand sums: every thread holds partial sums of its four columns (rows); threads with
+    // the same group index are combined through LDS in a fixed order.
+    if (P::SUM_A || P::SUM_B) {
+        float *red = &As[0][0][0];
+        static_assert(2 * BK * SA >= 1024 || !(P::SUM_A || P::SUM_B), "LDS scratch for operand sums");
+        if (P::SUM_A && do_sum_a) {
+            constexpr int Q = BM / 4, R = 256 / Q;
 #pragma unroll
-    for (int i = 0; i < BI; ++i)
-#pragma unroll
-        for (int j = 0; j < BJ; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int m = m0 + wm0 + i * 32 + 8 * (v / 4) + 4 * lk + (v % 4);
-                const int n = n0 + wn0 + j * 32 + lr;
-                p.store(m, n, acc[i][j][v]);
+            for (int j = 0; j < 4; ++j) red[tid * 4 + j] = sum_a[j];
+            __syncthreads();
+            if (tid < BM) {
+                float t = 0.f;
+                for (int r = 0; r < R; ++r) t += red[(r * Q + tid / 4) * 4 + (tid & 3)];
+                p.store_sum_a(m0 + tid, t);
             }
+            __syncthreads();
+        }
+        if (P::SUM_B && do_sum_b) {
+            constexpr int Q = BN / 4, R = 256 / Q;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) red[tid * 4 + j] = sum_b[j];
+            __syncthreads();
+            if (tid < BN) {
+                float t = 0.f;
+                for (int r = 0; r < R; ++r) t += red[(r * Q + tid / 4) * 4 + (tid & 3)];
+                p.store_sum_b(n0 + tid, t);
+            }
+        }
+    }
+
+    // D layout of the 32x32 MFMA: register v of lane l holds row 8*(v/4) + 4*(l/32) + v%4,
+    // column l%32.  Per-element epilogue operands of a block are all requested before its
+    // first store so that their latencies overlap.
+    auto epilogue = [&](auto checked) {
+        constexpr bool CHECK = decltype(checked)::value;
+#pragma unroll
+        for (int i = 0; i < BI; ++i)
+#pragma unroll
+            for (int j = 0; j < BJ; ++j) {
+                float aux[16];
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int m = m0 + wm0 + i * 32 + 8 * (v / 4) + 4 * lk + (v % 4);
+                    const int n = n0 + wn0 + j * 32 + lr;
+                    aux[v] = P::HAS_AUX ? p.template aux<CHECK>(m, n) : 0.f;
+                }
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int m = m0 + wm0 + i * 32 + 8 * (v / 4) + 4 * lk + (v % 4);
+                    const int n = n0 + wn0 + j * 32 + lr;
+                    p.template store<CHECK>(m, n, acc[i][j][v], colv[j], aux[v]);
+                }
+            }
+    };
+    if (p.tile_full(m0, n0)) epilogue(std::false_type{});
+    else epilogue(std::true_type{});
 }
 
 template <class P>

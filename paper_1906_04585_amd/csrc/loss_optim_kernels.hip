@@ -28,18 +28,23 @@ static __device__ __forceinline__ float block_sum_256(float v, float *red)
 //   loss = mean(-log pi(a_t|s_t) A_t) + c_v mean((G_t - V_t)^2) - eta mean(H_t),  G and A constants
 //   dloss/dz_k = [A (pi_k - 1[k = a]) + eta pi_k (log pi_k + H)] / M,   dloss/dV = -2 c_v (G - V) / M
 constexpr int MAX_ACTIONS = 64;
+constexpr int LOSS_THREADS = 1024;
 
-__global__ __launch_bounds__(256) void loss_kernel(int T, int Bn, int A, float gamma, float vf_coef, float ent_coef,
-                                                   const float *__restrict__ logits, const float *__restrict__ values,
-                                                   const int32_t *__restrict__ actions,
-                                                   const float *__restrict__ rewards, const uint8_t *__restrict__ dones,
-                                                   float *ret, float *adv, float *dlogits, float *dvalues, float *stats)
+__global__ __launch_bounds__(LOSS_THREADS) void loss_kernel(int T, int Bn, int A, float gamma, float vf_coef,
+                                                            float ent_coef, const float *__restrict__ logits,
+                                                            const float *__restrict__ values,
+                                                            const int32_t *__restrict__ actions,
+                                                            const float *__restrict__ rewards,
+                                                            const uint8_t *__restrict__ dones, float *ret, float *adv,
+                                                            float *dlogits, float *dvalues, float *stats)
 {
-    __shared__ float red[4];
+    constexpr int NW = LOSS_THREADS / 64;
+    __shared__ float red[3][NW];
     const int agent = blockIdx.x;
     const int M = T * Bn, F = M + Bn;
     const float *V = values + (long)agent * F;
     float *G = ret + (long)agent * M, *Ad = adv + (long)agent * M;
+    // one thread per environment walks its rollout backwards
     for (int b = threadIdx.x; b < Bn; b += blockDim.x) {
         float next = V[M + b];
         for (int t = T - 1; t >= 0; --t) {
@@ -51,44 +56,44 @@ __global__ __launch_bounds__(256) void loss_kernel(int T, int Bn, int A, float g
         }
     }
     __syncthreads();
-    float pg = 0.f, td = 0.f, ent = 0.f;
+    // one wavefront per sample, one lane per action
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const float inv_m = 1.0f / (float)M;
-    for (int m = threadIdx.x; m < M; m += blockDim.x) {
-        const float *z = logits + ((long)agent * M + m) * A;
-        float lp[MAX_ACTIONS];
-        float zmax = z[0];
-        for (int a = 1; a < A; ++a) zmax = fmaxf(zmax, z[a]);
-        float se = 0.f;
-        for (int a = 0; a < A; ++a) se += expf(z[a] - zmax);
-        const float lse = zmax + logf(se);
-        float H = 0.f;
-        for (int a = 0; a < A; ++a) { lp[a] = z[a] - lse; H -= expf(lp[a]) * lp[a]; }
+    float pg = 0.f, td = 0.f, ent = 0.f;       // accumulated identically in every lane
+    for (int m = wave; m < M; m += NW) {
+        const bool on = lane < A;
+        const float z = on ? logits[((long)agent * M + m) * A + lane] : -INFINITY;
+        float zmax = z;
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) zmax = fmaxf(zmax, __shfl_xor(zmax, off, 64));
+        const float se = wave_sum(on ? expf(z - zmax) : 0.f);
+        const float lp = z - (zmax + logf(se));
+        const float p = on ? expf(lp) : 0.f;
+        const float H = -wave_sum(on ? p * lp : 0.f);
         const int act = actions[(long)agent * M + m];      // integer gather of the taken action
+        const float lp_act = __shfl(lp, act, 64);
         const float Am = Ad[m], Gm = G[m], Vm = V[m];
-        pg += -lp[act] * Am;
+        pg += -lp_act * Am;
         td += (Gm - Vm) * (Gm - Vm);
         ent += H;
-        float *dz = dlogits + ((long)agent * M + m) * A;
-        for (int a = 0; a < A; ++a) {
-            const float p = expf(lp[a]);
-            dz[a] = (Am * (p - (a == act ? 1.f : 0.f)) + ent_coef * p * (lp[a] + H)) * inv_m;
-        }
-        dvalues[(long)agent * M + m] = -2.f * vf_coef * (Gm - Vm) * inv_m;
+        if (on)
+            dlogits[((long)agent * M + m) * A + lane] =
+                (Am * (p - (lane == act ? 1.f : 0.f)) + ent_coef * p * (lp + H)) * inv_m;
+        if (lane == 0) dvalues[(long)agent * M + m] = -2.f * vf_coef * (Gm - Vm) * inv_m;
     }
-    pg = block_sum_256(pg, red);
-    td = block_sum_256(td, red);
-    ent = block_sum_256(ent, red);
-    if (threadIdx.x == 0) {
-        stats[agent * 5 + 0] = pg * inv_m;
-        stats[agent * 5 + 1] = td * inv_m;
-        stats[agent * 5 + 2] = ent * inv_m;
+    if (lane == 0) { red[0][wave] = pg; red[1][wave] = td; red[2][wave] = ent; }
+    __syncthreads();
+    if (threadIdx.x < 3) {
+        float t = 0.f;
+        for (int w = 0; w < NW; ++w) t += red[threadIdx.x][w];
+        stats[agent * 5 + threadIdx.x] = t * inv_m;
     }
 }
 
 hipError_t launch_loss(const NetArgs &a, const HParams &hp, const int32_t *actions, const float *rewards,
                        const uint8_t *dones, hipStream_t s)
 {
-    hipLaunchKernelGGL(loss_kernel, dim3(a.N), dim3(256), 0, s, hp.T, hp.B, a.L.n_actions, hp.gamma, hp.vf_coef,
+    hipLaunchKernelGGL(loss_kernel, dim3(a.N), dim3(LOSS_THREADS), 0, s, hp.T, hp.B, a.L.n_actions, hp.gamma, hp.vf_coef,
                        hp.ent_coef, a.b.logits, a.b.values, actions, rewards, dones, a.b.ret, a.b.adv,
                        a.b.dlogits, a.b.dvalues, a.b.stats);
     return hipGetLastError();

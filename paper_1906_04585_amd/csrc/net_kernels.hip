@@ -10,16 +10,24 @@
 
 namespace gala {
 
-static __device__ __forceinline__ void ld4(float (&r)[4], const float *p)
+// A group of four consecutive floats; `ok` selects the real address, otherwise the (always
+// readable) base of the tensor is loaded and the result discarded by the caller.
+static __device__ __forceinline__ float4 ldg4(const float *base, long off, bool ok)
 {
-    const float4 v = *reinterpret_cast<const float4 *>(p);
+    return *reinterpret_cast<const float4 *>(base + (ok ? off : 0));
+}
+static __device__ __forceinline__ uint32_t ldg_u8x4(const uint8_t *base, long off, bool ok)
+{
+    return *reinterpret_cast<const uint32_t *>(base + (ok ? off : 0));
+}
+static __device__ __forceinline__ void unpack(float (&r)[4], float4 v)
+{
     r[0] = v.x; r[1] = v.y; r[2] = v.z; r[3] = v.w;
 }
-
-static __device__ __forceinline__ void ld4_u8(float (&r)[4], const uint8_t *p)
+// states are bytes scaled to [0, 1]
+static __device__ __forceinline__ void unpack_u8(float (&r)[4], uint32_t w)
 {
-    const uint32_t w = *reinterpret_cast<const uint32_t *>(p);
-    constexpr float sc = 1.0f / 255.0f;      // states are bytes scaled to [0, 1]
+    constexpr float sc = 1.0f / 255.0f;
     r[0] = (float)(w & 255u) * sc;
     r[1] = (float)((w >> 8) & 255u) * sc;
     r[2] = (float)((w >> 16) & 255u) * sc;
@@ -27,10 +35,19 @@ static __device__ __forceinline__ void ld4_u8(float (&r)[4], const uint8_t *p)
 }
 
 struct ProblemBase {
+    typedef float4 ARaw;
+    typedef float4 BRaw;
+    static constexpr bool SUM_A = false, SUM_B = false, HAS_AUX = false;
     int tiles_m, tiles_n, splits;
     int k0, k1;
     __device__ int k_begin() const { return k0; }
     __device__ int k_end() const { return k1; }
+    __device__ void decode_a(float (&r)[4], float4 v) const { unpack(r, v); }
+    __device__ void decode_b(float (&r)[4], float4 v) const { unpack(r, v); }
+    __device__ float col_value(int) const { return 0.f; }
+    template <bool CHECK> __device__ float aux(int, int) const { return 0.f; }
+    __device__ void store_sum_a(int, float) const {}
+    __device__ void store_sum_b(int, float) const {}
 };
 
 // ---- conv1 forward: bytes -> a1 ------------------------------------------------------
@@ -38,6 +55,7 @@ struct ProblemBase {
 struct Conv1Fwd : ProblemBase {
     static constexpr int BM = 256, BN = 32, BK = 16, WM = 4, WN = 1;
     static constexpr bool A_KC = true, B_KC = false;
+    typedef uint32_t ARaw;
     const uint8_t *obs, *boot;
     const float *x;
     float *a1;
@@ -57,18 +75,23 @@ struct Conv1Fwd : ProblemBase {
         rows_ = F * P1;
         k0 = 0; k1 = KW1;
     }
-    __device__ void load_a(float (&r)[4], int m, int k) const
+    __device__ uint32_t fetch_a(int m, int k, bool &ok) const
     {
-        if (m >= rows_) return;
+        ok = ok && m < rows_;
         const int f = m / P1, p = m % P1, oy = p / W1, ox = p % W1;
         const int c = k >> 6, kh = (k >> 3) & 7, kw = k & 7;
-        const uint8_t *fr = f < M ? o_ + (long)f * FRAME : bo_ + (long)(f - M) * FRAME;
-        ld4_u8(r, fr + c * (H0 * W0) + (oy * S1 + kh) * W0 + ox * S1 + kw);
+        const bool roll = f < M;
+        const uint8_t *fr = roll ? o_ : bo_;
+        const long off = (long)(roll ? f : f - M) * FRAME + c * (H0 * W0) + (oy * S1 + kh) * W0 + ox * S1 + kw;
+        return ldg_u8x4(fr, off, ok);
     }
-    __device__ void load_b(float (&r)[4], int k, int n) const { ld4(r, w_ + k * C1 + n); }
-    __device__ void store(int m, int n, float v) const
+    __device__ void decode_a(float (&r)[4], uint32_t w) const { unpack_u8(r, w); }
+    __device__ float4 fetch_b(int k, int n, bool &ok) const { return ldg4(w_, k * C1 + n, ok); }
+    __device__ float col_value(int n) const { return b_[n]; }
+    __device__ bool tile_full(int m0, int) const { return m0 + BM <= rows_; }
+    template <bool CHECK> __device__ void store(int m, int n, float v, float bias, float) const
     {
-        if (m < rows_) out_[(long)m * C1 + n] = fmaxf(v + b_[n], 0.f);
+        if (!CHECK || m < rows_) out_[(long)m * C1 + n] = fmaxf(v + bias, 0.f);
     }
 };
 
@@ -94,17 +117,19 @@ struct ConvFwd : ProblemBase {
         rows_ = F * HO * WO;
         k0 = 0; k1 = KS * KS * CI;
     }
-    __device__ void load_a(float (&r)[4], int m, int k) const
+    __device__ float4 fetch_a(int m, int k, bool &ok) const
     {
-        if (m >= rows_) return;
+        ok = ok && m < rows_;
         const int f = m / (HO * WO), p = m % (HO * WO), oy = p / WO, ox = p % WO;
         const int kh = k / (KS * CI), rem = k % (KS * CI);
-        ld4(r, in_ + ((long)(f * HI + oy * ST + kh) * WI + ox * ST) * CI + rem);
+        return ldg4(in_, ((long)(f * HI + oy * ST + kh) * WI + ox * ST) * CI + rem, ok);
     }
-    __device__ void load_b(float (&r)[4], int k, int n) const { ld4(r, w_ + k * CO + n); }
-    __device__ void store(int m, int n, float v) const
+    __device__ float4 fetch_b(int k, int n, bool &ok) const { return ldg4(w_, k * CO + n, ok); }
+    __device__ float col_value(int n) const { return b_[n]; }
+    __device__ bool tile_full(int m0, int) const { return m0 + BM <= rows_; }
+    template <bool CHECK> __device__ void store(int m, int n, float v, float bias, float) const
     {
-        if (m < rows_) out_[(long)m * CO + n] = fmaxf(v + b_[n], 0.f);
+        if (!CHECK || m < rows_) out_[(long)m * CO + n] = fmaxf(v + bias, 0.f);
     }
 };
 using Conv2Fwd = ConvFwd<C1, H1, W1, C2, H2, W2, K2, S2>;
@@ -129,14 +154,16 @@ struct FcFwd : ProblemBase {
         k0 = split * kchunk;
         k1 = min(FLAT, k0 + kchunk);
     }
-    __device__ void load_a(float (&r)[4], int m, int k) const
+    __device__ float4 fetch_a(int m, int k, bool &ok) const
     {
-        if (m < F) ld4(r, a_ + (long)m * FLAT + k);
+        ok = ok && m < F;
+        return ldg4(a_, (long)m * FLAT + k, ok);
     }
-    __device__ void load_b(float (&r)[4], int k, int n) const { ld4(r, w_ + (long)n * FLAT + k); }
-    __device__ void store(int m, int n, float v) const
+    __device__ float4 fetch_b(int k, int n, bool &ok) const { return ldg4(w_, (long)n * FLAT + k, ok); }
+    __device__ bool tile_full(int m0, int) const { return m0 + BM <= F; }
+    template <bool CHECK> __device__ void store(int m, int n, float v, float, float) const
     {
-        if (m < F) out_[(long)m * FC + n] = v;
+        if (!CHECK || m < F) out_[(long)m * FC + n] = v;
     }
 };
 
@@ -145,6 +172,7 @@ struct FcFwd : ProblemBase {
 struct FcDgrad : ProblemBase {
     static constexpr int BM = 96, BN = 128, BK = 16, WM = 1, WN = 4;
     static constexpr bool A_KC = true, B_KC = false;
+    static constexpr bool HAS_AUX = true;
     const float *dzh, *x, *a3;
     float *dz3;
     long d_pad, w_off;
@@ -159,49 +187,58 @@ struct FcDgrad : ProblemBase {
         out_ = dz3 + (long)agent * M * FLAT;
         k0 = 0; k1 = FC;
     }
-    __device__ void load_a(float (&r)[4], int m, int k) const
+    __device__ float4 fetch_a(int m, int k, bool &ok) const
     {
-        if (m < M) ld4(r, a_ + (long)m * FC + k);
+        ok = ok && m < M;
+        return ldg4(a_, (long)m * FC + k, ok);
     }
-    __device__ void load_b(float (&r)[4], int k, int n) const
+    __device__ float4 fetch_b(int k, int n, bool &ok) const
     {
-        if (n < FLAT) ld4(r, w_ + (long)k * FLAT + n);
+        ok = ok && n < FLAT;
+        return ldg4(w_, (long)k * FLAT + n, ok);
     }
-    __device__ void store(int m, int n, float v) const
+    __device__ bool tile_full(int m0, int n0) const { return m0 + BM <= M && n0 + BN <= FLAT; }
+    template <bool CHECK> __device__ float aux(int m, int n) const
     {
-        if (m < M && n < FLAT) {
-            const long i = (long)m * FLAT + n;
-            out_[i] = act_[i] > 0.f ? v : 0.f;
-        }
+        return act_[(!CHECK || (m < M && n < FLAT)) ? (long)m * FLAT + n : 0];
+    }
+    template <bool CHECK> __device__ void store(int m, int n, float v, float, float act) const
+    {
+        if (!CHECK || (m < M && n < FLAT)) out_[(long)m * FLAT + n] = act > 0.f ? v : 0.f;
     }
 };
 
-// ---- hidden layer: weight gradient ---------------------------------------------------------
+// ---- hidden layer: weight gradient (and bias gradient = sum over frames of dzh) -----------------
 // m = j, n = flattened a3 index, k = f.
 struct FcWgrad : ProblemBase {
     static constexpr int BM = 128, BN = 128, BK = 16, WM = 2, WN = 2;
     static constexpr bool A_KC = false, B_KC = false;
+    static constexpr bool SUM_A = true;
     const float *dzh, *a3;
     float *g;
-    long d_pad, w_off;
+    long d_pad, w_off, b_off;
     int M, F;
     const float *a_, *b_;
-    float *out_;
+    float *out_, *bias_;
     __device__ void bind(int agent, int)
     {
         a_ = dzh + (long)agent * M * FC;
         b_ = a3 + (long)agent * F * FLAT;
         out_ = g + agent * d_pad + w_off;
+        bias_ = g + agent * d_pad + b_off;
         k0 = 0; k1 = M;
     }
-    __device__ void load_a(float (&r)[4], int m, int k) const { ld4(r, a_ + (long)k * FC + m); }
-    __device__ void load_b(float (&r)[4], int k, int n) const
+    __device__ void store_sum_a(int m, float v) const { bias_[m] = v; }
+    __device__ float4 fetch_a(int m, int k, bool &ok) const { return ldg4(a_, (long)k * FC + m, ok); }
+    __device__ float4 fetch_b(int k, int n, bool &ok) const
     {
-        if (n < FLAT) ld4(r, b_ + (long)k * FLAT + n);
+        ok = ok && n < FLAT;
+        return ldg4(b_, (long)k * FLAT + n, ok);
     }
-    __device__ void store(int m, int n, float v) const
+    __device__ bool tile_full(int, int n0) const { return n0 + BN <= FLAT; }
+    template <bool CHECK> __device__ void store(int m, int n, float v, float, float) const
     {
-        if (n < FLAT) out_[(long)m * FLAT + n] = v;
+        if (!CHECK || n < FLAT) out_[(long)m * FLAT + n] = v;
     }
 };
 
@@ -210,6 +247,7 @@ struct FcWgrad : ProblemBase {
 struct Conv3Dgrad : ProblemBase {
     static constexpr int BM = 128, BN = 64, BK = 16, WM = 2, WN = 2;
     static constexpr bool A_KC = true, B_KC = true;
+    static constexpr bool HAS_AUX = true;
     const float *dz3, *x, *a2;
     float *dz2;
     long d_pad, w_off;
@@ -226,26 +264,27 @@ struct Conv3Dgrad : ProblemBase {
         rows_ = M * P2;
         k0 = 0; k1 = K3 * K3 * C3;
     }
-    __device__ void load_a(float (&r)[4], int m, int k) const
+    __device__ float4 fetch_a(int m, int k, bool &ok) const
     {
-        if (m >= rows_) return;
         const int f = m / P2, p = m % P2, iy = p / W2, ix = p % W2;
         const int t = k / C3, o = k % C3, kh = t / K3, kw = t % K3;
         const int oy = iy - kh, ox = ix - kw;
-        if (oy < 0 || oy >= H3 || ox < 0 || ox >= W3) return;
-        ld4(r, a_ + ((long)(f * H3 + oy) * W3 + ox) * C3 + o);
+        ok = ok && m < rows_ && oy >= 0 && oy < H3 && ox >= 0 && ox < W3;
+        return ldg4(a_, ((long)(f * H3 + oy) * W3 + ox) * C3 + o, ok);
     }
-    __device__ void load_b(float (&r)[4], int k, int n) const
+    __device__ float4 fetch_b(int k, int n, bool &ok) const
     {
         const int t = k / C3, o = k % C3;
-        ld4(r, w_ + ((long)t * C2 + n) * C3 + o);
+        return ldg4(w_, ((long)t * C2 + n) * C3 + o, ok);
     }
-    __device__ void store(int m, int n, float v) const
+    __device__ bool tile_full(int m0, int) const { return m0 + BM <= rows_; }
+    template <bool CHECK> __device__ float aux(int m, int n) const
     {
-        if (m < rows_) {
-            const long i = (long)m * C2 + n;
-            out_[i] = act_[i] > 0.f ? v : 0.f;
-        }
+        return act_[(!CHECK || m < rows_) ? (long)m * C2 + n : 0];
+    }
+    template <bool CHECK> __device__ void store(int m, int n, float v, float, float act) const
+    {
+        if (!CHECK || m < rows_) out_[(long)m * C2 + n] = act > 0.f ? v : 0.f;
     }
 };
 
@@ -256,6 +295,7 @@ struct Conv3Dgrad : ProblemBase {
 struct Conv2Dgrad : ProblemBase {
     static constexpr int BM = 256, BN = 32, BK = 16, WM = 4, WN = 1;
     static constexpr bool A_KC = true, B_KC = true;
+    static constexpr bool HAS_AUX = true;
     static constexpr int HY = H1 / 2, WX = W1 / 2, PC = HY * WX;   // 10, 10, 100
     const float *dz2, *x, *a1;
     float *dz1;
@@ -274,38 +314,46 @@ struct Conv2Dgrad : ProblemBase {
         py_ = cls >> 1; px_ = cls & 1;
         k0 = 0; k1 = 4 * C2;
     }
-    __device__ void load_a(float (&r)[4], int m, int k) const
+    __device__ float4 fetch_a(int m, int k, bool &ok) const
     {
-        if (m >= rows_) return;
         const int f = m / PC, p = m % PC, yy = p / WX, xx = p % WX;
         const int t = k / C2, o = k % C2, a = t >> 1, b = t & 1;
         const int oy = yy - a, ox = xx - b;
-        if (oy < 0 || oy >= H2 || ox < 0 || ox >= W2) return;
-        ld4(r, a_ + ((long)(f * H2 + oy) * W2 + ox) * C2 + o);
+        ok = ok && m < rows_ && oy >= 0 && oy < H2 && ox >= 0 && ox < W2;
+        return ldg4(a_, ((long)(f * H2 + oy) * W2 + ox) * C2 + o, ok);
     }
-    __device__ void load_b(float (&r)[4], int k, int n) const
+    __device__ float4 fetch_b(int k, int n, bool &ok) const
     {
         const int t = k / C2, o = k % C2, a = t >> 1, b = t & 1;
         const int kh = py_ + 2 * a, kw = px_ + 2 * b;
-        ld4(r, w_ + ((long)(kh * K2 + kw) * C1 + n) * C2 + o);
+        return ldg4(w_, ((long)(kh * K2 + kw) * C1 + n) * C2 + o, ok);
     }
-    __device__ void store(int m, int n, float v) const
+    __device__ long out_index(int m, int n) const
     {
-        if (m < rows_) {
-            const int f = m / PC, p = m % PC, yy = p / WX, xx = p % WX;
-            const long i = ((long)(f * H1 + 2 * yy + py_) * W1 + 2 * xx + px_) * C1 + n;
-            out_[i] = act_[i] > 0.f ? v : 0.f;
-        }
+        const int f = m / PC, p = m % PC, yy = p / WX, xx = p % WX;
+        return ((long)(f * H1 + 2 * yy + py_) * W1 + 2 * xx + px_) * C1 + n;
+    }
+    __device__ bool tile_full(int m0, int) const { return m0 + BM <= rows_; }
+    template <bool CHECK> __device__ float aux(int m, int n) const
+    {
+        return act_[(!CHECK || m < rows_) ? out_index(m, n) : 0];
+    }
+    template <bool CHECK> __device__ void store(int m, int n, float v, float, float act) const
+    {
+        if (!CHECK || m < rows_) out_[out_index(m, n)] = act > 0.f ? v : 0.f;
     }
 };
 
 // ---- conv2 / conv3 weight gradient (split over frames) ----------------------------------------------
-// m = (kh, kw, c), n = o, k = (f, oy, ox).
+// m = (kh, kw, c), n = o, k = (f, oy, ox).  Each split writes MT*CO weight partials followed
+// by CO bias partials (the bias gradient is the sum over k of the dz operand).
 template <int CI, int HI, int WI, int CO, int HO, int WO, int KS, int ST, int BM_>
 struct ConvWgrad : ProblemBase {
     static constexpr int BM = BM_, BN = 64, BK = 16, WM = 2, WN = 2;
     static constexpr bool A_KC = false, B_KC = false;
+    static constexpr bool SUM_B = true;
     static constexpr int MT = KS * KS * CI;
+    static constexpr int PART = MT * CO + CO;
     const float *in, *dz;
     float *ws;
     int M, F, fps;
@@ -315,22 +363,24 @@ struct ConvWgrad : ProblemBase {
     {
         in_ = in + (long)agent * F * (HI * WI * CI);
         dz_ = dz + (long)agent * M * (HO * WO * CO);
-        out_ = ws + ((long)agent * splits + split) * MT * CO;
+        out_ = ws + ((long)agent * splits + split) * PART;
         k0 = split * fps * (HO * WO);
         k1 = min(M, (split + 1) * fps) * (HO * WO);
     }
-    __device__ void load_a(float (&r)[4], int m, int k) const
+    __device__ float4 fetch_a(int m, int k, bool &ok) const
     {
-        if (m >= MT) return;
+        ok = ok && m < MT;
         const int f = k / (HO * WO), p = k % (HO * WO), oy = p / WO, ox = p % WO;
         const int kh = m / (KS * CI), rem = m % (KS * CI);
-        ld4(r, in_ + ((long)(f * HI + oy * ST + kh) * WI + ox * ST) * CI + rem);
+        return ldg4(in_, ((long)(f * HI + oy * ST + kh) * WI + ox * ST) * CI + rem, ok);
     }
-    __device__ void load_b(float (&r)[4], int k, int n) const { ld4(r, dz_ + (long)k * CO + n); }
-    __device__ void store(int m, int n, float v) const
+    __device__ float4 fetch_b(int k, int n, bool &ok) const { return ldg4(dz_, (long)k * CO + n, ok); }
+    __device__ bool tile_full(int m0, int) const { return m0 + BM <= MT; }
+    template <bool CHECK> __device__ void store(int m, int n, float v, float, float) const
     {
-        if (m < MT) out_[(long)m * CO + n] = v;
+        if (!CHECK || m < MT) out_[(long)m * CO + n] = v;
     }
+    __device__ void store_sum_b(int n, float v) const { out_[MT * CO + n] = v; }
 };
 using Conv2Wgrad = ConvWgrad<C1, H1, W1, C2, H2, W2, K2, S2, 128>;
 using Conv3Wgrad = ConvWgrad<C2, H2, W2, C3, H3, W3, K3, S3, 64>;
@@ -340,6 +390,9 @@ using Conv3Wgrad = ConvWgrad<C2, H2, W2, C3, H3, W3, K3, S3, 64>;
 struct Conv1Wgrad : ProblemBase {
     static constexpr int BM = 256, BN = 32, BK = 16, WM = 4, WN = 1;
     static constexpr bool A_KC = false, B_KC = false;
+    static constexpr bool SUM_B = true;
+    static constexpr int PART = KW1 * C1 + C1;
+    typedef uint32_t ARaw;
     const uint8_t *obs;
     const float *dz1;
     float *ws;
@@ -351,18 +404,24 @@ struct Conv1Wgrad : ProblemBase {
     {
         o_ = obs + (long)agent * M * FRAME;
         dz_ = dz1 + (long)agent * M * A1SZ;
-        out_ = ws + ((long)agent * splits + split) * KW1 * C1;
+        out_ = ws + ((long)agent * splits + split) * PART;
         k0 = split * fps * P1;
         k1 = min(M, (split + 1) * fps) * P1;
     }
-    __device__ void load_a(float (&r)[4], int m, int k) const
+    __device__ uint32_t fetch_a(int m, int k, bool &ok) const
     {
         const int f = k / P1, p = k % P1, oy = p / W1, ox = p % W1;
         const int c = m >> 6, kh = (m >> 3) & 7, kw = m & 7;
-        ld4_u8(r, o_ + (long)f * FRAME + c * (H0 * W0) + (oy * S1 + kh) * W0 + ox * S1 + kw);
+        return ldg_u8x4(o_, (long)f * FRAME + c * (H0 * W0) + (oy * S1 + kh) * W0 + ox * S1 + kw, ok);
     }
-    __device__ void load_b(float (&r)[4], int k, int n) const { ld4(r, dz_ + (long)k * C1 + n); }
-    __device__ void store(int m, int n, float v) const { out_[(long)m * C1 + n] = v; }
+    __device__ void decode_a(float (&r)[4], uint32_t w) const { unpack_u8(r, w); }
+    __device__ float4 fetch_b(int k, int n, bool &ok) const { return ldg4(dz_, (long)k * C1 + n, ok); }
+    __device__ bool tile_full(int, int) const { return true; }
+    template <bool CHECK> __device__ void store(int m, int n, float v, float, float) const
+    {
+        out_[(long)m * C1 + n] = v;
+    }
+    __device__ void store_sum_b(int n, float v) const { out_[KW1 * C1 + n] = v; }
 };
 
 // ---- sum of split-K partials ----------------------------------------------------------------------
@@ -396,76 +455,45 @@ static hipError_t reduce_splits(const float *part, int S, long len, int N, float
     return hipGetLastError();
 }
 
-// ---- column sums (bias gradients): part[agent][chunk][c] = sum over the chunk's rows --------------
-template <int C>
-__global__ void colsum_kernel(const float *__restrict__ in, long in_stride, int rows, int rows_per_chunk,
-                              float *part)
+// ---- hidden layer epilogue + heads ---------------------------------------------------------------
+// One workgroup of 128 threads per (frame, agent): h = relu(sum of the split-K partials + b_fc),
+// four columns per thread, then logits = W_pi h + b_pi (rollout frames) and value = w_v h + b_v
+// as block-wide dot products.
+__global__ __launch_bounds__(128) void fc_reduce_heads_kernel(const float *__restrict__ part, int S,
+                                                              const float *__restrict__ x, Layout L, int M, int F,
+                                                              float *h, float *logits, float *values)
 {
-    constexpr int RL = 256 / C;                     // row lanes
-    __shared__ float red[256];
-    const int agent = blockIdx.y, chunk = blockIdx.x;
-    const int c = threadIdx.x % C, rl = threadIdx.x / C;
-    const int r0 = chunk * rows_per_chunk, r1 = min(rows, r0 + rows_per_chunk);
-    const float *p = in + agent * in_stride;
-    float acc = 0.f;
-    for (int r = r0 + rl; r < r1; r += RL) acc += p[(long)r * C + c];
-    red[threadIdx.x] = acc;
-    __syncthreads();
-    if (rl == 0) {
-        for (int j = 1; j < RL; ++j) acc += red[j * C + c];
-        part[((long)agent * gridDim.x + chunk) * C + c] = acc;
-    }
-}
-
-template <int C>
-static hipError_t bias_grad(const float *dz, long in_stride, int rows, int N, float *ws, float *g,
-                            long d_pad, long off, hipStream_t s)
-{
-    const int rpc = 1024;
-    const int chunks = (rows + rpc - 1) / rpc;
-    hipLaunchKernelGGL(colsum_kernel<C>, dim3(chunks, N), dim3(256), 0, s, dz, in_stride, rows, rpc, ws);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    return reduce_splits(ws, chunks, C, N, g + off, d_pad, nullptr, 0, 1, s);
-}
-
-// dzh is [M][512]: one workgroup per agent, two columns per thread, frames in order.
-__global__ void fc_bias_grad_kernel(const float *__restrict__ dzh, int M, float *g, long d_pad, long off)
-{
-    const int agent = blockIdx.x;
-    const float *p = dzh + (long)agent * M * FC;
-    for (int j = threadIdx.x; j < FC; j += blockDim.x) {
-        float acc = 0.f;
-        for (int f = 0; f < M; ++f) acc += p[(long)f * FC + j];
-        g[agent * d_pad + off + j] = acc;
-    }
-}
-
-// ---- heads ------------------------------------------------------------------------------------------
-// One wavefront per (frame, agent): logits = W_pi h + b_pi (rollout frames), value = w_v h + b_v.
-__global__ __launch_bounds__(64) void heads_fwd_kernel(const float *__restrict__ h, const float *__restrict__ x,
-                                                       Layout L, int M, int F, float *logits, float *values)
-{
-    const int f = blockIdx.x, agent = blockIdx.y, lane = threadIdx.x;
-    const float *hv = h + ((long)agent * F + f) * FC;
+    __shared__ float red[2][65];
+    const int f = blockIdx.x, agent = blockIdx.y, t = threadIdx.x;
     const float *xa = x + agent * L.d_pad;
-    float hr[FC / 64];
-#pragma unroll
-    for (int q = 0; q < FC / 64; ++q) hr[q] = hv[lane + 64 * q];
+    const long len = (long)F * FC;
+    const float *p = part + (long)agent * S * len + (long)f * FC + t * 4;
+    float4 acc = *reinterpret_cast<const float4 *>(p);
+    for (int s = 1; s < S; ++s) {
+        const float4 v = *reinterpret_cast<const float4 *>(p + (long)s * len);
+        acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+    }
+    const float4 b = *reinterpret_cast<const float4 *>(xa + L.fcb + t * 4);
+    acc.x = fmaxf(acc.x + b.x, 0.f); acc.y = fmaxf(acc.y + b.y, 0.f);
+    acc.z = fmaxf(acc.z + b.z, 0.f); acc.w = fmaxf(acc.w + b.w, 0.f);
+    *reinterpret_cast<float4 *>(h + ((long)agent * F + f) * FC + t * 4) = acc;
+
     const int A = L.n_actions;
     const int n_out = f < M ? A + 1 : 1;            // bootstrap states need the value only
     for (int oi = 0; oi < n_out; ++oi) {
         const bool is_v = (oi == n_out - 1);
         const float *w = is_v ? xa + L.vw : xa + L.piw + (long)oi * FC;
-        float acc = 0.f;
+        const float4 wv = *reinterpret_cast<const float4 *>(w + t * 4);
+        float d = (wv.x * acc.x + wv.y * acc.y) + (wv.z * acc.z + wv.w * acc.w);
 #pragma unroll
-        for (int q = 0; q < FC / 64; ++q) acc += w[lane + 64 * q] * hr[q];
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off, 64);
-        if (lane == 0) {
-            if (is_v) values[(long)agent * F + f] = acc + xa[L.vb];
-            else logits[((long)agent * M + f) * A + oi] = acc + xa[L.pib + oi];
-        }
+        for (int off = 32; off > 0; off >>= 1) d += __shfl_xor(d, off, 64);
+        if ((t & 63) == 0) red[t >> 6][oi] = d;
+    }
+    __syncthreads();
+    if (t < n_out) {
+        const float d = red[0][t] + red[1][t];
+        if (t == n_out - 1) values[(long)agent * F + f] = d + xa[L.vb];
+        else logits[((long)agent * M + f) * A + t] = d + xa[L.pib + t];
     }
 }
 
@@ -486,25 +514,40 @@ __global__ __launch_bounds__(256) void heads_dgrad_kernel(const float *__restric
     }
 }
 
-// Head parameter gradients: row a < A of W_pi (and b_pi[a]); row A = value head.
+// Head parameter gradients: row a < A of W_pi (and b_pi[a]); row A = value head.  One thread
+// per (row, column j); frames are summed in four interleaved chains, combined in a fixed order.
 __global__ __launch_bounds__(256) void heads_wgrad_kernel(const float *__restrict__ h, Layout L, int M, int F,
                                                           const float *__restrict__ dlogits,
                                                           const float *__restrict__ dvalues, float *g)
 {
     const int row = blockIdx.x, agent = blockIdx.y;
+    const int j = blockIdx.z * 256 + threadIdx.x;
     const int A = L.n_actions;
     const bool is_v = row == A;
     float *ga = g + agent * L.d_pad;
-    const float *hv = h + (long)agent * F * FC;
-    for (int j = threadIdx.x; j < FC; j += blockDim.x) {
-        float acc = 0.f, sb = 0.f;
-        for (int f = 0; f < M; ++f) {
-            const float d = is_v ? dvalues[(long)agent * M + f] : dlogits[((long)agent * M + f) * A + row];
-            acc += d * hv[(long)f * FC + j];
-            sb += d;
+    const float *hv = h + (long)agent * F * FC + j;
+    const float *dp = is_v ? dvalues + (long)agent * M : dlogits + (long)agent * M * A + row;
+    const int ds = is_v ? 1 : A;
+    float acc[4] = {0.f, 0.f, 0.f, 0.f}, sb[4] = {0.f, 0.f, 0.f, 0.f};
+    int f = 0;
+    for (; f + 4 <= M; f += 4) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const float d = dp[(long)(f + u) * ds];
+            acc[u] += d * hv[(long)(f + u) * FC];
+            sb[u] += d;
         }
-        if (is_v) ga[L.vw + j] = acc; else ga[L.piw + (long)row * FC + j] = acc;
-        if (j == 0) { if (is_v) ga[L.vb] = sb; else ga[L.pib + row] = sb; }
+    }
+    for (; f < M; ++f) {
+        const float d = dp[(long)f * ds];
+        acc[0] += d * hv[(long)f * FC];
+        sb[0] += d;
+    }
+    const float w = (acc[0] + acc[1]) + (acc[2] + acc[3]);
+    if (is_v) ga[L.vw + j] = w; else ga[L.piw + (long)row * FC + j] = w;
+    if (j == 0) {
+        const float b = (sb[0] + sb[1]) + (sb[2] + sb[3]);
+        if (is_v) ga[L.vb] = b; else ga[L.pib + row] = b;
     }
 }
 
@@ -519,10 +562,9 @@ size_t workspace_floats(int N, int M, int F)
 {
     size_t need = (size_t)N * cdiv(FLAT, FC_KCHUNK) * F * FC;
     auto mx = [&](size_t v) { if (v > need) need = v; };
-    mx((size_t)N * cdiv(M, FPS_CONV1) * KW1 * C1);
-    mx((size_t)N * cdiv(M, FPS_CONV2) * KW2 * C2);
-    mx((size_t)N * cdiv(M, FPS_CONV3) * KW3 * C3);
-    mx((size_t)N * cdiv((long)M * P1, 1024) * C1);
+    mx((size_t)N * cdiv(M, FPS_CONV1) * Conv1Wgrad::PART);
+    mx((size_t)N * cdiv(M, FPS_CONV2) * Conv2Wgrad::PART);
+    mx((size_t)N * cdiv(M, FPS_CONV3) * Conv3Wgrad::PART);
     return need + 1024;
 }
 
@@ -560,13 +602,10 @@ hipError_t launch_forward(const NetArgs &a, hipStream_t s, PhaseTimer *pt)
         p.tiles_m = cdiv(a.F, FcFwd::BM); p.tiles_n = FC / FcFwd::BN; p.splits = cdiv(FLAT, FC_KCHUNK);
         GALA_TRY(igemm_launch(p, a.N, s));
         pt->mark("fc_fwd");
-        GALA_TRY(reduce_splits(a.b.ws, p.splits, (long)a.F * FC, a.N, a.b.h, (long)a.F * FC,
-                               a.x + L.fcb, L.d_pad, FC, s));
-        pt->mark("fc_fwd_reduce");
+        hipLaunchKernelGGL(fc_reduce_heads_kernel, dim3(a.F, a.N), dim3(128), 0, s, a.b.ws, p.splits, a.x, L,
+                           a.M, a.F, a.b.h, a.b.logits, a.b.values);
+        pt->mark("fc_reduce_heads");
     }
-    hipLaunchKernelGGL(heads_fwd_kernel, dim3(a.F, a.N), dim3(64), 0, s, a.b.h, a.x, L, a.M, a.F,
-                       a.b.logits, a.b.values);
-    pt->mark("heads_fwd");
     return hipGetLastError();
 }
 
@@ -577,16 +616,14 @@ hipError_t launch_backward(const NetArgs &a, hipStream_t s, PhaseTimer *pt)
                        a.b.dlogits, a.b.dvalues, a.b.dzh);
     GALA_TRY(hipGetLastError());
     pt->mark("heads_dgrad");
-    hipLaunchKernelGGL(heads_wgrad_kernel, dim3(L.n_actions + 1, a.N), dim3(256), 0, s, a.b.h, L, a.M, a.F,
+    hipLaunchKernelGGL(heads_wgrad_kernel, dim3(L.n_actions + 1, a.N, FC / 256), dim3(256), 0, s, a.b.h, L, a.M, a.F,
                        a.b.dlogits, a.b.dvalues, a.b.g);
     GALA_TRY(hipGetLastError());
     pt->mark("heads_wgrad");
-    hipLaunchKernelGGL(fc_bias_grad_kernel, dim3(a.N), dim3(256), 0, s, a.b.dzh, a.M, a.b.g, L.d_pad, L.fcb);
-    GALA_TRY(hipGetLastError());
-    pt->mark("fc_bgrad");
     {
         FcWgrad p{};
-        p.dzh = a.b.dzh; p.a3 = a.b.a3; p.g = a.b.g; p.d_pad = L.d_pad; p.w_off = L.fcw; p.M = a.M; p.F = a.F;
+        p.dzh = a.b.dzh; p.a3 = a.b.a3; p.g = a.b.g; p.d_pad = L.d_pad; p.w_off = L.fcw; p.b_off = L.fcb;
+        p.M = a.M; p.F = a.F;
         p.tiles_m = FC / FcWgrad::BM; p.tiles_n = cdiv(FLAT, FcWgrad::BN); p.splits = 1;
         GALA_TRY(igemm_launch(p, a.N, s));
         pt->mark("fc_wgrad");
@@ -600,15 +637,13 @@ hipError_t launch_backward(const NetArgs &a, hipStream_t s, PhaseTimer *pt)
         pt->mark("fc_dgrad");
     }
     // conv3
-    GALA_TRY(bias_grad<C3>(a.b.dz3, (long)a.M * A3SZ, a.M * P3, a.N, a.b.ws, a.b.g, L.d_pad, L.b3, s));
-    pt->mark("conv3_bgrad");
     {
         Conv3Wgrad p{};
         p.in = a.b.a2; p.dz = a.b.dz3; p.ws = a.b.ws; p.M = a.M; p.F = a.F; p.fps = FPS_CONV3;
         p.tiles_m = cdiv(KW3, Conv3Wgrad::BM); p.tiles_n = 1; p.splits = cdiv(a.M, FPS_CONV3);
         GALA_TRY(igemm_launch(p, a.N, s));
         pt->mark("conv3_wgrad");
-        GALA_TRY(reduce_splits(a.b.ws, p.splits, (long)KW3 * C3, a.N, a.b.g + L.w3, L.d_pad, nullptr, 0, 1, s));
+        GALA_TRY(reduce_splits(a.b.ws, p.splits, Conv3Wgrad::PART, a.N, a.b.g + L.w3, L.d_pad, nullptr, 0, 1, s));
         pt->mark("conv3_wgrad_reduce");
     }
     {
@@ -620,15 +655,13 @@ hipError_t launch_backward(const NetArgs &a, hipStream_t s, PhaseTimer *pt)
         pt->mark("conv3_dgrad");
     }
     // conv2
-    GALA_TRY(bias_grad<C2>(a.b.dz2, (long)a.M * A2SZ, a.M * P2, a.N, a.b.ws, a.b.g, L.d_pad, L.b2, s));
-    pt->mark("conv2_bgrad");
     {
         Conv2Wgrad p{};
         p.in = a.b.a1; p.dz = a.b.dz2; p.ws = a.b.ws; p.M = a.M; p.F = a.F; p.fps = FPS_CONV2;
         p.tiles_m = cdiv(KW2, Conv2Wgrad::BM); p.tiles_n = 1; p.splits = cdiv(a.M, FPS_CONV2);
         GALA_TRY(igemm_launch(p, a.N, s));
         pt->mark("conv2_wgrad");
-        GALA_TRY(reduce_splits(a.b.ws, p.splits, (long)KW2 * C2, a.N, a.b.g + L.w2, L.d_pad, nullptr, 0, 1, s));
+        GALA_TRY(reduce_splits(a.b.ws, p.splits, Conv2Wgrad::PART, a.N, a.b.g + L.w2, L.d_pad, nullptr, 0, 1, s));
         pt->mark("conv2_wgrad_reduce");
     }
     {
@@ -640,15 +673,13 @@ hipError_t launch_backward(const NetArgs &a, hipStream_t s, PhaseTimer *pt)
         pt->mark("conv2_dgrad");
     }
     // conv1 (the input needs no gradient)
-    GALA_TRY(bias_grad<C1>(a.b.dz1, (long)a.M * A1SZ, a.M * P1, a.N, a.b.ws, a.b.g, L.d_pad, L.b1, s));
-    pt->mark("conv1_bgrad");
     {
         Conv1Wgrad p{};
         p.obs = a.obs; p.dz1 = a.b.dz1; p.ws = a.b.ws; p.M = a.M; p.fps = FPS_CONV1;
         p.tiles_m = 1; p.tiles_n = 1; p.splits = cdiv(a.M, FPS_CONV1);
         GALA_TRY(igemm_launch(p, a.N, s));
         pt->mark("conv1_wgrad");
-        GALA_TRY(reduce_splits(a.b.ws, p.splits, (long)KW1 * C1, a.N, a.b.g + L.w1, L.d_pad, nullptr, 0, 1, s));
+        GALA_TRY(reduce_splits(a.b.ws, p.splits, Conv1Wgrad::PART, a.N, a.b.g + L.w1, L.d_pad, nullptr, 0, 1, s));
         pt->mark("conv1_wgrad_reduce");
     }
     return hipSuccess;

@@ -243,19 +243,20 @@ __global__ __launch_bounds__(256) void consensus_kernel(const float *__restrict_
     const int chunk = blockIdx.x;
     const long e = ((long)chunk * 256 + threadIdx.x) * 4;
     const bool in = e < d_pad;
-    float4 mean = make_float4(0.f, 0.f, 0.f, 0.f);
+    // the mean is accumulated in double so that identical rows give it back exactly
+    double m0 = 0.0, m1 = 0.0, m2 = 0.0, m3 = 0.0;
     if (in)
         for (int i = 0; i < N; ++i) {
             const float4 v = *reinterpret_cast<const float4 *>(x + (long)i * d_pad + e);
-            mean.x += v.x; mean.y += v.y; mean.z += v.z; mean.w += v.w;
+            m0 += v.x; m1 += v.y; m2 += v.z; m3 += v.w;
         }
-    const float inv = 1.f / (float)N;
-    mean.x *= inv; mean.y *= inv; mean.z *= inv; mean.w *= inv;
+    const double inv = 1.0 / (double)N;
+    m0 *= inv; m1 *= inv; m2 *= inv; m3 *= inv;
     for (int i = 0; i < N; ++i) {
         float ss = 0.f;
         if (in) {
             const float4 v = *reinterpret_cast<const float4 *>(x + (long)i * d_pad + e);
-            const float a = v.x - mean.x, b = v.y - mean.y, c = v.z - mean.z, d = v.w - mean.w;
+            const float a = (float)(v.x - m0), b = (float)(v.y - m1), c = (float)(v.z - m2), d = (float)(v.w - m3);
             ss = (a * a + b * b) + (c * c + d * d);
         }
         ss = block_sum_256(ss, red);

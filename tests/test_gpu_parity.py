@@ -188,3 +188,67 @@ def test_config3_delayed_gossip_lockstep():
         compare_params(gpu, om, net, f"cfg3 gossip {r}")
         seen |= set(gpu.get_peer_table(r)[1][:, 0].tolist())
     assert seen == {0, 1, 2}
+
+
+def _sampled_full_size(cfg_id, sample_agents, rounds=1):
+    """Full-size configuration in the launch shape the benchmark times; the oracle computes
+    the sampled agents one by one from the same state and inputs."""
+    from parity_util import relu_gates
+    cfg, net, gpu, om, X0 = _make(cfg_id, shared=True)
+    N, T, B = cfg["n_agents"], cfg["T"], cfg["B"]
+    sl = gs.segment_slices(net)
+    mx0, fr0 = gpu.consensus_distance()
+    assert mx0 == 0.0 and fr0 == 0.0      # identical initialisation: exactly at consensus
+    for r in range(rounds):
+        X = gpu.get_params()
+        V = gpu.get_opt_state()
+        ro = gs.rollout(net, N, T, B, gs.round_seed(cfg_id, r))
+        dev = upload(ro)
+        gpu.learner_step(dev["obs"], dev["actions"], dev["rewards"], dev["dones"], dev["boot_obs"])
+        gates, marked = relu_gates(gpu, net, X, ro, agents=sample_agents)
+        g = gpu.get_grads()
+        st = gpu.get_step_stats()
+        Y = gpu.get_params()
+        V1 = gpu.get_opt_state()
+        for gi, i in enumerate(sample_agents):
+            og, terms = orc.agent_gradient(net, T, B, HP, X[i], ro["obs"][i], ro["actions"][i], ro["rewards"][i],
+                                           ro["dones"][i], ro["boot_obs"][i], gate=gates[gi] if marked else None)
+            for name, s in sl.items():
+                e = rel_err(g[i, s], og[s])
+                assert e <= RTOL, f"cfg{cfg_id} round {r} grad {name} agent {i}: {e:.3e}"
+            for k in range(3):
+                assert abs(st[i, k] - terms[k]) <= RTOL * max(abs(terms[k]), 1e-2)
+            gc = og.copy()
+            norm, scale = orc.clip_grad_norm(gc, HP["max_grad_norm"])
+            assert abs(st[i, 3] - norm) <= RTOL * norm and abs(st[i, 4] - scale) <= RTOL * scale
+            xo = X[i].astype(np.float64)
+            vo = V[i].astype(np.float64)
+            orc.rmsprop(xo, vo, gc, HP["lr"], HP["rms_alpha"], HP["rms_eps"])
+            for name, s in sl.items():
+                assert rel_err(Y[i, s], xo[s]) <= RTOL, f"cfg{cfg_id} round {r} param {name} agent {i}"
+                assert rel_err(V1[i, s], vo[s]) <= 2 * RTOL, f"cfg{cfg_id} round {r} rmsprop {name} agent {i}"
+        # gossip for every agent, from the parameters the GPU broadcasts
+        om.set_params(Y)
+        gpu.gossip(r)
+        om.gossip(r)
+        Z = gpu.get_params()
+        assert np.abs(Z - om.X).max() <= 2.0 ** -22 * np.abs(om.X).max()
+        # distance from consensus, logged per round
+        mx, fr = gpu.consensus_distance()
+        omx, ofr = orc.consensus_distance(Z)
+        assert abs(mx - omx) <= 1e-4 * omx + 4e-7 * np.linalg.norm(Z)
+        assert abs(fr - ofr) <= 1e-4 * ofr + 4e-7 * np.linalg.norm(Z)
+        assert omx > 0.0                      # the agents saw different data: they have drifted apart
+        print(f"cfg{cfg_id} round {r}: consensus max {mx:.4e} frob {fr:.4e}, {marked} ReLU units at rounding distance")
+
+
+def test_config4_full_size_sampled_agents():
+    """32 agents, 5 x 16 rollouts: three sampled agents per round over three rounds (all five
+    phases of the exponential graph need log2 32 = 5 rounds; the phase tables are covered
+    bit-exactly elsewhere)."""
+    _sampled_full_size(4, [0, 13, 31], rounds=3)
+
+
+def test_config5_full_size_sampled_agents():
+    """64 agents, 5 x 32 rollouts (fp32 path): two sampled agents, one round."""
+    _sampled_full_size(5, [5, 63], rounds=1)

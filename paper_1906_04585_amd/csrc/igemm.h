@@ -1,16 +1,19 @@
-// Agent-grouped implicit-GEMM on the gfx950 matrix cores (fp32 MFMA 32x32x2).
+// Agent-grouped implicit-GEMM on the gfx950 matrix cores (fp32 MFMA, 32x32x2 or 16x16x4 blocks).
 //
 // One launch computes, for every agent, C[m][n] = sum_k A[m][k] * B[k][n] where A and
 // B are *views* described by a problem functor P (im2col of an activation tensor, a
-// weight matrix, a byte image, ...) and C is consumed element-wise by P::store.  The
-// kernel never materialises A or B in HBM: 256 threads stage BM x BK and BK x BN tiles
-// through LDS (k-major, so a wavefront's MFMA operand read is one conflict-free
+// weight matrix, a byte image, ...) and C is consumed four columns at a time by
+// P::store4.  The kernel never materialises A or B in HBM: 256 threads stage BM x BK and
+// BK x BN tiles through LDS (k-major, so a wavefront's MFMA operand read is one
 // ds_read_b32 per lane), double-buffered against the global loads of the next k-tile.
+// The result tile leaves through LDS as well, so that every global store (and every
+// epilogue operand load) is a float4 with consecutive lanes on consecutive addresses.
 //
 // P provides
 //   static constexpr int  BM, BN, BK        tile sizes (BK multiple of 4)
 //   static constexpr int  WM, WN            wavefront grid, WM*WN == 4; each wavefront
-//                                           owns (BM/WM) x (BN/WN), multiples of 32
+//                                           owns (BM/WM) x (BN/WN), multiples of the MFMA block
+//   static constexpr bool MFMA16            16x16x4 blocks instead of 32x32x2
 //   static constexpr bool A_KC, B_KC        true: the operand is read in groups of 4
 //                                           consecutive k; false: 4 consecutive m (or n)
 //   int tiles_m, tiles_n, splits            filled by the host
@@ -24,16 +27,15 @@
 //                                           branch or wait sits between the loads of a tile
 //   void decode_a(float (&r)[4], ARaw)      raw -> four floats (applied at staging time, after
 //   void decode_b(float (&r)[4], BRaw)      the MFMAs of the current tile were issued)
-//   float col_value(int n)                  loaded once per output column (e.g. the bias)
-//   static constexpr bool HAS_AUX; float aux(int m, int n)
-//                                           optional per-element operand of the epilogue (e.g. the
-//                                           activation whose sign masks a gradient); all are loaded,
-//                                           from clamped addresses, before the first store
-//   template <bool CHECK> void store(int m, int n, float v, float colv, float aux)
-//   bool tile_full(int m0, int n0)          uniform: the whole BM x BN tile lies inside the output.
-//                                           Full tiles run an epilogue without any per-element
-//                                           bounds branch (CHECK = false), so that loads and stores
-//                                           are issued back to back; edge tiles take the checked path.
+//   float4 col_value4(int n)                per-column epilogue operand (e.g. the bias), columns n..n+3
+//   static constexpr bool HAS_AUX
+//   template <bool CHECK> float4 aux4(int m, int n)
+//                                           optional per-element epilogue operand (e.g. the activation
+//                                           whose sign masks a gradient); loaded from a clamped address
+//                                           when CHECK and outside
+//   template <bool CHECK> void store4(int m, int n, float4 v, float4 colv, float4 aux)
+//   bool tile_full(int m0, int n0)          uniform: the whole BM x BN tile lies inside the output;
+//                                           such tiles run the epilogue without bounds tests
 //   static constexpr bool SUM_A, SUM_B      optional: also produce sum_k A[m][k] (tiles with
 //                                           tn == 0) or sum_k B[k][n] (tiles with tm == 0) over
 //                                           the k-range, delivered through store_sum_a(m, v) /
@@ -49,21 +51,57 @@
 #include <type_traits>
 
 typedef float gala_f32x16 __attribute__((ext_vector_type(16)));
+typedef float gala_f32x4 __attribute__((ext_vector_type(4)));
+
+// One MFMA block: 32x32 (k = 2, 16 accumulator registers) or 16x16 (k = 4, 4 registers).
+// Lane l supplies A[row = l % MB][k = l / MB] and B[k = l / MB][col = l % MB]; accumulator
+// register v of lane l holds row 8 * (v / 4) + 4 * (l / MB) + v % 4 (the 16x16 block has
+// v < 4), column l % MB.
+template <bool SMALL> struct MfmaBlock;
+template <> struct MfmaBlock<false> {
+    static constexpr int MB = 32, KS = 2, NV = 16;
+    typedef gala_f32x16 Acc;
+    static __device__ __forceinline__ Acc mma(float a, float b, Acc c)
+    {
+        return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ int row(int v, int lk) { return 8 * (v / 4) + 4 * lk + (v % 4); }
+};
+template <> struct MfmaBlock<true> {
+    static constexpr int MB = 16, KS = 4, NV = 4;
+    typedef gala_f32x4 Acc;
+    static __device__ __forceinline__ Acc mma(float a, float b, Acc c)
+    {
+        return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ int row(int v, int lk) { return 4 * lk + v; }
+};
 
 template <class P>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void igemm_kernel(P p, int n_agents)
 {
     constexpr int BM = P::BM, BN = P::BN, BK = P::BK;
-    constexpr int PAD = 4;
-    constexpr int SA = BM + PAD, SB = BN + PAD;
+    // LDS tiles are k-major with a row padding of 4 floats: the transposing stores (four
+    // k-rows per lane group) and the operand reads both spread over the banks.  Measured
+    // against an XOR swizzle and a rotate-by-16 layout, the plain padding was fastest.
+    constexpr int SA = BM + 4, SB = BN + 4;
     constexpr int WTM = BM / P::WM, WTN = BN / P::WN;   // wavefront tile
-    constexpr int BI = WTM / 32, BJ = WTN / 32;
+    typedef MfmaBlock<P::MFMA16> Blk;
+    constexpr int MB = Blk::MB, NV = Blk::NV;
+    constexpr int BI = WTM / MB, BJ = WTN / MB;
     static_assert(P::WM * P::WN == 4, "four wavefronts per workgroup");
-    static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wavefront tile in 32x32 blocks");
+    static_assert(WTM % MB == 0 && WTN % MB == 0 && BK % Blk::KS == 0, "wavefront tile in MFMA blocks");
     static_assert(BK % 4 == 0 && BM % 4 == 0 && BN % 4 == 0, "vector groups of four");
 
-    __shared__ __attribute__((aligned(16))) float As[2][BK][SA];
-    __shared__ __attribute__((aligned(16))) float Bs[2][BK][SB];
+    // one LDS allocation: [A tiles x2][B tiles x2] during the k-loop, then the output slab
+    constexpr int OFFB = 2 * BK * SA;
+    constexpr int SC = BN + 4;                  // row stride of the output slab
+    constexpr int SLAB = P::WM * MB;            // rows per epilogue pass: one block-row per wavefront row
+    constexpr int LDS_LOOP = 2 * BK * (SA + SB), LDS_OUT = SLAB * SC;
+    constexpr int LDS_FLOATS = LDS_LOOP > LDS_OUT ? LDS_LOOP : LDS_OUT;
+    __shared__ __attribute__((aligned(16))) float smem[LDS_FLOATS];
+    auto As = [&](int buf, int k, int c) -> float & { return smem[(buf * BK + k) * SA + c]; };
+    auto Bs = [&](int buf, int k, int c) -> float & { return smem[OFFB + (buf * BK + k) * SB + c]; };
 
     const int bid = blockIdx.x;
     const int xcd = bid & 7, slot = bid >> 3;
@@ -79,7 +117,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void i
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
-    const int wm0 = (wave / P::WN) * WTM, wn0 = (wave % P::WN) * WTN;
+    const int wmi = wave / P::WN;
+    const int wm0 = wmi * WTM, wn0 = (wave % P::WN) * WTN;
 
     constexpr int GA = BM * BK / 4, GB = BN * BK / 4;       // groups of four per tile
     constexpr int PA = (GA + 255) / 256, PB = (GB + 255) / 256;
@@ -137,11 +176,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void i
                 if (P::A_KC) {
                     const int row = g / (BK / 4), kq = g % (BK / 4);
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) As[buf][kq * 4 + j][row] = r[j];
+                    for (int j = 0; j < 4; ++j) As(buf, kq * 4 + j, row) = r[j];
                 } else {
                     const int k = g / (BM / 4), mq = g % (BM / 4);
-                    *reinterpret_cast<float4 *>(&As[buf][k][mq * 4]) = make_float4(r[0], r[1], r[2], r[3]);
-                    if (P::SUM_A && do_sum_a) {
+                    *reinterpret_cast<float4 *>(&As(buf, k, mq * 4)) = make_float4(r[0], r[1], r[2], r[3]);
+                    if (P::SUM_A && do_sum_a) {     // summed here, not at fetch, so the loads stay in flight
 #pragma unroll
                         for (int j = 0; j < 4; ++j) sum_a[j] += r[j];
                     }
@@ -159,10 +198,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void i
                 if (P::B_KC) {
                     const int col = g / (BK / 4), kq = g % (BK / 4);
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) Bs[buf][kq * 4 + j][col] = r[j];
+                    for (int j = 0; j < 4; ++j) Bs(buf, kq * 4 + j, col) = r[j];
                 } else {
                     const int k = g / (BN / 4), nq = g % (BN / 4);
-                    *reinterpret_cast<float4 *>(&Bs[buf][k][nq * 4]) = make_float4(r[0], r[1], r[2], r[3]);
+                    *reinterpret_cast<float4 *>(&Bs(buf, k, nq * 4)) = make_float4(r[0], r[1], r[2], r[3]);
                     if (P::SUM_B && do_sum_b) {
 #pragma unroll
                         for (int j = 0; j < 4; ++j) sum_b[j] += r[j];
@@ -172,19 +211,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void i
         }
     };
 
-    gala_f32x16 acc[BI][BJ];
+    typename Blk::Acc acc[BI][BJ];
 #pragma unroll
     for (int i = 0; i < BI; ++i)
 #pragma unroll
         for (int j = 0; j < BJ; ++j)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+            for (int v = 0; v < NV; ++v) acc[i][j][v] = 0.f;
 
-    const int lr = lane & 31, lk = lane >> 5;
-    float colv[BJ];          // requested now, consumed by the epilogue
-#pragma unroll
-    for (int j = 0; j < BJ; ++j) colv[j] = p.col_value(n0 + wn0 + j * 32 + lr);
-
+    const int lr = lane % MB, lk = lane / MB;
     const int nkt = (ke - kb + BK - 1) / BK;
     if (nkt > 0) {
         fetch(kb);
@@ -195,17 +230,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void i
         const int buf = kt & 1;
         if (kt + 1 < nkt) fetch(kb + (kt + 1) * BK);
 #pragma unroll
-        for (int kk = 0; kk < BK; kk += 2) {
+        for (int kk = 0; kk < BK; kk += Blk::KS) {
             float a[BI], b[BJ];
 #pragma unroll
-            for (int i = 0; i < BI; ++i) a[i] = As[buf][kk + lk][wm0 + i * 32 + lr];
+            for (int i = 0; i < BI; ++i) a[i] = As(buf, kk + lk, wm0 + i * MB + lr);
 #pragma unroll
-            for (int j = 0; j < BJ; ++j) b[j] = Bs[buf][kk + lk][wn0 + j * 32 + lr];
+            for (int j = 0; j < BJ; ++j) b[j] = Bs(buf, kk + lk, wn0 + j * MB + lr);
 #pragma unroll
             for (int i = 0; i < BI; ++i)
 #pragma unroll
-                for (int j = 0; j < BJ; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
+                for (int j = 0; j < BJ; ++j) acc[i][j] = Blk::mma(a[i], b[j], acc[i][j]);
         }
         if (kt + 1 < nkt) stage(buf ^ 1);
         __syncthreads();
@@ -214,8 +248,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void i
     // Operand sums: every thread holds partial sums of its four columns (rows); threads with
     // the same group index are combined through LDS in a fixed order.
     if (P::SUM_A || P::SUM_B) {
-        float *red = &As[0][0][0];
-        static_assert(2 * BK * SA >= 1024 || !(P::SUM_A || P::SUM_B), "LDS scratch for operand sums");
+        float *red = smem;
+        static_assert(LDS_FLOATS >= 1024, "LDS scratch for operand sums");
         if (P::SUM_A && do_sum_a) {
             constexpr int Q = BM / 4, R = 256 / Q;
 #pragma unroll
@@ -238,32 +272,47 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void i
                 for (int r = 0; r < R; ++r) t += red[(r * Q + tid / 4) * 4 + (tid & 3)];
                 p.store_sum_b(n0 + tid, t);
             }
+            __syncthreads();
         }
     }
 
-    // D layout of the 32x32 MFMA: register v of lane l holds row 8*(v/4) + 4*(l/32) + v%4,
-    // column l%32.  Per-element epilogue operands of a block are all requested before its
-    // first store so that their latencies overlap.
+    // Epilogue, one block-row of every wavefront per pass: accumulators -> LDS slab
+    // [WM * MB rows][BN], then the workgroup walks the slab in float4 groups, consecutive
+    // threads on consecutive columns.  The loop above ended with a barrier, so the slab may
+    // overwrite the operand tiles.
+    constexpr int GQ = BN / 4;                       // float4 groups per row
+    constexpr int GS = SLAB * GQ;                    // groups per slab
+    constexpr int PS = (GS + 255) / 256;
+    static_assert(256 % GQ == 0 || GQ % 256 == 0 || PS == 1, "a thread keeps its column group across passes");
     auto epilogue = [&](auto checked) {
         constexpr bool CHECK = decltype(checked)::value;
 #pragma unroll
-        for (int i = 0; i < BI; ++i)
+        for (int i = 0; i < BI; ++i) {
 #pragma unroll
-            for (int j = 0; j < BJ; ++j) {
-                float aux[16];
+            for (int j = 0; j < BJ; ++j)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int m = m0 + wm0 + i * 32 + 8 * (v / 4) + 4 * lk + (v % 4);
-                    const int n = n0 + wn0 + j * 32 + lr;
-                    aux[v] = P::HAS_AUX ? p.template aux<CHECK>(m, n) : 0.f;
-                }
+                for (int v = 0; v < NV; ++v)
+                    smem[(wmi * MB + Blk::row(v, lk)) * SC + wn0 + j * MB + lr] = acc[i][j][v];
+            __syncthreads();
+            float4 val[PS], aux[PS], colv[PS];
+            int mm[PS], nn[PS];
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int m = m0 + wm0 + i * 32 + 8 * (v / 4) + 4 * lk + (v % 4);
-                    const int n = n0 + wn0 + j * 32 + lr;
-                    p.template store<CHECK>(m, n, acc[i][j][v], colv[j], aux[v]);
-                }
+            for (int s = 0; s < PS; ++s) {
+                const int g = tid + s * 256;
+                const int q = (GS % 256 == 0 || g < GS) ? g / GQ : 0, nq = g % GQ;
+                mm[s] = m0 + (q / MB) * WTM + i * MB + (q % MB);
+                nn[s] = n0 + nq * 4;
+                aux[s] = P::HAS_AUX ? p.template aux4<CHECK>(mm[s], nn[s]) : make_float4(0.f, 0.f, 0.f, 0.f);
+                colv[s] = p.col_value4(nn[s]);
+                val[s] = *reinterpret_cast<const float4 *>(&smem[q * SC + nq * 4]);
             }
+#pragma unroll
+            for (int s = 0; s < PS; ++s) {
+                const int g = tid + s * 256;
+                if (GS % 256 == 0 || g < GS) p.template store4<CHECK>(mm[s], nn[s], val[s], colv[s], aux[s]);
+            }
+            if (i + 1 < BI) __syncthreads();
+        }
     };
     if (p.tile_full(m0, n0)) epilogue(std::false_type{});
     else epilogue(std::true_type{});

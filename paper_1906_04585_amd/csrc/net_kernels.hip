@@ -8,6 +8,10 @@
 #include "gala_internal.h"
 #include "igemm.h"
 
+#ifndef GALA_MFMA16
+#define GALA_MFMA16 true
+#endif
+
 namespace gala {
 
 // A group of four consecutive floats; `ok` selects the real address, otherwise the (always
@@ -20,6 +24,17 @@ static __device__ __forceinline__ uint32_t ldg_u8x4(const uint8_t *base, long of
 {
     return *reinterpret_cast<const uint32_t *>(base + (ok ? off : 0));
 }
+static __device__ __forceinline__ float4 relu_bias4(float4 v, float4 b)
+{
+    return make_float4(fmaxf(v.x + b.x, 0.f), fmaxf(v.y + b.y, 0.f), fmaxf(v.z + b.z, 0.f), fmaxf(v.w + b.w, 0.f));
+}
+// gradient passes where the forward activation was positive
+static __device__ __forceinline__ float4 relu_mask4(float4 v, float4 act)
+{
+    return make_float4(act.x > 0.f ? v.x : 0.f, act.y > 0.f ? v.y : 0.f, act.z > 0.f ? v.z : 0.f,
+                       act.w > 0.f ? v.w : 0.f);
+}
+static __device__ __forceinline__ void st4(float *p, float4 v) { *reinterpret_cast<float4 *>(p) = v; }
 static __device__ __forceinline__ void unpack(float (&r)[4], float4 v)
 {
     r[0] = v.x; r[1] = v.y; r[2] = v.z; r[3] = v.w;
@@ -38,14 +53,15 @@ struct ProblemBase {
     typedef float4 ARaw;
     typedef float4 BRaw;
     static constexpr bool SUM_A = false, SUM_B = false, HAS_AUX = false;
+    static constexpr bool MFMA16 = GALA_MFMA16;
     int tiles_m, tiles_n, splits;
     int k0, k1;
     __device__ int k_begin() const { return k0; }
     __device__ int k_end() const { return k1; }
     __device__ void decode_a(float (&r)[4], float4 v) const { unpack(r, v); }
     __device__ void decode_b(float (&r)[4], float4 v) const { unpack(r, v); }
-    __device__ float col_value(int) const { return 0.f; }
-    template <bool CHECK> __device__ float aux(int, int) const { return 0.f; }
+    __device__ float4 col_value4(int) const { return make_float4(0.f, 0.f, 0.f, 0.f); }
+    template <bool CHECK> __device__ float4 aux4(int, int) const { return make_float4(0.f, 0.f, 0.f, 0.f); }
     __device__ void store_sum_a(int, float) const {}
     __device__ void store_sum_b(int, float) const {}
 };
@@ -87,11 +103,11 @@ struct Conv1Fwd : ProblemBase {
     }
     __device__ void decode_a(float (&r)[4], uint32_t w) const { unpack_u8(r, w); }
     __device__ float4 fetch_b(int k, int n, bool &ok) const { return ldg4(w_, k * C1 + n, ok); }
-    __device__ float col_value(int n) const { return b_[n]; }
+    __device__ float4 col_value4(int n) const { return *reinterpret_cast<const float4 *>(b_ + n); }
     __device__ bool tile_full(int m0, int) const { return m0 + BM <= rows_; }
-    template <bool CHECK> __device__ void store(int m, int n, float v, float bias, float) const
+    template <bool CHECK> __device__ void store4(int m, int n, float4 v, float4 bias, float4) const
     {
-        if (!CHECK || m < rows_) out_[(long)m * C1 + n] = fmaxf(v + bias, 0.f);
+        if (!CHECK || m < rows_) st4(out_ + (long)m * C1 + n, relu_bias4(v, bias));
     }
 };
 
@@ -125,11 +141,11 @@ struct ConvFwd : ProblemBase {
         return ldg4(in_, ((long)(f * HI + oy * ST + kh) * WI + ox * ST) * CI + rem, ok);
     }
     __device__ float4 fetch_b(int k, int n, bool &ok) const { return ldg4(w_, k * CO + n, ok); }
-    __device__ float col_value(int n) const { return b_[n]; }
+    __device__ float4 col_value4(int n) const { return *reinterpret_cast<const float4 *>(b_ + n); }
     __device__ bool tile_full(int m0, int) const { return m0 + BM <= rows_; }
-    template <bool CHECK> __device__ void store(int m, int n, float v, float bias, float) const
+    template <bool CHECK> __device__ void store4(int m, int n, float4 v, float4 bias, float4) const
     {
-        if (!CHECK || m < rows_) out_[(long)m * CO + n] = fmaxf(v + bias, 0.f);
+        if (!CHECK || m < rows_) st4(out_ + (long)m * CO + n, relu_bias4(v, bias));
     }
 };
 using Conv2Fwd = ConvFwd<C1, H1, W1, C2, H2, W2, K2, S2>;
@@ -161,9 +177,9 @@ struct FcFwd : ProblemBase {
     }
     __device__ float4 fetch_b(int k, int n, bool &ok) const { return ldg4(w_, (long)n * FLAT + k, ok); }
     __device__ bool tile_full(int m0, int) const { return m0 + BM <= F; }
-    template <bool CHECK> __device__ void store(int m, int n, float v, float, float) const
+    template <bool CHECK> __device__ void store4(int m, int n, float4 v, float4, float4) const
     {
-        if (!CHECK || m < F) out_[(long)m * FC + n] = v;
+        if (!CHECK || m < F) st4(out_ + (long)m * FC + n, v);
     }
 };
 
@@ -198,13 +214,13 @@ struct FcDgrad : ProblemBase {
         return ldg4(w_, (long)k * FLAT + n, ok);
     }
     __device__ bool tile_full(int m0, int n0) const { return m0 + BM <= M && n0 + BN <= FLAT; }
-    template <bool CHECK> __device__ float aux(int m, int n) const
+    template <bool CHECK> __device__ float4 aux4(int m, int n) const
     {
-        return act_[(!CHECK || (m < M && n < FLAT)) ? (long)m * FLAT + n : 0];
+        return ldg4(act_, (long)m * FLAT + n, !CHECK || (m < M && n < FLAT));
     }
-    template <bool CHECK> __device__ void store(int m, int n, float v, float, float act) const
+    template <bool CHECK> __device__ void store4(int m, int n, float4 v, float4, float4 act) const
     {
-        if (!CHECK || (m < M && n < FLAT)) out_[(long)m * FLAT + n] = act > 0.f ? v : 0.f;
+        if (!CHECK || (m < M && n < FLAT)) st4(out_ + (long)m * FLAT + n, relu_mask4(v, act));
     }
 };
 
@@ -236,9 +252,9 @@ struct FcWgrad : ProblemBase {
         return ldg4(b_, (long)k * FLAT + n, ok);
     }
     __device__ bool tile_full(int, int n0) const { return n0 + BN <= FLAT; }
-    template <bool CHECK> __device__ void store(int m, int n, float v, float, float) const
+    template <bool CHECK> __device__ void store4(int m, int n, float4 v, float4, float4) const
     {
-        if (!CHECK || n < FLAT) out_[(long)m * FLAT + n] = v;
+        if (!CHECK || n < FLAT) st4(out_ + (long)m * FLAT + n, v);
     }
 };
 
@@ -278,13 +294,13 @@ struct Conv3Dgrad : ProblemBase {
         return ldg4(w_, ((long)t * C2 + n) * C3 + o, ok);
     }
     __device__ bool tile_full(int m0, int) const { return m0 + BM <= rows_; }
-    template <bool CHECK> __device__ float aux(int m, int n) const
+    template <bool CHECK> __device__ float4 aux4(int m, int n) const
     {
-        return act_[(!CHECK || m < rows_) ? (long)m * C2 + n : 0];
+        return ldg4(act_, (long)m * C2 + n, !CHECK || m < rows_);
     }
-    template <bool CHECK> __device__ void store(int m, int n, float v, float, float act) const
+    template <bool CHECK> __device__ void store4(int m, int n, float4 v, float4, float4 act) const
     {
-        if (!CHECK || m < rows_) out_[(long)m * C2 + n] = act > 0.f ? v : 0.f;
+        if (!CHECK || m < rows_) st4(out_ + (long)m * C2 + n, relu_mask4(v, act));
     }
 };
 
@@ -334,13 +350,14 @@ struct Conv2Dgrad : ProblemBase {
         return ((long)(f * H1 + 2 * yy + py_) * W1 + 2 * xx + px_) * C1 + n;
     }
     __device__ bool tile_full(int m0, int) const { return m0 + BM <= rows_; }
-    template <bool CHECK> __device__ float aux(int m, int n) const
+    template <bool CHECK> __device__ float4 aux4(int m, int n) const
     {
-        return act_[(!CHECK || m < rows_) ? out_index(m, n) : 0];
+        const bool ok = !CHECK || m < rows_;
+        return ldg4(act_, ok ? out_index(m, n) : 0, ok);
     }
-    template <bool CHECK> __device__ void store(int m, int n, float v, float, float act) const
+    template <bool CHECK> __device__ void store4(int m, int n, float4 v, float4, float4 act) const
     {
-        if (!CHECK || m < rows_) out_[out_index(m, n)] = act > 0.f ? v : 0.f;
+        if (!CHECK || m < rows_) st4(out_ + out_index(m, n), relu_mask4(v, act));
     }
 };
 
@@ -376,9 +393,9 @@ struct ConvWgrad : ProblemBase {
     }
     __device__ float4 fetch_b(int k, int n, bool &ok) const { return ldg4(dz_, (long)k * CO + n, ok); }
     __device__ bool tile_full(int m0, int) const { return m0 + BM <= MT; }
-    template <bool CHECK> __device__ void store(int m, int n, float v, float, float) const
+    template <bool CHECK> __device__ void store4(int m, int n, float4 v, float4, float4) const
     {
-        if (!CHECK || m < MT) out_[(long)m * CO + n] = v;
+        if (!CHECK || m < MT) st4(out_ + (long)m * CO + n, v);
     }
     __device__ void store_sum_b(int n, float v) const { out_[MT * CO + n] = v; }
 };
@@ -417,9 +434,9 @@ struct Conv1Wgrad : ProblemBase {
     __device__ void decode_a(float (&r)[4], uint32_t w) const { unpack_u8(r, w); }
     __device__ float4 fetch_b(int k, int n, bool &ok) const { return ldg4(dz_, (long)k * C1 + n, ok); }
     __device__ bool tile_full(int, int) const { return true; }
-    template <bool CHECK> __device__ void store(int m, int n, float v, float, float) const
+    template <bool CHECK> __device__ void store4(int m, int n, float4 v, float4, float4) const
     {
-        out_[(long)m * C1 + n] = v;
+        st4(out_ + (long)m * C1 + n, v);
     }
     __device__ void store_sum_b(int n, float v) const { out_[KW1 * C1 + n] = v; }
 };

@@ -11,7 +11,7 @@ import os
 import numpy as np
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_PKG, "libgala.so")
+_LIB_PATH = os.environ.get("GALA_LIBRARY", os.path.join(_PKG, "libgala.so"))
 
 EXPORTS = [
     "gala_create", "gala_destroy", "gala_param_count", "gala_last_error",

@@ -229,6 +229,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void i
     for (int kt = 0; kt < nkt; ++kt) {
         const int buf = kt & 1;
         if (kt + 1 < nkt) fetch(kb + (kt + 1) * BK);
+        // keep the global loads of the next tile ahead of this tile's MFMAs: without the fence
+        // the scheduler sinks them next to their first use and their latency is exposed
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int kk = 0; kk < BK; kk += Blk::KS) {
             float a[BI], b[BJ];

@@ -175,13 +175,19 @@ extern "C" int gala_create(gala_ctx **out, int n_agents, const gala_topology *to
     ALLOC(b.x[0], N * dp, true); ALLOC(b.x[1], N * dp, true);
     ALLOC(b.g, N * dp, true); ALLOC(b.v, N * dp, true);
     if (c->tau > 0) ALLOC(b.hist, (size_t)(c->tau + 1) * N * dp, true);
-    ALLOC(b.a1, N * F * A1SZ, false); ALLOC(b.a2, N * F * A2SZ, false);
-    ALLOC(b.a3, N * F * A3SZ, false); ALLOC(b.h, N * F * FC, false);
+    // activation / gradient buffers: ZERO_PAGE zeros, then the data
+#define ALLOC_ZP(ptr, count) do { ALLOC(ptr, (count) + ZERO_PAGE, false); \
+        he = hipMemsetAsync((ptr), 0, ZERO_PAGE * sizeof(float), c->stream); \
+        if (he != hipSuccess) { fail(c, GALA_EHIP, "zero page: %s", hipGetErrorString(he)); return bail(GALA_EHIP); } \
+        (ptr) += ZERO_PAGE; } while (0)
+    ALLOC_ZP(b.a1, N * F * A1SZ); ALLOC_ZP(b.a2, N * F * A2SZ);
+    ALLOC_ZP(b.a3, N * F * A3SZ); ALLOC_ZP(b.h, N * F * FC);
     ALLOC(b.logits, N * M * A, true); ALLOC(b.values, N * F, true);
     ALLOC(b.ret, N * M, true); ALLOC(b.adv, N * M, true);
     ALLOC(b.dlogits, N * M * A, false); ALLOC(b.dvalues, N * M, false);
-    ALLOC(b.dzh, N * M * FC, false); ALLOC(b.dz3, N * M * A3SZ, false);
-    ALLOC(b.dz2, N * M * A2SZ, false); ALLOC(b.dz1, N * M * A1SZ, false);
+    ALLOC_ZP(b.dzh, N * M * FC); ALLOC_ZP(b.dz3, N * M * A3SZ);
+    ALLOC_ZP(b.dz2, N * M * A2SZ); ALLOC_ZP(b.dz1, N * M * A1SZ);
+#undef ALLOC_ZP
     ALLOC(b.ws, workspace_floats(c->N, c->M, c->F), false);
     ALLOC(b.norm_part, N * NORM_BLOCKS, true);
     ALLOC(b.stats, N * 5, true);

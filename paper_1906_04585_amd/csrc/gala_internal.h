@@ -88,6 +88,10 @@ struct Buffers {
 };
 
 constexpr int NORM_BLOCKS = 64;
+// Activation and gradient buffers (a1, a2, a3, h, dz1..dz3, dzh) are allocated with this many
+// zero floats in front of the data.  Kernels that must treat a group as zero (a padding tap
+// of a transposed convolution, the tail of a k-range) read it from there instead of masking.
+constexpr int ZERO_PAGE = 64;
 
 // Optional per-phase timing with HIP events on the context's stream (diagnostic).
 struct PhaseTimer {

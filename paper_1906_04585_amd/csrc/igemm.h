@@ -21,12 +21,22 @@
 //   int  k_begin(), k_end()
 //   typedef ARaw, BRaw                      what one global load of a group returns (float4, or a
 //                                           uint32_t of four bytes)
-//   ARaw fetch_a(int m, int k, bool &ok)    ok comes in as "k is inside the k-range" and goes out
-//   BRaw fetch_b(int k, int n, bool &ok)    as "this group exists"; the load itself is always
-//                                           issued, from a clamped address when !ok, so that no
-//                                           branch or wait sits between the loads of a tile
-//   void decode_a(float (&r)[4], ARaw)      raw -> four floats (applied at staging time, after
-//   void decode_b(float (&r)[4], BRaw)      the MFMAs of the current tile were issued)
+//   typedef CtxA, CtxB                      per-thread, per-group state prepared once before the
+//                                           k-loop (row offsets, tap masks, running positions), so
+//                                           that the per-tile address work is a few instructions:
+//                                           on this hardware ordinary vector instructions and MFMAs
+//                                           share one issue port per SIMD, every VALU instruction in
+//                                           the loop is paid for in matrix throughput
+//   void prep_a(CtxA &, int m, int kl)      group of rows m.. (A_KC: one row, kl = first local k;
+//   void prep_b(CtxB &, int kl, int n)      otherwise 4 rows from m, kl = local k)
+//   ARaw fetch_a(CtxA &, int k0, bool &ok)  load the group for the tile starting at k0 (uniform);
+//   BRaw fetch_b(CtxB &, int k0, bool &ok)  always issues the load, from a clamped or zero-page
+//                                           address when the group does not exist; called once per
+//                                           tile with k0 ascending by BK, so it may advance the context
+//   static constexpr bool A_ZERO, B_ZERO    the staged values must be zeroed where !ok (operands
+//                                           whose invalid groups cannot be read from a zero page)
+//   void decode_a(float (&r)[4], ARaw, bool ok)   raw -> four floats (applied at staging time, after
+//   void decode_b(float (&r)[4], BRaw, bool ok)   the MFMAs of the current tile were issued)
 //   float4 col_value4(int n)                per-column epilogue operand (e.g. the bias), columns n..n+3
 //   static constexpr bool HAS_AUX
 //   template <bool CHECK> float4 aux4(int m, int n)
@@ -124,6 +134,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void i
     constexpr int PA = (GA + 255) / 256, PB = (GB + 255) / 256;
     typename P::ARaw ra[PA];
     typename P::BRaw rb[PB];
+    typename P::CtxA ca[PA];
+    typename P::CtxB cb[PB];
     bool oka[PA], okb[PB];
     static_assert(!P::SUM_A || (!P::A_KC && 256 % (BM / 4) == 0), "SUM_A needs m-contiguous groups");
     static_assert(!P::SUM_B || (!P::B_KC && 256 % (BN / 4) == 0), "SUM_B needs n-contiguous groups");
@@ -132,47 +144,49 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void i
 
     const int kb = p.k_begin(), ke = p.k_end();
 
+#pragma unroll
+    for (int i = 0; i < PA; ++i) {
+        const int g = tid + i * 256;
+        oka[i] = true;
+        if (GA % 256 == 0 || g < GA) {
+            if (P::A_KC) p.prep_a(ca[i], m0 + g / (BK / 4), (g % (BK / 4)) * 4);
+            else p.prep_a(ca[i], m0 + (g % (BM / 4)) * 4, g / (BM / 4));
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < PB; ++i) {
+        const int g = tid + i * 256;
+        okb[i] = true;
+        if (GB % 256 == 0 || g < GB) {
+            if (P::B_KC) p.prep_b(cb[i], (g % (BK / 4)) * 4, n0 + g / (BK / 4));
+            else p.prep_b(cb[i], g / (BN / 4), n0 + (g % (BN / 4)) * 4);
+        }
+    }
+
     auto fetch = [&](int k0) {
 #pragma unroll
         for (int i = 0; i < PA; ++i) {
             const int g = tid + i * 256;
-            if (GA % 256 == 0 || g < GA) {
-                if (P::A_KC) {
-                    const int row = g / (BK / 4), kq = g % (BK / 4);
-                    oka[i] = k0 + kq * 4 < ke;
-                    ra[i] = p.fetch_a(m0 + row, k0 + kq * 4, oka[i]);
-                } else {
-                    const int k = g / (BM / 4), mq = g % (BM / 4);
-                    oka[i] = k0 + k < ke;
-                    ra[i] = p.fetch_a(m0 + mq * 4, k0 + k, oka[i]);
-                }
-            }
+            if (GA % 256 == 0 || g < GA) ra[i] = p.fetch_a(ca[i], k0, oka[i]);
         }
 #pragma unroll
         for (int i = 0; i < PB; ++i) {
             const int g = tid + i * 256;
-            if (GB % 256 == 0 || g < GB) {
-                if (P::B_KC) {
-                    const int col = g / (BK / 4), kq = g % (BK / 4);
-                    okb[i] = k0 + kq * 4 < ke;
-                    rb[i] = p.fetch_b(k0 + kq * 4, n0 + col, okb[i]);
-                } else {
-                    const int k = g / (BN / 4), nq = g % (BN / 4);
-                    okb[i] = k0 + k < ke;
-                    rb[i] = p.fetch_b(k0 + k, n0 + nq * 4, okb[i]);
-                }
-            }
+            if (GB % 256 == 0 || g < GB) rb[i] = p.fetch_b(cb[i], k0, okb[i]);
         }
     };
-    auto stage = [&](int buf) {
+    auto stage = [&](auto bufc) {
+        constexpr int buf = decltype(bufc)::value;
 #pragma unroll
         for (int i = 0; i < PA; ++i) {
             const int g = tid + i * 256;
             if (GA % 256 == 0 || g < GA) {
                 float r[4];
-                p.decode_a(r, ra[i]);
+                p.decode_a(r, ra[i], oka[i]);
+                if (P::A_ZERO) {
 #pragma unroll
-                for (int j = 0; j < 4; ++j) r[j] = oka[i] ? r[j] : 0.f;
+                    for (int j = 0; j < 4; ++j) r[j] = oka[i] ? r[j] : 0.f;
+                }
                 if (P::A_KC) {
                     const int row = g / (BK / 4), kq = g % (BK / 4);
 #pragma unroll
@@ -192,9 +206,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void i
             const int g = tid + i * 256;
             if (GB % 256 == 0 || g < GB) {
                 float r[4];
-                p.decode_b(r, rb[i]);
+                p.decode_b(r, rb[i], okb[i]);
+                if (P::B_ZERO) {
 #pragma unroll
-                for (int j = 0; j < 4; ++j) r[j] = okb[i] ? r[j] : 0.f;
+                    for (int j = 0; j < 4; ++j) r[j] = okb[i] ? r[j] : 0.f;
+                }
                 if (P::B_KC) {
                     const int col = g / (BK / 4), kq = g % (BK / 4);
 #pragma unroll
@@ -223,11 +239,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void i
     const int nkt = (ke - kb + BK - 1) / BK;
     if (nkt > 0) {
         fetch(kb);
-        stage(0);
+        stage(std::integral_constant<int, 0>{});
     }
     __syncthreads();
-    for (int kt = 0; kt < nkt; ++kt) {
-        const int buf = kt & 1;
+    // One k-tile: request the next tile, run this tile's MFMAs out of buffer `buf`, stage the
+    // next tile into the other buffer.  `buf` is a compile-time constant (the loop below is
+    // unrolled by two) so that every LDS address is a per-lane base plus an immediate.
+    auto tile_step = [&](auto bufc, int kt) {
+        constexpr int buf = decltype(bufc)::value;
         if (kt + 1 < nkt) fetch(kb + (kt + 1) * BK);
         // keep the global loads of the next tile ahead of this tile's MFMAs: without the fence
         // the scheduler sinks them next to their first use and their latency is exposed
@@ -244,8 +263,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void i
 #pragma unroll
                 for (int j = 0; j < BJ; ++j) acc[i][j] = Blk::mma(a[i], b[j], acc[i][j]);
         }
-        if (kt + 1 < nkt) stage(buf ^ 1);
+        if (kt + 1 < nkt) stage(std::integral_constant<int, buf ^ 1>{});
         __syncthreads();
+    };
+    for (int kt = 0; kt < nkt; kt += 2) {
+        tile_step(std::integral_constant<int, 0>{}, kt);
+        if (kt + 1 < nkt) tile_step(std::integral_constant<int, 1>{}, kt + 1);
     }
 
     // Operand sums: every thread holds partial sums of its four columns (rows); threads with

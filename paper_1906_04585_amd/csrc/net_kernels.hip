@@ -14,15 +14,14 @@
 
 namespace gala {
 
-// A group of four consecutive floats; `ok` selects the real address, otherwise the (always
-// readable) base of the tensor is loaded and the result discarded by the caller.
-static __device__ __forceinline__ float4 ldg4(const float *base, long off, bool ok)
+// Loads by (uniform base pointer, per-lane byte offset): the base stays in scalar registers.
+static __device__ __forceinline__ float4 ldg4b(const void *base, unsigned boff)
 {
-    return *reinterpret_cast<const float4 *>(base + (ok ? off : 0));
+    return *reinterpret_cast<const float4 *>(static_cast<const char *>(base) + boff);
 }
-static __device__ __forceinline__ uint32_t ldg_u8x4(const uint8_t *base, long off, bool ok)
+static __device__ __forceinline__ uint32_t ldg_u32b(const void *base, unsigned boff)
 {
-    return *reinterpret_cast<const uint32_t *>(base + (ok ? off : 0));
+    return *reinterpret_cast<const uint32_t *>(static_cast<const char *>(base) + boff);
 }
 static __device__ __forceinline__ float4 relu_bias4(float4 v, float4 b)
 {
@@ -34,32 +33,39 @@ static __device__ __forceinline__ float4 relu_mask4(float4 v, float4 act)
     return make_float4(act.x > 0.f ? v.x : 0.f, act.y > 0.f ? v.y : 0.f, act.z > 0.f ? v.z : 0.f,
                        act.w > 0.f ? v.w : 0.f);
 }
+static __device__ __forceinline__ float4 scale4(float4 v, float s) { return make_float4(v.x * s, v.y * s, v.z * s, v.w * s); }
 static __device__ __forceinline__ void st4(float *p, float4 v) { *reinterpret_cast<float4 *>(p) = v; }
 static __device__ __forceinline__ void unpack(float (&r)[4], float4 v)
 {
     r[0] = v.x; r[1] = v.y; r[2] = v.z; r[3] = v.w;
 }
-// states are bytes scaled to [0, 1]
+// Four state bytes as floats 0..255.  The 1/255 that scales states to [0, 1] is applied once
+// per output element in the epilogue of the two kernels that read bytes.
 static __device__ __forceinline__ void unpack_u8(float (&r)[4], uint32_t w)
 {
-    constexpr float sc = 1.0f / 255.0f;
-    r[0] = (float)(w & 255u) * sc;
-    r[1] = (float)((w >> 8) & 255u) * sc;
-    r[2] = (float)((w >> 16) & 255u) * sc;
-    r[3] = (float)(w >> 24) * sc;
+    r[0] = (float)(w & 255u);
+    r[1] = (float)((w >> 8) & 255u);
+    r[2] = (float)((w >> 16) & 255u);
+    r[3] = (float)(w >> 24);
 }
+constexpr float STATE_SCALE = 1.0f / 255.0f;
+constexpr unsigned ZPB = ZERO_PAGE * 4;      // bytes of zeros in front of every activation buffer
+
+struct OffCtx { unsigned off; };             // byte offset of the group, fixed over the k-loop
 
 struct ProblemBase {
     typedef float4 ARaw;
     typedef float4 BRaw;
-    static constexpr bool SUM_A = false, SUM_B = false, HAS_AUX = false;
+    typedef OffCtx CtxA;
+    typedef OffCtx CtxB;
+    static constexpr bool SUM_A = false, SUM_B = false, HAS_AUX = false, A_ZERO = false, B_ZERO = false;
     static constexpr bool MFMA16 = GALA_MFMA16;
     int tiles_m, tiles_n, splits;
     int k0, k1;
     __device__ int k_begin() const { return k0; }
     __device__ int k_end() const { return k1; }
-    __device__ void decode_a(float (&r)[4], float4 v) const { unpack(r, v); }
-    __device__ void decode_b(float (&r)[4], float4 v) const { unpack(r, v); }
+    __device__ void decode_a(float (&r)[4], float4 v, bool) const { unpack(r, v); }
+    __device__ void decode_b(float (&r)[4], float4 v, bool) const { unpack(r, v); }
     __device__ float4 col_value4(int) const { return make_float4(0.f, 0.f, 0.f, 0.f); }
     template <bool CHECK> __device__ float4 aux4(int, int) const { return make_float4(0.f, 0.f, 0.f, 0.f); }
     __device__ void store_sum_a(int, float) const {}
@@ -67,11 +73,13 @@ struct ProblemBase {
 };
 
 // ---- conv1 forward: bytes -> a1 ------------------------------------------------------
-// m = (f, oy, ox), n = o, k = (c, kh, kw).
+// m = (f, oy, ox), n = o, k = (c, kh, kw).  A tile of 16 consecutive k is one channel, two
+// kernel rows of eight bytes: the tile-dependent part of the address is uniform.
 struct Conv1Fwd : ProblemBase {
     static constexpr int BM = 256, BN = 32, BK = 16, WM = 4, WN = 1;
     static constexpr bool A_KC = true, B_KC = false;
     typedef uint32_t ARaw;
+    struct CtxA { const uint8_t *ptr; };
     const uint8_t *obs, *boot;
     const float *x;
     float *a1;
@@ -91,32 +99,37 @@ struct Conv1Fwd : ProblemBase {
         rows_ = F * P1;
         k0 = 0; k1 = KW1;
     }
-    __device__ uint32_t fetch_a(int m, int k, bool &ok) const
+    __device__ void prep_a(CtxA &c, int m, int kl) const
     {
-        ok = ok && m < rows_;
         const int f = m / P1, p = m % P1, oy = p / W1, ox = p % W1;
-        const int c = k >> 6, kh = (k >> 3) & 7, kw = k & 7;
         const bool roll = f < M;
-        const uint8_t *fr = roll ? o_ : bo_;
-        const long off = (long)(roll ? f : f - M) * FRAME + c * (H0 * W0) + (oy * S1 + kh) * W0 + ox * S1 + kw;
-        return ldg_u8x4(fr, off, ok);
+        const uint8_t *fr = roll ? o_ + (long)f * FRAME : bo_ + (long)(f - M) * FRAME;
+        c.ptr = m < rows_ ? fr + (oy * S1 + (kl >> 3)) * W0 + ox * S1 + (kl & 7) : o_;
     }
-    __device__ void decode_a(float (&r)[4], uint32_t w) const { unpack_u8(r, w); }
-    __device__ float4 fetch_b(int k, int n, bool &ok) const { return ldg4(w_, k * C1 + n, ok); }
+    __device__ uint32_t fetch_a(CtxA &c, int kt0, bool &) const
+    {
+        const int koff = (kt0 >> 6) * (H0 * W0) + ((kt0 >> 3) & 7) * W0;      // uniform
+        return *reinterpret_cast<const uint32_t *>(c.ptr + koff);
+    }
+    __device__ void decode_a(float (&r)[4], uint32_t w, bool) const { unpack_u8(r, w); }
+    __device__ void prep_b(CtxB &c, int kl, int n) const { c.off = (kl * C1 + n) * 4; }
+    __device__ float4 fetch_b(CtxB &c, int kt0, bool &) const { return ldg4b(w_ + kt0 * C1, c.off); }
     __device__ float4 col_value4(int n) const { return *reinterpret_cast<const float4 *>(b_ + n); }
     __device__ bool tile_full(int m0, int) const { return m0 + BM <= rows_; }
     template <bool CHECK> __device__ void store4(int m, int n, float4 v, float4 bias, float4) const
     {
-        if (!CHECK || m < rows_) st4(out_ + (long)m * C1 + n, relu_bias4(v, bias));
+        if (!CHECK || m < rows_) st4(out_ + (long)m * C1 + n, relu_bias4(scale4(v, STATE_SCALE), bias));
     }
 };
 
 // ---- conv2 / conv3 forward ---------------------------------------------------------------
-// m = (f, oy, ox), n = o, k = (kh, kw, c) over a channels-last input.
+// m = (f, oy, ox), n = o, k = (kh, kw, c) over a channels-last input: a tile of 16 consecutive
+// k never crosses a kernel row, so its offset is uniform.
 template <int CI, int HI, int WI, int CO, int HO, int WO, int KS, int ST>
 struct ConvFwd : ProblemBase {
     static constexpr int BM = 128, BN = 64, BK = 16, WM = 2, WN = 2;
     static constexpr bool A_KC = true, B_KC = false;
+    static_assert((KS * CI) % BK == 0, "a k-tile stays inside one kernel row");
     const float *in, *x;
     float *out;
     long d_pad, w_off, b_off;
@@ -133,14 +146,18 @@ struct ConvFwd : ProblemBase {
         rows_ = F * HO * WO;
         k0 = 0; k1 = KS * KS * CI;
     }
-    __device__ float4 fetch_a(int m, int k, bool &ok) const
+    __device__ void prep_a(CtxA &c, int m, int kl) const
     {
-        ok = ok && m < rows_;
         const int f = m / (HO * WO), p = m % (HO * WO), oy = p / WO, ox = p % WO;
-        const int kh = k / (KS * CI), rem = k % (KS * CI);
-        return ldg4(in_, ((long)(f * HI + oy * ST + kh) * WI + ox * ST) * CI + rem, ok);
+        c.off = m < rows_ ? (unsigned)((((f * HI + oy * ST) * WI + ox * ST) * CI + kl) * 4) : 0u;
     }
-    __device__ float4 fetch_b(int k, int n, bool &ok) const { return ldg4(w_, k * CO + n, ok); }
+    __device__ float4 fetch_a(CtxA &c, int kt0, bool &) const
+    {
+        const int kh = kt0 / (KS * CI), rem = kt0 % (KS * CI);
+        return ldg4b(in_ + kh * (WI * CI) + rem, c.off);
+    }
+    __device__ void prep_b(CtxB &c, int kl, int n) const { c.off = (kl * CO + n) * 4; }
+    __device__ float4 fetch_b(CtxB &c, int kt0, bool &) const { return ldg4b(w_ + kt0 * CO, c.off); }
     __device__ float4 col_value4(int n) const { return *reinterpret_cast<const float4 *>(b_ + n); }
     __device__ bool tile_full(int m0, int) const { return m0 + BM <= rows_; }
     template <bool CHECK> __device__ void store4(int m, int n, float4 v, float4 bias, float4) const
@@ -170,12 +187,10 @@ struct FcFwd : ProblemBase {
         k0 = split * kchunk;
         k1 = min(FLAT, k0 + kchunk);
     }
-    __device__ float4 fetch_a(int m, int k, bool &ok) const
-    {
-        ok = ok && m < F;
-        return ldg4(a_, (long)m * FLAT + k, ok);
-    }
-    __device__ float4 fetch_b(int k, int n, bool &ok) const { return ldg4(w_, (long)n * FLAT + k, ok); }
+    __device__ void prep_a(CtxA &c, int m, int kl) const { c.off = m < F ? (unsigned)((m * FLAT + kl) * 4) : 0u; }
+    __device__ float4 fetch_a(CtxA &c, int kt0, bool &) const { return ldg4b(a_ + kt0, c.off); }
+    __device__ void prep_b(CtxB &c, int kl, int n) const { c.off = (unsigned)((n * FLAT + kl) * 4); }
+    __device__ float4 fetch_b(CtxB &c, int kt0, bool &) const { return ldg4b(w_ + kt0, c.off); }
     __device__ bool tile_full(int m0, int) const { return m0 + BM <= F; }
     template <bool CHECK> __device__ void store4(int m, int n, float4 v, float4, float4) const
     {
@@ -203,20 +218,14 @@ struct FcDgrad : ProblemBase {
         out_ = dz3 + (long)agent * M * FLAT;
         k0 = 0; k1 = FC;
     }
-    __device__ float4 fetch_a(int m, int k, bool &ok) const
-    {
-        ok = ok && m < M;
-        return ldg4(a_, (long)m * FC + k, ok);
-    }
-    __device__ float4 fetch_b(int k, int n, bool &ok) const
-    {
-        ok = ok && n < FLAT;
-        return ldg4(w_, (long)k * FLAT + n, ok);
-    }
+    __device__ void prep_a(CtxA &c, int m, int kl) const { c.off = m < M ? (unsigned)((m * FC + kl) * 4) : 0u; }
+    __device__ float4 fetch_a(CtxA &c, int kt0, bool &) const { return ldg4b(a_ + kt0, c.off); }
+    __device__ void prep_b(CtxB &c, int kl, int n) const { c.off = n < FLAT ? (unsigned)((kl * FLAT + n) * 4) : 0u; }
+    __device__ float4 fetch_b(CtxB &c, int kt0, bool &) const { return ldg4b(w_ + (long)kt0 * FLAT, c.off); }
     __device__ bool tile_full(int m0, int n0) const { return m0 + BM <= M && n0 + BN <= FLAT; }
     template <bool CHECK> __device__ float4 aux4(int m, int n) const
     {
-        return ldg4(act_, (long)m * FLAT + n, !CHECK || (m < M && n < FLAT));
+        return ldg4b(act_, (!CHECK || (m < M && n < FLAT)) ? (unsigned)((m * FLAT + n) * 4) : 0u);
     }
     template <bool CHECK> __device__ void store4(int m, int n, float4 v, float4, float4 act) const
     {
@@ -225,11 +234,14 @@ struct FcDgrad : ProblemBase {
 };
 
 // ---- hidden layer: weight gradient (and bias gradient = sum over frames of dzh) -----------------
-// m = j, n = flattened a3 index, k = f.
+// m = j, n = flattened a3 index, k = f.  The number of frames need not be a multiple of the
+// k-tile: groups beyond it are read from the start of the buffer and zeroed.
 struct FcWgrad : ProblemBase {
     static constexpr int BM = 128, BN = 128, BK = 16, WM = 2, WN = 2;
     static constexpr bool A_KC = false, B_KC = false;
-    static constexpr bool SUM_A = true;
+    static constexpr bool SUM_A = true, A_ZERO = true, B_ZERO = true;
+    struct CtxA { unsigned off; int kl; };
+    struct CtxB { unsigned off; int kl; bool col_ok; };
     const float *dzh, *a3;
     float *g;
     long d_pad, w_off, b_off;
@@ -245,11 +257,20 @@ struct FcWgrad : ProblemBase {
         k0 = 0; k1 = M;
     }
     __device__ void store_sum_a(int m, float v) const { bias_[m] = v; }
-    __device__ float4 fetch_a(int m, int k, bool &ok) const { return ldg4(a_, (long)k * FC + m, ok); }
-    __device__ float4 fetch_b(int k, int n, bool &ok) const
+    __device__ void prep_a(CtxA &c, int m, int kl) const { c.off = (unsigned)((kl * FC + m) * 4); c.kl = kl; }
+    __device__ float4 fetch_a(CtxA &c, int kt0, bool &ok) const
     {
-        ok = ok && n < FLAT;
-        return ldg4(b_, (long)k * FLAT + n, ok);
+        ok = kt0 + c.kl < k1;
+        return ldg4b(a_, ok ? c.off + (unsigned)(kt0 * FC * 4) : 0u);
+    }
+    __device__ void prep_b(CtxB &c, int kl, int n) const
+    {
+        c.off = (unsigned)((kl * FLAT + n) * 4); c.kl = kl; c.col_ok = n < FLAT;
+    }
+    __device__ float4 fetch_b(CtxB &c, int kt0, bool &ok) const
+    {
+        ok = kt0 + c.kl < k1;
+        return ldg4b(b_, (ok && c.col_ok) ? c.off + (unsigned)(kt0 * FLAT * 4) : 0u);
     }
     __device__ bool tile_full(int, int n0) const { return n0 + BN <= FLAT; }
     template <bool CHECK> __device__ void store4(int m, int n, float4 v, float4, float4) const
@@ -258,45 +279,64 @@ struct FcWgrad : ProblemBase {
     }
 };
 
+// Context of a transposed-convolution row: byte offset of the centre tap inside the zero-paged
+// gradient buffer and one validity bit per kernel tap.
+struct TapCtx { unsigned off; unsigned mask; };
+
 // ---- conv3: gradient to a2 (stride 1: full correlation with the flipped kernel) -----------------
-// m = (f, iy, ix), n = c, k = (kh, kw, o).
+// m = (f, iy, ix), n = c, k = (kh, kw, o); a tile of 16 consecutive k lies inside one tap.  Taps
+// that fall outside the 7x7 output are read from the zero page in front of dz3.
 struct Conv3Dgrad : ProblemBase {
     static constexpr int BM = 128, BN = 64, BK = 16, WM = 2, WN = 2;
     static constexpr bool A_KC = true, B_KC = true;
     static constexpr bool HAS_AUX = true;
-    const float *dz3, *x, *a2;
+    typedef TapCtx CtxA;
+    const float *dz3, *x, *a2;      // dz3 points at the data; ZERO_PAGE zeros precede the allocation's data
     float *dz2;
     long d_pad, w_off;
     int M, F;
-    const float *a_, *w_, *act_;
+    const float *zp_, *w_, *act_;
     float *out_;
     int rows_;
+    unsigned abase_;
     __device__ void bind(int agent, int)
     {
-        a_ = dz3 + (long)agent * M * A3SZ;
+        zp_ = dz3 - ZERO_PAGE;
+        abase_ = ZPB + (unsigned)agent * (unsigned)(M * A3SZ) * 4u;
         w_ = x + agent * d_pad + w_off;
         act_ = a2 + (long)agent * F * A2SZ;
         out_ = dz2 + (long)agent * M * A2SZ;
         rows_ = M * P2;
         k0 = 0; k1 = K3 * K3 * C3;
     }
-    __device__ float4 fetch_a(int m, int k, bool &ok) const
+    __device__ void prep_a(CtxA &c, int m, int kl) const
     {
         const int f = m / P2, p = m % P2, iy = p / W2, ix = p % W2;
-        const int t = k / C3, o = k % C3, kh = t / K3, kw = t % K3;
-        const int oy = iy - kh, ox = ix - kw;
-        ok = ok && m < rows_ && oy >= 0 && oy < H3 && ox >= 0 && ox < W3;
-        return ldg4(a_, ((long)(f * H3 + oy) * W3 + ox) * C3 + o, ok);
+        c.off = abase_ + (unsigned)((((f * H3 + iy) * W3 + ix) * C3 + kl) * 4);
+        unsigned mask = 0;
+#pragma unroll
+        for (int t = 0; t < K3 * K3; ++t) {
+            const int oy = iy - t / K3, ox = ix - t % K3;
+            if (oy >= 0 && oy < H3 && ox >= 0 && ox < W3) mask |= 1u << t;
+        }
+        c.mask = m < rows_ ? mask : 0u;
     }
-    __device__ float4 fetch_b(int k, int n, bool &ok) const
+    __device__ float4 fetch_a(CtxA &c, int kt0, bool &) const
     {
-        const int t = k / C3, o = k % C3;
-        return ldg4(w_, ((long)t * C2 + n) * C3 + o, ok);
+        const int t = kt0 / C3, o0 = kt0 % C3, kh = t / K3, kw = t % K3;          // uniform
+        const int tap = (o0 - (kh * W3 + kw) * C3) * 4;
+        return ldg4b(zp_, ((c.mask >> t) & 1u) ? c.off + (unsigned)tap : 0u);
+    }
+    __device__ void prep_b(CtxB &c, int kl, int n) const { c.off = (unsigned)((n * C3 + kl) * 4); }
+    __device__ float4 fetch_b(CtxB &c, int kt0, bool &) const
+    {
+        const int t = kt0 / C3, o0 = kt0 % C3;
+        return ldg4b(w_ + t * (C2 * C3) + o0, c.off);
     }
     __device__ bool tile_full(int m0, int) const { return m0 + BM <= rows_; }
     template <bool CHECK> __device__ float4 aux4(int m, int n) const
     {
-        return ldg4(act_, (long)m * C2 + n, !CHECK || m < rows_);
+        return ldg4b(act_, (!CHECK || m < rows_) ? (unsigned)((m * C2 + n) * 4) : 0u);
     }
     template <bool CHECK> __device__ void store4(int m, int n, float4 v, float4, float4 act) const
     {
@@ -313,16 +353,19 @@ struct Conv2Dgrad : ProblemBase {
     static constexpr bool A_KC = true, B_KC = true;
     static constexpr bool HAS_AUX = true;
     static constexpr int HY = H1 / 2, WX = W1 / 2, PC = HY * WX;   // 10, 10, 100
+    typedef TapCtx CtxA;
     const float *dz2, *x, *a1;
     float *dz1;
     long d_pad, w_off;
     int M, F;
-    const float *a_, *w_, *act_;
+    const float *zp_, *w_, *act_;
     float *out_;
     int rows_, py_, px_;
+    unsigned abase_;
     __device__ void bind(int agent, int cls)
     {
-        a_ = dz2 + (long)agent * M * A2SZ;
+        zp_ = dz2 - ZERO_PAGE;
+        abase_ = ZPB + (unsigned)agent * (unsigned)(M * A2SZ) * 4u;
         w_ = x + agent * d_pad + w_off;
         act_ = a1 + (long)agent * F * A1SZ;
         out_ = dz1 + (long)agent * M * A1SZ;
@@ -330,30 +373,40 @@ struct Conv2Dgrad : ProblemBase {
         py_ = cls >> 1; px_ = cls & 1;
         k0 = 0; k1 = 4 * C2;
     }
-    __device__ float4 fetch_a(int m, int k, bool &ok) const
+    __device__ void prep_a(CtxA &c, int m, int kl) const
     {
         const int f = m / PC, p = m % PC, yy = p / WX, xx = p % WX;
-        const int t = k / C2, o = k % C2, a = t >> 1, b = t & 1;
-        const int oy = yy - a, ox = xx - b;
-        ok = ok && m < rows_ && oy >= 0 && oy < H2 && ox >= 0 && ox < W2;
-        return ldg4(a_, ((long)(f * H2 + oy) * W2 + ox) * C2 + o, ok);
+        c.off = abase_ + (unsigned)((((f * H2 + yy) * W2 + xx) * C2 + kl) * 4);
+        unsigned mask = 0;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const int oy = yy - (t >> 1), ox = xx - (t & 1);
+            if (oy >= 0 && oy < H2 && ox >= 0 && ox < W2) mask |= 1u << t;
+        }
+        c.mask = m < rows_ ? mask : 0u;
     }
-    __device__ float4 fetch_b(int k, int n, bool &ok) const
+    __device__ float4 fetch_a(CtxA &c, int kt0, bool &) const
     {
-        const int t = k / C2, o = k % C2, a = t >> 1, b = t & 1;
-        const int kh = py_ + 2 * a, kw = px_ + 2 * b;
-        return ldg4(w_, ((long)(kh * K2 + kw) * C1 + n) * C2 + o, ok);
+        const int t = kt0 / C2, o0 = kt0 % C2;                                     // uniform
+        const int tap = (o0 - ((t >> 1) * W2 + (t & 1)) * C2) * 4;
+        return ldg4b(zp_, ((c.mask >> t) & 1u) ? c.off + (unsigned)tap : 0u);
     }
-    __device__ long out_index(int m, int n) const
+    __device__ void prep_b(CtxB &c, int kl, int n) const { c.off = (unsigned)((n * C2 + kl) * 4); }
+    __device__ float4 fetch_b(CtxB &c, int kt0, bool &) const
+    {
+        const int t = kt0 / C2, o0 = kt0 % C2;
+        const int kh = py_ + 2 * (t >> 1), kw = px_ + 2 * (t & 1);
+        return ldg4b(w_ + (kh * K2 + kw) * (C1 * C2) + o0, c.off);
+    }
+    __device__ unsigned out_index(int m, int n) const
     {
         const int f = m / PC, p = m % PC, yy = p / WX, xx = p % WX;
-        return ((long)(f * H1 + 2 * yy + py_) * W1 + 2 * xx + px_) * C1 + n;
+        return (unsigned)(((f * H1 + 2 * yy + py_) * W1 + 2 * xx + px_) * C1 + n);
     }
     __device__ bool tile_full(int m0, int) const { return m0 + BM <= rows_; }
     template <bool CHECK> __device__ float4 aux4(int m, int n) const
     {
-        const bool ok = !CHECK || m < rows_;
-        return ldg4(act_, ok ? out_index(m, n) : 0, ok);
+        return ldg4b(act_, (!CHECK || m < rows_) ? out_index(m, n) * 4u : 0u);
     }
     template <bool CHECK> __device__ void store4(int m, int n, float4 v, float4, float4 act) const
     {
@@ -361,9 +414,14 @@ struct Conv2Dgrad : ProblemBase {
     }
 };
 
+// Running position of a weight-gradient thread inside the (frame, oy, ox) reduction index: it
+// advances by one k-tile per fetch, so no division is needed inside the loop.
+struct WalkCtx { unsigned moff; int p; unsigned foff; int k; };
+
 // ---- conv2 / conv3 weight gradient (split over frames) ----------------------------------------------
 // m = (kh, kw, c), n = o, k = (f, oy, ox).  Each split writes MT*CO weight partials followed
-// by CO bias partials (the bias gradient is the sum over k of the dz operand).
+// by CO bias partials (the bias gradient is the sum over k of the dz operand).  Both operands
+// live in zero-paged buffers: groups past the end of the split's k-range read zeros.
 template <int CI, int HI, int WI, int CO, int HO, int WO, int KS, int ST, int BM_>
 struct ConvWgrad : ProblemBase {
     static constexpr int BM = BM_, BN = 64, BK = 16, WM = 2, WN = 2;
@@ -371,27 +429,54 @@ struct ConvWgrad : ProblemBase {
     static constexpr bool SUM_B = true;
     static constexpr int MT = KS * KS * CI;
     static constexpr int PART = MT * CO + CO;
-    const float *in, *dz;
+    static constexpr int HW = HO * WO;
+    static_assert(BK <= HW, "one wrap per tile at most");
+    typedef WalkCtx CtxA;
+    struct CtxB { unsigned off; int k; };
+    const float *in, *dz;           // both preceded by ZERO_PAGE zeros
     float *ws;
     int M, F, fps;
-    const float *in_, *dz_;
+    const float *zin_, *zdz_;
     float *out_;
+    unsigned abase_, bbase_;
     __device__ void bind(int agent, int split)
     {
-        in_ = in + (long)agent * F * (HI * WI * CI);
-        dz_ = dz + (long)agent * M * (HO * WO * CO);
+        zin_ = in - ZERO_PAGE;
+        zdz_ = dz - ZERO_PAGE;
+        abase_ = ZPB + (unsigned)agent * (unsigned)(F * (HI * WI * CI)) * 4u;
+        bbase_ = ZPB + (unsigned)agent * (unsigned)(M * (HW * CO)) * 4u;
         out_ = ws + ((long)agent * splits + split) * PART;
-        k0 = split * fps * (HO * WO);
-        k1 = min(M, (split + 1) * fps) * (HO * WO);
+        k0 = split * fps * HW;
+        k1 = min(M, (split + 1) * fps) * HW;
     }
-    __device__ float4 fetch_a(int m, int k, bool &ok) const
+    __device__ void prep_a(CtxA &c, int m, int kl) const
     {
-        ok = ok && m < MT;
-        const int f = k / (HO * WO), p = k % (HO * WO), oy = p / WO, ox = p % WO;
         const int kh = m / (KS * CI), rem = m % (KS * CI);
-        return ldg4(in_, ((long)(f * HI + oy * ST + kh) * WI + ox * ST) * CI + rem, ok);
+        c.moff = m < MT ? abase_ + (unsigned)((kh * (WI * CI) + rem) * 4) : 0u;
+        c.k = k0 + kl;
+        c.p = c.k % HW;
+        c.foff = (unsigned)(c.k / HW) * (unsigned)(HI * WI * CI * 4);
     }
-    __device__ float4 fetch_b(int k, int n, bool &ok) const { return ldg4(dz_, (long)k * CO + n, ok); }
+    __device__ float4 fetch_a(CtxA &c, int, bool &) const
+    {
+        const int oy = c.p / WO, ox = c.p - oy * WO;
+        const unsigned off = c.moff + c.foff + (unsigned)(((oy * ST) * WI + ox * ST) * CI * 4);
+        const float4 v = ldg4b(zin_, (c.k < k1 && c.moff != 0u) ? off : 0u);
+        c.k += BK; c.p += BK;
+        if (c.p >= HW) { c.p -= HW; c.foff += (unsigned)(HI * WI * CI * 4); }
+        return v;
+    }
+    __device__ void prep_b(CtxB &c, int kl, int n) const
+    {
+        c.k = k0 + kl;
+        c.off = bbase_ + (unsigned)((c.k * CO + n) * 4);
+    }
+    __device__ float4 fetch_b(CtxB &c, int, bool &) const
+    {
+        const float4 v = ldg4b(zdz_, c.k < k1 ? c.off : 0u);
+        c.k += BK; c.off += (unsigned)(BK * CO * 4);
+        return v;
+    }
     __device__ bool tile_full(int m0, int) const { return m0 + BM <= MT; }
     template <bool CHECK> __device__ void store4(int m, int n, float4 v, float4, float4) const
     {
@@ -403,40 +488,65 @@ using Conv2Wgrad = ConvWgrad<C1, H1, W1, C2, H2, W2, K2, S2, 128>;
 using Conv3Wgrad = ConvWgrad<C2, H2, W2, C3, H3, W3, K3, S3, 64>;
 
 // ---- conv1 weight gradient (split over frames) ---------------------------------------------------
-// m = (c, kh, kw), n = o, k = (f, oy, ox); rollout frames only.
+// m = (c, kh, kw), n = o, k = (f, oy, ox); rollout frames only.  The byte operand comes from
+// the caller's buffer (no zero page): groups past the k-range are zeroed after the load.
 struct Conv1Wgrad : ProblemBase {
     static constexpr int BM = 256, BN = 32, BK = 16, WM = 4, WN = 1;
     static constexpr bool A_KC = false, B_KC = false;
     static constexpr bool SUM_B = true;
     static constexpr int PART = KW1 * C1 + C1;
     typedef uint32_t ARaw;
+    typedef WalkCtx CtxA;
+    struct CtxB { unsigned off; int k; };
     const uint8_t *obs;
-    const float *dz1;
+    const float *dz1;               // preceded by ZERO_PAGE zeros
     float *ws;
     int M, fps;
     const uint8_t *o_;
-    const float *dz_;
+    const float *zdz_;
     float *out_;
+    unsigned bbase_;
     __device__ void bind(int agent, int split)
     {
         o_ = obs + (long)agent * M * FRAME;
-        dz_ = dz1 + (long)agent * M * A1SZ;
+        zdz_ = dz1 - ZERO_PAGE;
+        bbase_ = ZPB + (unsigned)agent * (unsigned)(M * A1SZ) * 4u;
         out_ = ws + ((long)agent * splits + split) * PART;
         k0 = split * fps * P1;
         k1 = min(M, (split + 1) * fps) * P1;
     }
-    __device__ uint32_t fetch_a(int m, int k, bool &ok) const
+    __device__ void prep_a(CtxA &c, int m, int kl) const
     {
-        const int f = k / P1, p = k % P1, oy = p / W1, ox = p % W1;
-        const int c = m >> 6, kh = (m >> 3) & 7, kw = m & 7;
-        return ldg_u8x4(o_, (long)f * FRAME + c * (H0 * W0) + (oy * S1 + kh) * W0 + ox * S1 + kw, ok);
+        c.moff = (unsigned)((m >> 6) * (H0 * W0) + ((m >> 3) & 7) * W0 + (m & 7));
+        c.k = k0 + kl;
+        c.p = c.k % P1;
+        c.foff = (unsigned)(c.k / P1) * (unsigned)FRAME;
     }
-    __device__ void decode_a(float (&r)[4], uint32_t w) const { unpack_u8(r, w); }
-    __device__ float4 fetch_b(int k, int n, bool &ok) const { return ldg4(dz_, (long)k * C1 + n, ok); }
+    __device__ uint32_t fetch_a(CtxA &c, int, bool &ok) const
+    {
+        const int oy = c.p / W1, ox = c.p - oy * W1;
+        ok = c.k < k1;
+        const uint32_t v = ldg_u32b(o_, ok ? c.moff + c.foff + (unsigned)((oy * S1) * W0 + ox * S1) : 0u);
+        c.k += BK; c.p += BK;
+        if (c.p >= P1) { c.p -= P1; c.foff += (unsigned)FRAME; }
+        return v;
+    }
+    __device__ void decode_a(float (&r)[4], uint32_t w, bool ok) const { unpack_u8(r, ok ? w : 0u); }
+    __device__ void prep_b(CtxB &c, int kl, int n) const
+    {
+        c.k = k0 + kl;
+        c.off = bbase_ + (unsigned)((c.k * C1 + n) * 4);
+    }
+    __device__ float4 fetch_b(CtxB &c, int, bool &) const
+    {
+        const float4 v = ldg4b(zdz_, c.k < k1 ? c.off : 0u);
+        c.k += BK; c.off += (unsigned)(BK * C1 * 4);
+        return v;
+    }
     __device__ bool tile_full(int, int) const { return true; }
     template <bool CHECK> __device__ void store4(int m, int n, float4 v, float4, float4) const
     {
-        st4(out_ + (long)m * C1 + n, v);
+        st4(out_ + (long)m * C1 + n, scale4(v, STATE_SCALE));
     }
     __device__ void store_sum_b(int n, float v) const { out_[KW1 * C1 + n] = v; }
 };

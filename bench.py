@@ -24,6 +24,41 @@ MACS = dict(conv1=3_276_800, conv2=2_654_208, conv3=1_806_336, fc=1_605_632)
 PEAK_MFMA_F32_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0
 
+# event-timed phase -> kernel name in the rocprofv3 summaries under profiles/
+KERNEL_OF_PHASE = {
+    "conv1_fwd": "igemm_kernel<Conv1Fwd>",
+    "conv2_fwd": "igemm_kernel<ConvFwd<32, 20, 20, 64, 9, 9, 4, 2> >",
+    "conv3_fwd": "igemm_kernel<ConvFwd<64, 9, 9, 64, 7, 7, 3, 1> >",
+    "fc_fwd": "igemm_kernel<FcFwd>", "fc_wgrad": "igemm_kernel<FcWgrad>", "fc_dgrad": "igemm_kernel<FcDgrad>",
+    "conv3_wgrad": "igemm_kernel<ConvWgrad<64, 9, 9, 64, 7, 7, 3, 1, 64> >", "conv3_dgrad": "igemm_kernel<Conv3Dgrad>",
+    "conv2_wgrad": "igemm_kernel<ConvWgrad<32, 20, 20, 64, 9, 9, 4, 2, 128> >", "conv2_dgrad": "igemm_kernel<Conv2Dgrad>",
+    "conv1_wgrad": "igemm_kernel<Conv1Wgrad>", "grad_norm": "sumsq_kernel", "clip_rmsprop": "rmsprop_kernel",
+    "gossip_mix": "mix_kernel", "gossip_publish": "copy_kernel",
+}
+
+
+def measured_traffic(phase: str, config: int):
+    """HBM bytes per launch of the kernel behind `phase` from the committed FETCH_SIZE / WRITE_SIZE
+    summary, or None when there is none for this workload or the kernel sources changed since."""
+    import glob
+    import hashlib
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_n32_exp_5x16_fp32.txt")
+    if config != 4 or not os.path.exists(path):
+        return None
+    rec = None
+    for line in open(path):
+        if line.startswith("JSON "):
+            rec = json.loads(line[5:])
+    if rec is None:
+        return None
+    sha = hashlib.sha256()
+    for fn in sorted(glob.glob(os.path.join(ROOT, "paper_1906_04585_amd", "csrc", "*.h*"))):
+        sha.update(open(fn, "rb").read())
+    if sha.hexdigest() != rec["source_sha256"]:
+        return None
+    k = rec["kernels"].get(KERNEL_OF_PHASE.get(phase, ""))
+    return k["bytes"] if k else None
+
 
 def kernel_work(N: int, M: int, F: int, d: int, tau: int) -> dict:
     """Algorithmic work of one launch of each kernel: ('mfma', flop) or ('hbm', bytes)."""
@@ -124,12 +159,12 @@ def main() -> int:
     dur = acc[dominant] * 1e-3
     if kind == "mfma":
         roofline = dict(kernel=dominant, bound="mfma", achieved=amount / dur / 1e12, peak=PEAK_MFMA_F32_TFLOPS,
-                        unit="TFLOP/s", frac=amount / dur / 1e12 / PEAK_MFMA_F32_TFLOPS, traffic=None,
-                        avg_launch_ms=acc[dominant])
+                        unit="TFLOP/s", frac=amount / dur / 1e12 / PEAK_MFMA_F32_TFLOPS,
+                        traffic=measured_traffic(dominant, args.config), avg_launch_ms=acc[dominant])
     else:
         roofline = dict(kernel=dominant, bound="hbm", achieved=amount / dur / 1e9, peak=PEAK_HBM_GBS,
-                        unit="GB/s", frac=amount / dur / 1e9 / PEAK_HBM_GBS, traffic=None,
-                        avg_launch_ms=acc[dominant])
+                        unit="GB/s", frac=amount / dur / 1e9 / PEAK_HBM_GBS,
+                        traffic=measured_traffic(dominant, args.config), avg_launch_ms=acc[dominant])
     mfma_ms = sum(acc[k] for k in acc if k in work and work[k][0] == "mfma")
     mfma_flop = sum(work[k][1] for k in acc if k in work and work[k][0] == "mfma")
     hbm_ms = sum(acc[k] for k in acc if k in work and work[k][0] == "hbm")
@@ -145,17 +180,18 @@ def main() -> int:
     if not args.no_cpu_baseline:
         from oracle import gala_oracle as orc
         threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
-        n_s = min(N, 16)                       # a bounded sample: one round of the first 16 agents
+        n_s, n_r = min(N, 32), 2               # a bounded sample: two rounds of (up to) 32 agents
         om = orc.OracleGala(net, n_s, T, B, gs.HPARAMS, cfg["topology"])
         om.set_params(X0[:n_s])
-        ro = gs.rollout(net, n_s, T, B, gs.round_seed(args.config, 0))
+        ros = [gs.rollout(net, n_s, T, B, gs.round_seed(args.config, r)) for r in range(n_r)]
         t0 = time.perf_counter()
-        om.learner_step(ro["obs"], ro["actions"], ro["rewards"], ro["dones"], ro["boot_obs"])
-        om.gossip(0)
+        for r, ro in enumerate(ros):
+            om.learner_step(ro["obs"], ro["actions"], ro["rewards"], ro["dones"], ro["boot_obs"])
+            om.gossip(r)
         cpu_t = time.perf_counter() - t0
-        cpu_baseline = dict(value=n_s / cpu_t, unit="agent-steps/s", cores=threads, kind="oracle",
-                            sample=f"one round (learner step + gossip) of {n_s} of the {N} agents, "
-                                   f"{n_s * M} frames, fp64, {cpu_t:.2f} s")
+        cpu_baseline = dict(value=n_s * n_r / cpu_t, unit="agent-steps/s", cores=threads, kind="oracle",
+                            sample=f"{n_r} rounds (learner step + gossip) of {n_s} of the {N} agents, "
+                                   f"{n_s * n_r * M} frames, fp64, {cpu_t:.2f} s wall on {threads} threads")
 
     out = {
         "metric": "agent learner-steps/sec (one learner step + one gossip round per agent)",

@@ -21,7 +21,7 @@ if ROOT not in sys.path:
 
 # MACs per frame of each layer (unpadded 8x8/4, 4x4/2, 3x3/1 convolutions on 4x84x84, 512 hidden)
 MACS = dict(conv1=3_276_800, conv2=2_654_208, conv3=1_806_336, fc=1_605_632)
-PEAK_MFMA_F32_TFLOPS = 157.3
+PEAK_MFMA_TFLOPS = {"f32": 157.3, "bf16": 2500.0}     # dense matrix-instruction peaks of MI355X
 PEAK_HBM_GBS = 8000.0
 
 # event-timed phase -> kernel name in the rocprofv3 summaries under profiles/
@@ -37,13 +37,13 @@ KERNEL_OF_PHASE = {
 }
 
 
-def measured_traffic(phase: str, config: int):
+def measured_traffic(phase: str, config: int, dtype: str):
     """HBM bytes per launch of the kernel behind `phase` from the committed FETCH_SIZE / WRITE_SIZE
     summary, or None when there is none for this workload or the kernel sources changed since."""
     import glob
     import hashlib
     path = os.path.join(ROOT, "profiles", "hbm_traffic_n32_exp_5x16_fp32.txt")
-    if config != 4 or not os.path.exists(path):
+    if config != 4 or dtype != "f32" or not os.path.exists(path):
         return None
     rec = None
     for line in open(path):
@@ -82,6 +82,8 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=300)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=4, help="workload shape 1..5 (default: 32 agents)")
+    ap.add_argument("--dtype", choices=["f32", "bf16"], default="f32",
+                    help="matrix-instruction operand type of the conv/fc kernels (parameters stay fp32)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-rounds", type=int, default=20)
     args = ap.parse_args()
@@ -103,7 +105,9 @@ def main() -> int:
     N, A, T, B = cfg["n_agents"], cfg["n_actions"], cfg["T"], cfg["B"]
     M, F = T * B, T * B + B
     net = gs.make_net(A)
-    gpu = Gala(N, A, T, B, gs.HPARAMS, cfg["topology"], max_delay=cfg["max_delay"], delay_seed=7)
+    hparams = dict(gs.HPARAMS, compute_dtype=1 if args.dtype == "bf16" else 0)
+    peak_mfma = PEAK_MFMA_TFLOPS[args.dtype]
+    gpu = Gala(N, A, T, B, hparams, cfg["topology"], max_delay=cfg["max_delay"], delay_seed=7)
     X0 = gs.init_params(net, N, shared=True)
     gpu.set_params(X0)
     pool = []
@@ -149,7 +153,7 @@ def main() -> int:
             kind, amount = work[k]
             if kind == "mfma":
                 ent.update(bound="mfma", achieved=round(amount / (ms * 1e-3) / 1e12, 2), unit="TFLOP/s",
-                           frac=round(amount / (ms * 1e-3) / 1e12 / PEAK_MFMA_F32_TFLOPS, 4))
+                           frac=round(amount / (ms * 1e-3) / 1e12 / peak_mfma, 4))
             else:
                 ent.update(bound="hbm", achieved=round(amount / (ms * 1e-3) / 1e9, 1), unit="GB/s",
                            frac=round(amount / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4))
@@ -158,20 +162,20 @@ def main() -> int:
     kind, amount = work[dominant]
     dur = acc[dominant] * 1e-3
     if kind == "mfma":
-        roofline = dict(kernel=dominant, bound="mfma", achieved=amount / dur / 1e12, peak=PEAK_MFMA_F32_TFLOPS,
-                        unit="TFLOP/s", frac=amount / dur / 1e12 / PEAK_MFMA_F32_TFLOPS,
-                        traffic=measured_traffic(dominant, args.config), avg_launch_ms=acc[dominant])
+        roofline = dict(kernel=dominant, bound="mfma", achieved=amount / dur / 1e12, peak=peak_mfma,
+                        unit="TFLOP/s", frac=amount / dur / 1e12 / peak_mfma,
+                        traffic=measured_traffic(dominant, args.config, args.dtype), avg_launch_ms=acc[dominant])
     else:
         roofline = dict(kernel=dominant, bound="hbm", achieved=amount / dur / 1e9, peak=PEAK_HBM_GBS,
                         unit="GB/s", frac=amount / dur / 1e9 / PEAK_HBM_GBS,
-                        traffic=measured_traffic(dominant, args.config), avg_launch_ms=acc[dominant])
+                        traffic=measured_traffic(dominant, args.config, args.dtype), avg_launch_ms=acc[dominant])
     mfma_ms = sum(acc[k] for k in acc if k in work and work[k][0] == "mfma")
     mfma_flop = sum(work[k][1] for k in acc if k in work and work[k][0] == "mfma")
     hbm_ms = sum(acc[k] for k in acc if k in work and work[k][0] == "hbm")
     hbm_bytes = sum(work[k][1] for k in acc if k in work and work[k][0] == "hbm")
     phase_summary = dict(
         conv_fc=dict(ms=round(mfma_ms, 4), tflops=round(mfma_flop / (mfma_ms * 1e-3) / 1e12, 2),
-                     frac_mfma_f32=round(mfma_flop / (mfma_ms * 1e-3) / 1e12 / PEAK_MFMA_F32_TFLOPS, 4)),
+                     frac_mfma=round(mfma_flop / (mfma_ms * 1e-3) / 1e12 / peak_mfma, 4)),
         optimizer_gossip=dict(ms=round(hbm_ms, 4), gbs=round(hbm_bytes / (hbm_ms * 1e-3) / 1e9, 1),
                               frac_hbm=round(hbm_bytes / (hbm_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)),
         other_ms=round(sum(acc.values()) - mfma_ms - hbm_ms, 4))
@@ -205,10 +209,11 @@ def main() -> int:
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f32",
+        "dtype": args.dtype,
         "data": "synthetic",
         "config": {"workload": f"N={N} agents, 1-peer {cfg['topology']} graph, Nature-CNN, {A} actions, "
-                               f"rollout {T}x{B} per agent ({N * M} frames/round), fp32",
+                               f"rollout {T}x{B} per agent ({N * M} frames/round), "
+                               f"{'fp32' if args.dtype == 'f32' else 'bf16 operands / fp32 accumulation'}",
                    "n_agents": N, "T": T, "B": B, "n_actions": A, "topology": cfg["topology"],
                    "max_delay": cfg["max_delay"]},
         "roofline": roofline,

@@ -64,7 +64,8 @@ typedef struct {
     float gamma, vf_coef, ent_coef;
     float lr, rms_alpha, rms_eps;
     float max_grad_norm;
-    int   compute_dtype;       /* 0 = fp32 (the only value accepted by this build) */
+    int   compute_dtype;       /* 0 = fp32 matrix instructions; 1 = conv/fc operands rounded to bf16
+                                  (fp32 parameters, activations and accumulation; everything else fp32) */
 } gala_hparams;
 
 #define GALA_TOPO_RING      0   /* directed ring v1->v2->...->vn->v1: agent i receives from i-1 (Fig. 5) */

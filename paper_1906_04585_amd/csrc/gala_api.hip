@@ -141,7 +141,8 @@ extern "C" int gala_create(gala_ctx **out, int n_agents, const gala_topology *to
         return fail(nullptr, GALA_EINVAL, "only the 4x84x84 -> 32/64/64 -> 512 network is supported");
     if (net->n_actions < 1 || net->n_actions > 64) return fail(nullptr, GALA_EINVAL, "n_actions must be in [1, 64]");
     if (hp->T < 1 || hp->B < 1 || (long)hp->T * hp->B > 4096) return fail(nullptr, GALA_EINVAL, "need T, B >= 1 and T*B <= 4096");
-    if (hp->compute_dtype != 0) return fail(nullptr, GALA_EINVAL, "compute_dtype %d not available (0 = fp32)", hp->compute_dtype);
+    if (hp->compute_dtype != 0 && hp->compute_dtype != 1)
+        return fail(nullptr, GALA_EINVAL, "compute_dtype %d not available (0 = fp32, 1 = bf16 MFMA)", hp->compute_dtype);
     if (!(hp->rms_eps > 0.f) || !(hp->rms_alpha >= 0.f && hp->rms_alpha < 1.f) || !(hp->max_grad_norm > 0.f))
         return fail(nullptr, GALA_EINVAL, "need rms_eps > 0, 0 <= rms_alpha < 1, max_grad_norm > 0");
 
@@ -157,7 +158,7 @@ extern "C" int gala_create(gala_ctx **out, int n_agents, const gala_topology *to
         return fail(nullptr, GALA_EINVAL, "internal layout: bias does not follow its weight tensor");
     }
     c->hp = HParams{hp->T, hp->B, hp->gamma, hp->vf_coef, hp->ent_coef, hp->lr, hp->rms_alpha, hp->rms_eps,
-                    hp->max_grad_norm};
+                    hp->max_grad_norm, hp->compute_dtype};
     c->M = hp->T * hp->B;
     c->F = c->M + hp->B;
     c->stream = static_cast<hipStream_t>(hip_stream);
@@ -261,6 +262,7 @@ extern "C" int gala_learner_step(gala_ctx *c, const uint8_t *obs_u8, const int32
     NetArgs a{};
     a.N = c->N; a.M = c->M; a.F = c->F; a.Bn = c->hp.B; a.L = c->L;
     a.x = c->b.x[c->cur]; a.b = c->b; a.obs = obs_u8; a.boot = bootstrap_obs;
+    a.bf16 = c->hp.compute_dtype == 1;
     PhaseTimer *pt = &c->timer;
     pt->begin();
     HIP_OK(c, launch_forward(a, c->stream, pt));

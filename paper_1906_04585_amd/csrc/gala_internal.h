@@ -66,6 +66,7 @@ SegmentTable make_segments(const Layout &L);
 struct HParams {
     int T, B;
     float gamma, vf_coef, ent_coef, lr, rms_alpha, rms_eps, max_grad_norm;
+    int compute_dtype;           // 0 = fp32 MFMA, 1 = bf16 MFMA with fp32 master weights and accumulation
 };
 
 // Device buffers of one context.  M = T*B rollout frames, F = M + B frames incl. bootstrap.
@@ -123,7 +124,7 @@ struct NetArgs {
     const float *x;              // current parameters
     Buffers b;
     const uint8_t *obs, *boot;
-    int cu_count;
+    bool bf16;                   // conv/fc operands rounded to bf16 in LDS, fp32 accumulation
 };
 
 hipError_t launch_forward(const NetArgs &a, hipStream_t s, PhaseTimer *pt);

@@ -1,4 +1,5 @@
-// Agent-grouped implicit-GEMM on the gfx950 matrix cores (fp32 MFMA, 32x32x2 or 16x16x4 blocks).
+// Agent-grouped implicit-GEMM on the gfx950 matrix cores (fp32 MFMA in 32x32x2 or 16x16x4
+// blocks; optionally bf16 operands with fp32 accumulation).
 //
 // One launch computes, for every agent, C[m][n] = sum_k A[m][k] * B[k][n] where A and
 // B are *views* described by a problem functor P (im2col of an activation tensor, a
@@ -87,7 +88,23 @@ template <> struct MfmaBlock<true> {
     static __device__ __forceinline__ int row(int v, int lk) { return 4 * lk + v; }
 };
 
-template <class P>
+typedef __bf16 gala_bf16x2 __attribute__((ext_vector_type(2)));
+typedef float gala_f32x2 __attribute__((ext_vector_type(2)));
+typedef short gala_s16x4 __attribute__((ext_vector_type(4)));
+
+// two floats -> two bf16 (round to nearest even) packed in 32 bits
+static __device__ __forceinline__ unsigned gala_pack_bf16(float lo, float hi)
+{
+    gala_f32x2 v = {lo, hi};
+    gala_bf16x2 b = __builtin_convertvector(v, gala_bf16x2);
+    return *reinterpret_cast<unsigned *>(&b);
+}
+
+// BF16 = true: the same tiling with operands rounded to bf16 when they are staged into LDS
+// (fp32 in HBM, fp32 accumulation): LDS tiles become [row][k] with k contiguous, one lane
+// reads its four consecutive k as 8 bytes, and each 16x16 block takes one
+// v_mfma_f32_16x16x16_bf16 per 16 k.
+template <class P, bool BF16>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void igemm_kernel(P p, int n_agents)
 {
     constexpr int BM = P::BM, BN = P::BN, BK = P::BK;
@@ -112,6 +129,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void i
     __shared__ __attribute__((aligned(16))) float smem[LDS_FLOATS];
     auto As = [&](int buf, int k, int c) -> float & { return smem[(buf * BK + k) * SA + c]; };
     auto Bs = [&](int buf, int k, int c) -> float & { return smem[OFFB + (buf * BK + k) * SB + c]; };
+    // bf16 tiles: [buf][row][BK + 4] shorts (the padding keeps 8-byte alignment and spreads banks)
+    static_assert(!BF16 || (P::MFMA16 && BK % 16 == 0), "bf16 path: 16x16x16 blocks");
+    constexpr int BKP = BK + 4;
+    constexpr int OFFBH = 2 * BM * BKP;
+    static_assert(!BF16 || (2 * (BM + BN) * BKP * 2 <= LDS_FLOATS * 4), "bf16 tiles fit the allocation");
+    unsigned short *hs = reinterpret_cast<unsigned short *>(smem);
+    auto Ah = [&](int buf, int m, int k) -> unsigned short & { return hs[(buf * BM + m) * BKP + k]; };
+    auto Bh = [&](int buf, int n, int k) -> unsigned short & { return hs[OFFBH + (buf * BN + n) * BKP + k]; };
 
     const int bid = blockIdx.x;
     const int xcd = bid & 7, slot = bid >> 3;
@@ -187,17 +212,28 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void i
 #pragma unroll
                     for (int j = 0; j < 4; ++j) r[j] = oka[i] ? r[j] : 0.f;
                 }
-                if (P::A_KC) {
+                if (BF16 && P::A_KC) {
+                    const int row = g / (BK / 4), kq = g % (BK / 4);
+                    *reinterpret_cast<uint2 *>(&Ah(buf, row, kq * 4)) =
+                        make_uint2(gala_pack_bf16(r[0], r[1]), gala_pack_bf16(r[2], r[3]));
+                } else if (BF16) {
+                    const int k = g / (BM / 4), mq = g % (BM / 4);
+                    const unsigned p01 = gala_pack_bf16(r[0], r[1]), p23 = gala_pack_bf16(r[2], r[3]);
+                    Ah(buf, mq * 4 + 0, k) = (unsigned short)(p01 & 0xffffu);
+                    Ah(buf, mq * 4 + 1, k) = (unsigned short)(p01 >> 16);
+                    Ah(buf, mq * 4 + 2, k) = (unsigned short)(p23 & 0xffffu);
+                    Ah(buf, mq * 4 + 3, k) = (unsigned short)(p23 >> 16);
+                } else if (P::A_KC) {
                     const int row = g / (BK / 4), kq = g % (BK / 4);
 #pragma unroll
                     for (int j = 0; j < 4; ++j) As(buf, kq * 4 + j, row) = r[j];
                 } else {
                     const int k = g / (BM / 4), mq = g % (BM / 4);
                     *reinterpret_cast<float4 *>(&As(buf, k, mq * 4)) = make_float4(r[0], r[1], r[2], r[3]);
-                    if (P::SUM_A && do_sum_a) {     // summed here, not at fetch, so the loads stay in flight
+                }
+                if (!P::A_KC && P::SUM_A && do_sum_a) {     // summed here, not at fetch, so the loads stay in flight
 #pragma unroll
-                        for (int j = 0; j < 4; ++j) sum_a[j] += r[j];
-                    }
+                    for (int j = 0; j < 4; ++j) sum_a[j] += r[j];
                 }
             }
         }
@@ -211,17 +247,28 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void i
 #pragma unroll
                     for (int j = 0; j < 4; ++j) r[j] = okb[i] ? r[j] : 0.f;
                 }
-                if (P::B_KC) {
+                if (BF16 && P::B_KC) {
+                    const int col = g / (BK / 4), kq = g % (BK / 4);
+                    *reinterpret_cast<uint2 *>(&Bh(buf, col, kq * 4)) =
+                        make_uint2(gala_pack_bf16(r[0], r[1]), gala_pack_bf16(r[2], r[3]));
+                } else if (BF16) {
+                    const int k = g / (BN / 4), nq = g % (BN / 4);
+                    const unsigned p01 = gala_pack_bf16(r[0], r[1]), p23 = gala_pack_bf16(r[2], r[3]);
+                    Bh(buf, nq * 4 + 0, k) = (unsigned short)(p01 & 0xffffu);
+                    Bh(buf, nq * 4 + 1, k) = (unsigned short)(p01 >> 16);
+                    Bh(buf, nq * 4 + 2, k) = (unsigned short)(p23 & 0xffffu);
+                    Bh(buf, nq * 4 + 3, k) = (unsigned short)(p23 >> 16);
+                } else if (P::B_KC) {
                     const int col = g / (BK / 4), kq = g % (BK / 4);
 #pragma unroll
                     for (int j = 0; j < 4; ++j) Bs(buf, kq * 4 + j, col) = r[j];
                 } else {
                     const int k = g / (BN / 4), nq = g % (BN / 4);
                     *reinterpret_cast<float4 *>(&Bs(buf, k, nq * 4)) = make_float4(r[0], r[1], r[2], r[3]);
-                    if (P::SUM_B && do_sum_b) {
+                }
+                if (!P::B_KC && P::SUM_B && do_sum_b) {
 #pragma unroll
-                        for (int j = 0; j < 4; ++j) sum_b[j] += r[j];
-                    }
+                    for (int j = 0; j < 4; ++j) sum_b[j] += r[j];
                 }
             }
         }
@@ -251,17 +298,35 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void i
         // keep the global loads of the next tile ahead of this tile's MFMAs: without the fence
         // the scheduler sinks them next to their first use and their latency is exposed
         __builtin_amdgcn_sched_barrier(0);
+        if constexpr (BF16) {
 #pragma unroll
-        for (int kk = 0; kk < BK; kk += Blk::KS) {
-            float a[BI], b[BJ];
+            for (int kk = 0; kk < BK; kk += 16) {
+                gala_s16x4 a[BI], b[BJ];
 #pragma unroll
-            for (int i = 0; i < BI; ++i) a[i] = As(buf, kk + lk, wm0 + i * MB + lr);
+                for (int i = 0; i < BI; ++i)
+                    a[i] = *reinterpret_cast<const gala_s16x4 *>(&Ah(buf, wm0 + i * MB + lr, kk + lk * 4));
 #pragma unroll
-            for (int j = 0; j < BJ; ++j) b[j] = Bs(buf, kk + lk, wn0 + j * MB + lr);
+                for (int j = 0; j < BJ; ++j)
+                    b[j] = *reinterpret_cast<const gala_s16x4 *>(&Bh(buf, wn0 + j * MB + lr, kk + lk * 4));
 #pragma unroll
-            for (int i = 0; i < BI; ++i)
+                for (int i = 0; i < BI; ++i)
 #pragma unroll
-                for (int j = 0; j < BJ; ++j) acc[i][j] = Blk::mma(a[i], b[j], acc[i][j]);
+                    for (int j = 0; j < BJ; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a[i], b[j], acc[i][j], 0, 0, 0);
+            }
+        } else {
+#pragma unroll
+            for (int kk = 0; kk < BK; kk += Blk::KS) {
+                float a[BI], b[BJ];
+#pragma unroll
+                for (int i = 0; i < BI; ++i) a[i] = As(buf, kk + lk, wm0 + i * MB + lr);
+#pragma unroll
+                for (int j = 0; j < BJ; ++j) b[j] = Bs(buf, kk + lk, wn0 + j * MB + lr);
+#pragma unroll
+                for (int i = 0; i < BI; ++i)
+#pragma unroll
+                    for (int j = 0; j < BJ; ++j) acc[i][j] = Blk::mma(a[i], b[j], acc[i][j]);
+            }
         }
         if (kt + 1 < nkt) stage(std::integral_constant<int, buf ^ 1>{});
         __syncthreads();
@@ -345,10 +410,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void i
 }
 
 template <class P>
-static inline hipError_t igemm_launch(const P &p, int n_agents, hipStream_t stream)
+static inline hipError_t igemm_launch(const P &p, int n_agents, hipStream_t stream, bool bf16 = false)
 {
     const int agents_pad = (n_agents + 7) / 8 * 8;
     const int grid = agents_pad * p.tiles_m * p.tiles_n * p.splits;
-    hipLaunchKernelGGL(igemm_kernel<P>, dim3(grid), dim3(256), 0, stream, p, n_agents);
+    if (bf16) hipLaunchKernelGGL((igemm_kernel<P, true>), dim3(grid), dim3(256), 0, stream, p, n_agents);
+    else hipLaunchKernelGGL((igemm_kernel<P, false>), dim3(grid), dim3(256), 0, stream, p, n_agents);
     return hipGetLastError();
 }

@@ -705,21 +705,21 @@ hipError_t launch_forward(const NetArgs &a, hipStream_t s, PhaseTimer *pt)
         p.obs = a.obs; p.boot = a.boot; p.x = a.x; p.a1 = a.b.a1; p.d_pad = L.d_pad; p.w_off = L.w1; p.b_off = L.b1;
         p.M = a.M; p.F = a.F; p.Bn = a.Bn;
         p.tiles_m = cdiv((long)a.F * P1, Conv1Fwd::BM); p.tiles_n = 1; p.splits = 1;
-        GALA_TRY(igemm_launch(p, a.N, s));
+        GALA_TRY(igemm_launch(p, a.N, s, a.bf16));
         pt->mark("conv1_fwd");
     }
     {
         Conv2Fwd p{};
         p.in = a.b.a1; p.x = a.x; p.out = a.b.a2; p.d_pad = L.d_pad; p.w_off = L.w2; p.b_off = L.b2; p.F = a.F;
         p.tiles_m = cdiv((long)a.F * P2, Conv2Fwd::BM); p.tiles_n = 1; p.splits = 1;
-        GALA_TRY(igemm_launch(p, a.N, s));
+        GALA_TRY(igemm_launch(p, a.N, s, a.bf16));
         pt->mark("conv2_fwd");
     }
     {
         Conv3Fwd p{};
         p.in = a.b.a2; p.x = a.x; p.out = a.b.a3; p.d_pad = L.d_pad; p.w_off = L.w3; p.b_off = L.b3; p.F = a.F;
         p.tiles_m = cdiv((long)a.F * P3, Conv3Fwd::BM); p.tiles_n = 1; p.splits = 1;
-        GALA_TRY(igemm_launch(p, a.N, s));
+        GALA_TRY(igemm_launch(p, a.N, s, a.bf16));
         pt->mark("conv3_fwd");
     }
     {
@@ -727,7 +727,7 @@ hipError_t launch_forward(const NetArgs &a, hipStream_t s, PhaseTimer *pt)
         p.a3 = a.b.a3; p.x = a.x; p.ws = a.b.ws; p.d_pad = L.d_pad; p.w_off = L.fcw; p.F = a.F;
         p.kchunk = FC_KCHUNK;
         p.tiles_m = cdiv(a.F, FcFwd::BM); p.tiles_n = FC / FcFwd::BN; p.splits = cdiv(FLAT, FC_KCHUNK);
-        GALA_TRY(igemm_launch(p, a.N, s));
+        GALA_TRY(igemm_launch(p, a.N, s, a.bf16));
         pt->mark("fc_fwd");
         hipLaunchKernelGGL(fc_reduce_heads_kernel, dim3(a.F, a.N), dim3(128), 0, s, a.b.ws, p.splits, a.x, L,
                            a.M, a.F, a.b.h, a.b.logits, a.b.values);
@@ -752,7 +752,7 @@ hipError_t launch_backward(const NetArgs &a, hipStream_t s, PhaseTimer *pt)
         p.dzh = a.b.dzh; p.a3 = a.b.a3; p.g = a.b.g; p.d_pad = L.d_pad; p.w_off = L.fcw; p.b_off = L.fcb;
         p.M = a.M; p.F = a.F;
         p.tiles_m = FC / FcWgrad::BM; p.tiles_n = cdiv(FLAT, FcWgrad::BN); p.splits = 1;
-        GALA_TRY(igemm_launch(p, a.N, s));
+        GALA_TRY(igemm_launch(p, a.N, s, a.bf16));
         pt->mark("fc_wgrad");
     }
     {
@@ -760,7 +760,7 @@ hipError_t launch_backward(const NetArgs &a, hipStream_t s, PhaseTimer *pt)
         p.dzh = a.b.dzh; p.x = a.x; p.a3 = a.b.a3; p.dz3 = a.b.dz3; p.d_pad = L.d_pad; p.w_off = L.fcw;
         p.M = a.M; p.F = a.F;
         p.tiles_m = cdiv(a.M, FcDgrad::BM); p.tiles_n = cdiv(FLAT, FcDgrad::BN); p.splits = 1;
-        GALA_TRY(igemm_launch(p, a.N, s));
+        GALA_TRY(igemm_launch(p, a.N, s, a.bf16));
         pt->mark("fc_dgrad");
     }
     // conv3
@@ -768,7 +768,7 @@ hipError_t launch_backward(const NetArgs &a, hipStream_t s, PhaseTimer *pt)
         Conv3Wgrad p{};
         p.in = a.b.a2; p.dz = a.b.dz3; p.ws = a.b.ws; p.M = a.M; p.F = a.F; p.fps = FPS_CONV3;
         p.tiles_m = cdiv(KW3, Conv3Wgrad::BM); p.tiles_n = 1; p.splits = cdiv(a.M, FPS_CONV3);
-        GALA_TRY(igemm_launch(p, a.N, s));
+        GALA_TRY(igemm_launch(p, a.N, s, a.bf16));
         pt->mark("conv3_wgrad");
         GALA_TRY(reduce_splits(a.b.ws, p.splits, Conv3Wgrad::PART, a.N, a.b.g + L.w3, L.d_pad, nullptr, 0, 1, s));
         pt->mark("conv3_wgrad_reduce");
@@ -778,7 +778,7 @@ hipError_t launch_backward(const NetArgs &a, hipStream_t s, PhaseTimer *pt)
         p.dz3 = a.b.dz3; p.x = a.x; p.a2 = a.b.a2; p.dz2 = a.b.dz2; p.d_pad = L.d_pad; p.w_off = L.w3;
         p.M = a.M; p.F = a.F;
         p.tiles_m = cdiv((long)a.M * P2, Conv3Dgrad::BM); p.tiles_n = 1; p.splits = 1;
-        GALA_TRY(igemm_launch(p, a.N, s));
+        GALA_TRY(igemm_launch(p, a.N, s, a.bf16));
         pt->mark("conv3_dgrad");
     }
     // conv2
@@ -786,7 +786,7 @@ hipError_t launch_backward(const NetArgs &a, hipStream_t s, PhaseTimer *pt)
         Conv2Wgrad p{};
         p.in = a.b.a1; p.dz = a.b.dz2; p.ws = a.b.ws; p.M = a.M; p.F = a.F; p.fps = FPS_CONV2;
         p.tiles_m = cdiv(KW2, Conv2Wgrad::BM); p.tiles_n = 1; p.splits = cdiv(a.M, FPS_CONV2);
-        GALA_TRY(igemm_launch(p, a.N, s));
+        GALA_TRY(igemm_launch(p, a.N, s, a.bf16));
         pt->mark("conv2_wgrad");
         GALA_TRY(reduce_splits(a.b.ws, p.splits, Conv2Wgrad::PART, a.N, a.b.g + L.w2, L.d_pad, nullptr, 0, 1, s));
         pt->mark("conv2_wgrad_reduce");
@@ -796,7 +796,7 @@ hipError_t launch_backward(const NetArgs &a, hipStream_t s, PhaseTimer *pt)
         p.dz2 = a.b.dz2; p.x = a.x; p.a1 = a.b.a1; p.dz1 = a.b.dz1; p.d_pad = L.d_pad; p.w_off = L.w2;
         p.M = a.M; p.F = a.F;
         p.tiles_m = cdiv((long)a.M * Conv2Dgrad::PC, Conv2Dgrad::BM); p.tiles_n = 1; p.splits = 4;
-        GALA_TRY(igemm_launch(p, a.N, s));
+        GALA_TRY(igemm_launch(p, a.N, s, a.bf16));
         pt->mark("conv2_dgrad");
     }
     // conv1 (the input needs no gradient)
@@ -804,7 +804,7 @@ hipError_t launch_backward(const NetArgs &a, hipStream_t s, PhaseTimer *pt)
         Conv1Wgrad p{};
         p.obs = a.obs; p.dz1 = a.b.dz1; p.ws = a.b.ws; p.M = a.M; p.fps = FPS_CONV1;
         p.tiles_m = 1; p.tiles_n = 1; p.splits = cdiv(a.M, FPS_CONV1);
-        GALA_TRY(igemm_launch(p, a.N, s));
+        GALA_TRY(igemm_launch(p, a.N, s, a.bf16));
         pt->mark("conv1_wgrad");
         GALA_TRY(reduce_splits(a.b.ws, p.splits, Conv1Wgrad::PART, a.N, a.b.g + L.w1, L.d_pad, nullptr, 0, 1, s));
         pt->mark("conv1_wgrad_reduce");

@@ -58,7 +58,7 @@ def _create(n_agents=2, n_actions=6, topology="ring", **kw):
     (dict(in_c=3), "network"),
     (dict(fc=256), "network"),
     (dict(T=0), "T, B"),
-    (dict(compute_dtype=1), "compute_dtype"),
+    (dict(compute_dtype=2), "compute_dtype"),
     (dict(rms_eps=0.0), "rms_eps"),
     (dict(rms_alpha=1.0), "rms_alpha"),
     (dict(topology="exp", n_agents=6), "power-of-two"),

@@ -164,10 +164,29 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void i
     bool oka[PA], okb[PB];
     static_assert(!P::SUM_A || (!P::A_KC && 256 % (BM / 4) == 0), "SUM_A needs m-contiguous groups");
     static_assert(!P::SUM_B || (!P::B_KC && 256 % (BN / 4) == 0), "SUM_B needs n-contiguous groups");
-    float sum_a[4] = {0.f, 0.f, 0.f, 0.f}, sum_b[4] = {0.f, 0.f, 0.f, 0.f};
+    static_assert(!P::SUM_A || (BM / 4) % (256 / BK) == 0 || PA == 1, "SUM_A: one pass unless k is shared");
+    static_assert(!P::SUM_B || (BN / 4) % (256 / BK) == 0 || PB == 1, "SUM_B: one pass unless k is shared");
+    float sum_a[PA][4], sum_b[PB][4];
+#pragma unroll
+    for (int i = 0; i < PA; ++i) sum_a[i][0] = sum_a[i][1] = sum_a[i][2] = sum_a[i][3] = 0.f;
+#pragma unroll
+    for (int i = 0; i < PB; ++i) sum_b[i][0] = sum_b[i][1] = sum_b[i][2] = sum_b[i][3] = 0.f;
     const bool do_sum_a = P::SUM_A && tn == 0, do_sum_b = P::SUM_B && tm == 0;
 
     const int kb = p.k_begin(), ke = p.k_end();
+
+    // Group g of an operand read "4 consecutive m (n)" -> (local k, quad index).  When a k-row
+    // holds at least 256/BK quads, 256/BK consecutive threads share one k and a thread keeps
+    // that k for all of its groups, so whatever the functor derives from k (a position walked
+    // through frame, row, column) is computed once per thread and tile, not once per group.
+    constexpr int TPK = 256 / BK;                   // threads per k-row in that arrangement
+    auto map_mc = [&](auto qc, int i, int &kl, int &q) {
+        constexpr int Q = decltype(qc)::value;      // quads per k-row
+        if (Q % TPK == 0) { kl = tid / TPK; q = tid % TPK + TPK * i; }
+        else { const int g = tid + i * 256; kl = g / Q; q = g % Q; }
+    };
+    typedef std::integral_constant<int, BM / 4> QA;
+    typedef std::integral_constant<int, BN / 4> QB;
 
 #pragma unroll
     for (int i = 0; i < PA; ++i) {
@@ -175,7 +194,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void i
         oka[i] = true;
         if (GA % 256 == 0 || g < GA) {
             if (P::A_KC) p.prep_a(ca[i], m0 + g / (BK / 4), (g % (BK / 4)) * 4);
-            else p.prep_a(ca[i], m0 + (g % (BM / 4)) * 4, g / (BM / 4));
+            else { int kl, q; map_mc(QA{}, i, kl, q); p.prep_a(ca[i], m0 + q * 4, kl); }
         }
     }
 #pragma unroll
@@ -184,7 +203,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void i
         okb[i] = true;
         if (GB % 256 == 0 || g < GB) {
             if (P::B_KC) p.prep_b(cb[i], (g % (BK / 4)) * 4, n0 + g / (BK / 4));
-            else p.prep_b(cb[i], g / (BN / 4), n0 + (g % (BN / 4)) * 4);
+            else { int kl, q; map_mc(QB{}, i, kl, q); p.prep_b(cb[i], kl, n0 + q * 4); }
         }
     }
 
@@ -217,7 +236,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void i
                     *reinterpret_cast<uint2 *>(&Ah(buf, row, kq * 4)) =
                         make_uint2(gala_pack_bf16(r[0], r[1]), gala_pack_bf16(r[2], r[3]));
                 } else if (BF16) {
-                    const int k = g / (BM / 4), mq = g % (BM / 4);
+                    int k, mq; map_mc(QA{}, i, k, mq);
                     const unsigned p01 = gala_pack_bf16(r[0], r[1]), p23 = gala_pack_bf16(r[2], r[3]);
                     Ah(buf, mq * 4 + 0, k) = (unsigned short)(p01 & 0xffffu);
                     Ah(buf, mq * 4 + 1, k) = (unsigned short)(p01 >> 16);
@@ -228,12 +247,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void i
 #pragma unroll
                     for (int j = 0; j < 4; ++j) As(buf, kq * 4 + j, row) = r[j];
                 } else {
-                    const int k = g / (BM / 4), mq = g % (BM / 4);
+                    int k, mq; map_mc(QA{}, i, k, mq);
                     *reinterpret_cast<float4 *>(&As(buf, k, mq * 4)) = make_float4(r[0], r[1], r[2], r[3]);
                 }
                 if (!P::A_KC && P::SUM_A && do_sum_a) {     // summed here, not at fetch, so the loads stay in flight
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) sum_a[j] += r[j];
+                    for (int j = 0; j < 4; ++j) sum_a[i][j] += r[j];
                 }
             }
         }
@@ -252,7 +271,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void i
                     *reinterpret_cast<uint2 *>(&Bh(buf, col, kq * 4)) =
                         make_uint2(gala_pack_bf16(r[0], r[1]), gala_pack_bf16(r[2], r[3]));
                 } else if (BF16) {
-                    const int k = g / (BN / 4), nq = g % (BN / 4);
+                    int k, nq; map_mc(QB{}, i, k, nq);
                     const unsigned p01 = gala_pack_bf16(r[0], r[1]), p23 = gala_pack_bf16(r[2], r[3]);
                     Bh(buf, nq * 4 + 0, k) = (unsigned short)(p01 & 0xffffu);
                     Bh(buf, nq * 4 + 1, k) = (unsigned short)(p01 >> 16);
@@ -263,12 +282,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void i
 #pragma unroll
                     for (int j = 0; j < 4; ++j) Bs(buf, kq * 4 + j, col) = r[j];
                 } else {
-                    const int k = g / (BN / 4), nq = g % (BN / 4);
+                    int k, nq; map_mc(QB{}, i, k, nq);
                     *reinterpret_cast<float4 *>(&Bs(buf, k, nq * 4)) = make_float4(r[0], r[1], r[2], r[3]);
                 }
                 if (!P::B_KC && P::SUM_B && do_sum_b) {
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) sum_b[j] += r[j];
+                    for (int j = 0; j < 4; ++j) sum_b[i][j] += r[j];
                 }
             }
         }
@@ -336,34 +355,38 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void i
         if (kt + 1 < nkt) tile_step(std::integral_constant<int, 1>{}, kt + 1);
     }
 
-    // Operand sums: every thread holds partial sums of its four columns (rows); threads with
-    // the same group index are combined through LDS in a fixed order.
+    // Operand sums: every thread holds partial sums of the four rows (columns) of each of its
+    // groups; the threads that share a quad are combined through LDS in a fixed order.
     if (P::SUM_A || P::SUM_B) {
         float *red = smem;
         static_assert(LDS_FLOATS >= 1024, "LDS scratch for operand sums");
-        if (P::SUM_A && do_sum_a) {
-            constexpr int Q = BM / 4, R = 256 / Q;
+        auto reduce_quads = [&](auto qc, int i, const float (&part)[4], auto &&emit) {
+            constexpr int Q = decltype(qc)::value;
+            // quads of this pass and the threads that hold each of them
+            constexpr bool SHARED_K = Q % TPK == 0;
+            constexpr int QP = SHARED_K ? TPK : Q;            // distinct quads in one pass
+            constexpr int R = 256 / QP;                       // threads per quad
 #pragma unroll
-            for (int j = 0; j < 4; ++j) red[tid * 4 + j] = sum_a[j];
+            for (int j = 0; j < 4; ++j) red[tid * 4 + j] = part[j];
             __syncthreads();
-            if (tid < BM) {
+            if (tid < QP * 4) {
+                const int ql = tid / 4, j = tid & 3;          // thread t of a quad group has tid % QP == ql
                 float t = 0.f;
-                for (int r = 0; r < R; ++r) t += red[(r * Q + tid / 4) * 4 + (tid & 3)];
-                p.store_sum_a(m0 + tid, t);
+                for (int r = 0; r < R; ++r) t += red[(r * QP + ql) * 4 + j];
+                const int quad = SHARED_K ? ql + TPK * i : ql;
+                if (SHARED_K || i == 0) emit(quad * 4 + j, t);
             }
             __syncthreads();
+        };
+        if (P::SUM_A && do_sum_a) {
+#pragma unroll
+            for (int i = 0; i < PA; ++i)
+                reduce_quads(QA{}, i, sum_a[i], [&](int m, float v) { p.store_sum_a(m0 + m, v); });
         }
         if (P::SUM_B && do_sum_b) {
-            constexpr int Q = BN / 4, R = 256 / Q;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) red[tid * 4 + j] = sum_b[j];
-            __syncthreads();
-            if (tid < BN) {
-                float t = 0.f;
-                for (int r = 0; r < R; ++r) t += red[(r * Q + tid / 4) * 4 + (tid & 3)];
-                p.store_sum_b(n0 + tid, t);
-            }
-            __syncthreads();
+            for (int i = 0; i < PB; ++i)
+                reduce_quads(QB{}, i, sum_b[i], [&](int n, float v) { p.store_sum_b(n0 + n, v); });
         }
     }
 

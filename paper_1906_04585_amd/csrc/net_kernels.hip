@@ -201,7 +201,7 @@ struct FcFwd : ProblemBase {
 // ---- hidden layer: gradient to a3 (masked by its ReLU) ---------------------------------------
 // m = f, n = flattened a3 index, k = j.
 struct FcDgrad : ProblemBase {
-    static constexpr int BM = 96, BN = 128, BK = 16, WM = 1, WN = 4;
+    static constexpr int BM = 80, BN = 128, BK = 16, WM = 1, WN = 4;     // 5 x 16 rows: no padding at M = 80, 160
     static constexpr bool A_KC = true, B_KC = false;
     static constexpr bool HAS_AUX = true;
     const float *dzh, *x, *a3;

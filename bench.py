@@ -1,9 +1,11 @@
 #!/usr/bin/env python3
 """Throughput of the GALA-A2C hot path on one MI355X.
 
-A step is one round of Algorithm 1 for all agents: gala_learner_step (returns,
-A2C loss, forward/backward, clip, RMSprop for every agent) followed by gala_gossip
-(one mixing iteration over the 1-peer exponential graph).  Inputs are synthetic
+A step is one round of Algorithm 1 for all agents: returns, A2C loss, forward/backward,
+clip and RMSprop for every agent, then one mixing iteration over the 1-peer exponential
+graph.  --mode fused (default) issues it as one gala_round call, whose optimizer and mixing
+step share a kernel; --mode split as gala_learner_step followed by gala_gossip; both
+compute the same values bit for bit.  Inputs are synthetic
 Atari-shaped rollouts that are resident in HBM before the timed region starts; a
 pool of four rollouts is cycled.  One JSON line is printed on stdout.
 """
@@ -33,7 +35,7 @@ KERNEL_OF_PHASE = {
     "conv3_wgrad": "igemm_kernel<ConvWgrad<64, 9, 9, 64, 7, 7, 3, 1, 64> >", "conv3_dgrad": "igemm_kernel<Conv3Dgrad>",
     "conv2_wgrad": "igemm_kernel<ConvWgrad<32, 20, 20, 64, 9, 9, 4, 2, 128> >", "conv2_dgrad": "igemm_kernel<Conv2Dgrad>",
     "conv1_wgrad": "igemm_kernel<Conv1Wgrad>", "grad_norm": "sumsq_kernel", "clip_rmsprop": "rmsprop_kernel",
-    "gossip_mix": "mix_kernel", "gossip_publish": "copy_kernel",
+    "gossip_mix": "mix_kernel", "gossip_publish": "copy_kernel", "clip_rmsprop_mix": "rmsprop_mix_kernel<64>",
 }
 
 
@@ -68,11 +70,13 @@ def kernel_work(N: int, M: int, F: int, d: int, tau: int) -> dict:
         w[f"{layer}_wgrad"] = ("mfma", 2.0 * macs * M * N)
         if layer != "conv1":                     # the input needs no gradient
             w[f"{layer}_dgrad"] = ("mfma", 2.0 * macs * M * N)
-    w["grad_norm"] = ("hbm", 4.0 * d * N)        # read g
+    # the gradient norm is assembled from partial sums the weight-gradient kernels emit: no pass over g
     w["clip_rmsprop"] = ("hbm", 20.0 * d * N)    # read g, x, v; write x, v
     w["gossip_mix"] = ("hbm", 12.0 * d * N)      # read x_i, x_j; write x_i
     if tau > 0:
         w["gossip_publish"] = ("hbm", 8.0 * d * N)
+    # fused: read g, x, v; write v, x (+ write the history slot and read stale messages with delays)
+    w["clip_rmsprop_mix"] = ("hbm", (20.0 + (8.0 if tau > 0 else 0.0)) * d * N)
     return w
 
 
@@ -84,6 +88,8 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=4, help="workload shape 1..5 (default: 32 agents)")
     ap.add_argument("--dtype", choices=["f32", "bf16"], default="f32",
                     help="matrix-instruction operand type of the conv/fc kernels (parameters stay fp32)")
+    ap.add_argument("--mode", choices=["fused", "split"], default="fused",
+                    help="one gala_round call per step, or gala_learner_step + gala_gossip")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-rounds", type=int, default=20)
     args = ap.parse_args()
@@ -118,8 +124,11 @@ def main() -> int:
 
     def one_round(r):
         d = pool[r % len(pool)]
-        gpu.learner_step(d["obs"], d["actions"], d["rewards"], d["dones"], d["boot_obs"])
-        gpu.gossip(r)
+        if args.mode == "fused":
+            gpu.round(d["obs"], d["actions"], d["rewards"], d["dones"], d["boot_obs"], r)
+        else:
+            gpu.learner_step(d["obs"], d["actions"], d["rewards"], d["dones"], d["boot_obs"])
+            gpu.gossip(r)
 
     rnd = 0
     for _ in range(args.warmup):
@@ -215,7 +224,8 @@ def main() -> int:
                                f"rollout {T}x{B} per agent ({N * M} frames/round), "
                                f"{'fp32' if args.dtype == 'f32' else 'bf16 operands / fp32 accumulation'}",
                    "n_agents": N, "T": T, "B": B, "n_actions": A, "topology": cfg["topology"],
-                   "max_delay": cfg["max_delay"]},
+                   "max_delay": cfg["max_delay"],
+                   "calls": "gala_round" if args.mode == "fused" else "gala_learner_step + gala_gossip"},
         "roofline": roofline,
         "phases": phase_summary,
         "kernels": kernels,

@@ -190,7 +190,7 @@ extern "C" int gala_create(gala_ctx **out, int n_agents, const gala_topology *to
     ALLOC_ZP(b.dz2, N * M * A2SZ); ALLOC_ZP(b.dz1, N * M * A1SZ);
 #undef ALLOC_ZP
     ALLOC(b.ws, workspace_floats(c->N, c->M, c->F), false);
-    ALLOC(b.norm_part, N * NORM_BLOCKS, true);
+    ALLOC(b.norm_part, N * NORM_PARTS, true);
     ALLOC(b.stats, N * 5, true);
     ALLOC(b.cons_part, N * ((dp + CONS_COLS - 1) / CONS_COLS) + 2, true);
     ALLOC(b.peer, c->h_peer.size(), false); ALLOC(b.delay, c->h_delay.size(), false);
@@ -252,10 +252,10 @@ extern "C" int gala_set_opt_state(gala_ctx *c, const float *src, int dev) { retu
 extern "C" int gala_get_opt_state(gala_ctx *c, float *dst, int dev) { return c ? export_arena(c, c->b.v, dst, dev) : GALA_EINVAL; }
 extern "C" int gala_get_grads(gala_ctx *c, float *dst, int dev) { return c ? export_arena(c, c->b.g, dst, dev) : GALA_EINVAL; }
 
-extern "C" int gala_learner_step(gala_ctx *c, const uint8_t *obs_u8, const int32_t *actions, const float *rewards,
-                                 const uint8_t *dones, const uint8_t *bootstrap_obs)
+// forward, loss, backward and the per-agent gradient norm / clip factor
+static int enqueue_gradients(gala_ctx *c, const uint8_t *obs_u8, const int32_t *actions, const float *rewards,
+                             const uint8_t *dones, const uint8_t *bootstrap_obs)
 {
-    if (!c) return GALA_EINVAL;
     if (!obs_u8 || !actions || !rewards || !dones || !bootstrap_obs) return fail(c, GALA_EINVAL, "null input buffer");
     if ((reinterpret_cast<uintptr_t>(obs_u8) | reinterpret_cast<uintptr_t>(bootstrap_obs)) & 3)
         return fail(c, GALA_EINVAL, "observation buffers must be 4-byte aligned");
@@ -269,30 +269,69 @@ extern "C" int gala_learner_step(gala_ctx *c, const uint8_t *obs_u8, const int32
     HIP_OK(c, launch_loss(a, c->hp, actions, rewards, dones, c->stream));
     pt->mark("returns_loss");
     HIP_OK(c, launch_backward(a, c->stream, pt));
-    HIP_OK(c, launch_optimizer(c->N, c->L, c->hp, c->b.x[c->cur], c->b.v, c->b.g, c->b.norm_part, c->b.stats, c->stream, pt));
+    HIP_OK(c, launch_grad_norm(c->N, c->L, c->hp, c->b.g, c->b.norm_part, c->b.stats, c->stream));
+    pt->mark("grad_norm");
+    return GALA_OK;
+}
+
+static int check_round(gala_ctx *c, int64_t round)
+{
+    if (round < 0) return fail(c, GALA_EINVAL, "negative round");
+    // delayed messages are read from the history of consecutive rounds
+    if (c->tau > 0 && round != c->last_round + 1)
+        return fail(c, GALA_ESTATE, "with max_delay > 0 rounds must be consecutive from 0: got %lld after %lld",
+                    (long long)round, (long long)c->last_round);
+    if (round < c->last_round)
+        return fail(c, GALA_ESTATE, "gossip round went backwards: %lld after %lld", (long long)round, (long long)c->last_round);
+    return GALA_OK;
+}
+
+extern "C" int gala_learner_step(gala_ctx *c, const uint8_t *obs_u8, const int32_t *actions, const float *rewards,
+                                 const uint8_t *dones, const uint8_t *bootstrap_obs)
+{
+    if (!c) return GALA_EINVAL;
+    int rc = enqueue_gradients(c, obs_u8, actions, rewards, dones, bootstrap_obs);
+    if (rc != GALA_OK) return rc;
+    HIP_OK(c, launch_rmsprop(c->N, c->L, c->hp, c->b.x[c->cur], c->b.v, c->b.g, c->b.stats, c->stream));
+    c->timer.mark("clip_rmsprop");
     return GALA_OK;
 }
 
 extern "C" int gala_gossip(gala_ctx *c, int64_t round)
 {
     if (!c) return GALA_EINVAL;
-    if (round < 0) return fail(c, GALA_EINVAL, "negative round");
+    int rc = check_round(c, round);
+    if (rc != GALA_OK) return rc;
     if (c->tau > 0) {
-        // delayed messages are read from the history of consecutive rounds
-        if (round != c->last_round + 1)
-            return fail(c, GALA_ESTATE, "with max_delay > 0 rounds must be consecutive from 0: got %lld after %lld",
-                        (long long)round, (long long)c->last_round);
         float *slot = c->b.hist + (size_t)(round % (c->tau + 1)) * c->N * c->L.d_pad;
         HIP_OK(c, launch_publish(c->N, c->L, c->b.x[c->cur], slot, c->stream));
         c->timer.mark("gossip_publish");
-    } else if (round < c->last_round) {
-        return fail(c, GALA_ESTATE, "gossip round went backwards: %lld after %lld", (long long)round, (long long)c->last_round);
     }
     const int phase = (int)(round % c->n_phases);
     HIP_OK(c, launch_mix(c->N, c->L, c->b.x[c->cur], c->b.x[c->cur ^ 1], c->b.hist, c->tau, (long)round, phase,
                          c->max_in, c->b.peer, c->b.delay, c->b.weight, c->stream));
     c->timer.mark("gossip_mix");
     c->cur ^= 1;
+    c->last_round = round;
+    return GALA_OK;
+}
+
+extern "C" int gala_round(gala_ctx *c, const uint8_t *obs_u8, const int32_t *actions, const float *rewards,
+                          const uint8_t *dones, const uint8_t *bootstrap_obs, int64_t round)
+{
+    if (!c) return GALA_EINVAL;
+    int rc = check_round(c, round);
+    if (rc != GALA_OK) return rc;
+    if (!fused_mix_available(c->N)) {
+        rc = gala_learner_step(c, obs_u8, actions, rewards, dones, bootstrap_obs);
+        return rc != GALA_OK ? rc : gala_gossip(c, round);
+    }
+    rc = enqueue_gradients(c, obs_u8, actions, rewards, dones, bootstrap_obs);
+    if (rc != GALA_OK) return rc;
+    const int phase = (int)(round % c->n_phases);
+    HIP_OK(c, launch_rmsprop_mix(c->N, c->L, c->hp, c->b.x[c->cur], c->b.v, c->b.g, c->b.hist, c->tau, (long)round,
+                                 phase, c->max_in, c->b.peer, c->b.delay, c->b.weight, c->b.stats, c->stream));
+    c->timer.mark("clip_rmsprop_mix");
     c->last_round = round;
     return GALA_OK;
 }

@@ -81,14 +81,17 @@ struct Buffers {
     float *dlogits, *dvalues;         // [N][M][A], [N][M]
     float *dzh, *dz3, *dz2, *dz1;     // [N][M][..] pre-activation gradients
     float *ws;                        // split-K partial sums
-    float *norm_part;                 // [N][NORM_BLOCKS]
+    float *norm_part;                 // [N][NORM_PARTS]
     float *stats;                     // [N][5]
     float *cons_part;                 // [N][CONS_CHUNKS] + 2 results
     int32_t *peer, *delay;            // [phases][N][max_in]
     float *weight;                    // [phases][N][max_in+1]
 };
 
-constexpr int NORM_BLOCKS = 64;
+// Per-agent partial sums of squared gradients written by the hidden layer's weight-gradient
+// kernel, one per output tile (the first FC_WGRAD_TILES entries of a row are used).
+constexpr int NORM_PARTS = 128;
+constexpr int FC_WGRAD_TILES = 100;
 // Activation and gradient buffers (a1, a2, a3, h, dz1..dz3, dzh) are allocated with this many
 // zero floats in front of the data.  Kernels that must treat a group as zero (a padding tap
 // of a transposed convolution, the tail of a k-range) read it from there instead of masking.
@@ -133,8 +136,14 @@ hipError_t launch_loss(const NetArgs &a, const HParams &hp, const int32_t *actio
 hipError_t launch_backward(const NetArgs &a, hipStream_t s, PhaseTimer *pt);
 size_t workspace_floats(int N, int M, int F);
 
-hipError_t launch_optimizer(int N, const Layout &L, const HParams &hp, float *x, float *v, const float *g,
-                            float *norm_part, float *stats, hipStream_t s, PhaseTimer *pt);
+hipError_t launch_grad_norm(int N, const Layout &L, const HParams &hp, const float *g, const float *norm_part,
+                            float *stats, hipStream_t s);
+hipError_t launch_rmsprop(int N, const Layout &L, const HParams &hp, float *x, float *v, const float *g,
+                          const float *stats, hipStream_t s);
+bool fused_mix_available(int N);
+hipError_t launch_rmsprop_mix(int N, const Layout &L, const HParams &hp, float *x, float *v, const float *g,
+                              float *hist, int tau, long round, int phase, int max_in, const int32_t *peer,
+                              const int32_t *delay, const float *weight, const float *stats, hipStream_t s);
 hipError_t launch_publish(int N, const Layout &L, const float *x, float *hist_slot, hipStream_t s);
 hipError_t launch_mix(int N, const Layout &L, const float *x_in, float *x_out, const float *hist, int tau,
                       long round, int phase, int max_in, const int32_t *peer, const int32_t *delay,

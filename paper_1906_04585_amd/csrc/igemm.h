@@ -53,6 +53,12 @@
 //                                           store_sum_b(n, v); needs the operand in "4 consecutive
 //                                           m (n)" mode.  Used for bias gradients, which are exactly
 //                                           these sums of an operand the weight-gradient GEMM reads.
+//   static constexpr bool SUMSQ             optional: the workgroup also delivers the sum of
+//                                           squares of what it stored, through
+//                                           template <bool CHECK> float sumsq4(m, n, v) (the share of
+//                                           one float4 group) and store_sumsq(tile, total), tile =
+//                                           tm * tiles_n + tn; summed in a fixed order.  Lets a gradient
+//                                           producer supply its part of the gradient norm.
 //
 // Workgroup ids are interleaved over the 8 XCDs by the dispatcher; the decode below
 // keeps all tiles of one agent on one XCD so that its weights and activations are
@@ -398,6 +404,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void i
     constexpr int GS = SLAB * GQ;                    // groups per slab
     constexpr int PS = (GS + 255) / 256;
     static_assert(256 % GQ == 0 || GQ % 256 == 0 || PS == 1, "a thread keeps its column group across passes");
+    float ssq = 0.f;
     auto epilogue = [&](auto checked) {
         constexpr bool CHECK = decltype(checked)::value;
 #pragma unroll
@@ -423,13 +430,24 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void i
 #pragma unroll
             for (int s = 0; s < PS; ++s) {
                 const int g = tid + s * 256;
-                if (GS % 256 == 0 || g < GS) p.template store4<CHECK>(mm[s], nn[s], val[s], colv[s], aux[s]);
+                if (GS % 256 == 0 || g < GS) {
+                    p.template store4<CHECK>(mm[s], nn[s], val[s], colv[s], aux[s]);
+                    if (P::SUMSQ) ssq += p.template sumsq4<CHECK>(mm[s], nn[s], val[s]);
+                }
             }
             if (i + 1 < BI) __syncthreads();
         }
     };
     if (p.tile_full(m0, n0)) epilogue(std::false_type{});
     else epilogue(std::true_type{});
+    if (P::SUMSQ) {
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) ssq += __shfl_xor(ssq, off, 64);
+        __syncthreads();
+        if (lane == 0) smem[wave] = ssq;
+        __syncthreads();
+        if (tid == 0) p.store_sumsq(tm * p.tiles_n + tn, (smem[0] + smem[1]) + (smem[2] + smem[3]));
+    }
 }
 
 template <class P>

@@ -99,67 +99,87 @@ hipError_t launch_loss(const NetArgs &a, const HParams &hp, const int32_t *actio
     return hipGetLastError();
 }
 
-// ---- global gradient norm per agent (Table 2: clip global gradient norm) -------------------------
-__global__ __launch_bounds__(256) void sumsq_kernel(const float *__restrict__ g, long d_pad, float *part)
+// ---- global gradient norm per agent and clip factor (Table 2: clip global gradient norm) ----------
+// The hidden layer's weight gradient (95 % of the parameters) arrives as per-tile sums of
+// squares from the kernel that produced it; this kernel adds the squares of everything in
+// front of and behind that tensor and turns the total into
+//   c = min(1, max_norm / (||g|| + 1e-6)).
+// One workgroup per agent, fixed summation order.
+constexpr int NORM_THREADS = 1024;
+
+__global__ __launch_bounds__(NORM_THREADS) void grad_norm_kernel(const float *__restrict__ g, long d_pad, long fcw_begin,
+                                                                 long fcw_end, const float *__restrict__ part,
+                                                                 float max_norm, float *stats)
 {
-    __shared__ float red[4];
-    const int agent = blockIdx.y;
+    __shared__ float red[NORM_THREADS / 64];
+    const int agent = blockIdx.x;
     const float4 *p = reinterpret_cast<const float4 *>(g + agent * d_pad);
-    const long n4 = d_pad / 4;
     float acc = 0.f;
-    for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < n4; i += (long)gridDim.x * 256) {
+    for (long i = threadIdx.x; i < fcw_begin / 4; i += NORM_THREADS) {
         const float4 v = p[i];
         acc += (v.x * v.x + v.y * v.y) + (v.z * v.z + v.w * v.w);
     }
-    acc = block_sum_256(acc, red);
-    if (threadIdx.x == 0) part[agent * NORM_BLOCKS + blockIdx.x] = acc;
+    for (long i = fcw_end / 4 + threadIdx.x; i < d_pad / 4; i += NORM_THREADS) {
+        const float4 v = p[i];
+        acc += (v.x * v.x + v.y * v.y) + (v.z * v.z + v.w * v.w);
+    }
+    if (threadIdx.x < FC_WGRAD_TILES) acc += part[agent * NORM_PARTS + threadIdx.x];
+    acc = wave_sum(acc);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float ss = 0.f;
+        for (int w = 0; w < NORM_THREADS / 64; ++w) ss += red[w];
+        const float norm = sqrtf(ss);
+        stats[agent * 5 + 3] = norm;
+        stats[agent * 5 + 4] = fminf(1.f, max_norm / (norm + 1e-6f));
+    }
 }
 
 // ---- clip + RMSprop (Table 2; momentum 0) ---------------------------------------------------------------
-//   c = min(1, max_norm / (||g|| + 1e-6));  g <- c g;  v <- a v + (1 - a) g^2;  x <- x - lr g / (sqrt(v) + eps)
+//   g <- c g;  v <- a v + (1 - a) g^2;  x <- x - lr g / (sqrt(v) + eps)
+static __device__ __forceinline__ void rmsprop4(float4 &xx, float4 &vv, float4 gg, float c, float lr, float alpha,
+                                                float om, float eps)
+{
+    gg.x *= c; gg.y *= c; gg.z *= c; gg.w *= c;
+    vv.x = alpha * vv.x + om * gg.x * gg.x; vv.y = alpha * vv.y + om * gg.y * gg.y;
+    vv.z = alpha * vv.z + om * gg.z * gg.z; vv.w = alpha * vv.w + om * gg.w * gg.w;
+    xx.x -= lr * gg.x / (sqrtf(vv.x) + eps); xx.y -= lr * gg.y / (sqrtf(vv.y) + eps);
+    xx.z -= lr * gg.z / (sqrtf(vv.z) + eps); xx.w -= lr * gg.w / (sqrtf(vv.w) + eps);
+}
+
 __global__ __launch_bounds__(256) void rmsprop_kernel(float *x, float *v, const float *__restrict__ g, long d_pad,
-                                                      const float *__restrict__ part, float max_norm, float lr,
-                                                      float alpha, float eps, float *stats)
+                                                      const float *__restrict__ stats, float lr, float alpha,
+                                                      float eps)
 {
     const int agent = blockIdx.y;
-    float ss = 0.f;
-    if (threadIdx.x < 64) {
-        ss = part[agent * NORM_BLOCKS + threadIdx.x];
-        ss = wave_sum(ss);
-    }
-    __shared__ float sh;
-    if (threadIdx.x == 0) sh = ss;
-    __syncthreads();
-    const float norm = sqrtf(sh);
-    const float c = fminf(1.f, max_norm / (norm + 1e-6f));
-    if (blockIdx.x == 0 && threadIdx.x == 0) { stats[agent * 5 + 3] = norm; stats[agent * 5 + 4] = c; }
+    const float c = stats[agent * 5 + 4];
     const long n4 = d_pad / 4;
     float4 *x4 = reinterpret_cast<float4 *>(x + agent * d_pad);
     float4 *v4 = reinterpret_cast<float4 *>(v + agent * d_pad);
     const float4 *g4 = reinterpret_cast<const float4 *>(g + agent * d_pad);
     const float om = 1.f - alpha;
     for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < n4; i += (long)gridDim.x * 256) {
-        float4 gg = g4[i], vv = v4[i], xx = x4[i];
-        gg.x *= c; gg.y *= c; gg.z *= c; gg.w *= c;
-        vv.x = alpha * vv.x + om * gg.x * gg.x; vv.y = alpha * vv.y + om * gg.y * gg.y;
-        vv.z = alpha * vv.z + om * gg.z * gg.z; vv.w = alpha * vv.w + om * gg.w * gg.w;
-        xx.x -= lr * gg.x / (sqrtf(vv.x) + eps); xx.y -= lr * gg.y / (sqrtf(vv.y) + eps);
-        xx.z -= lr * gg.z / (sqrtf(vv.z) + eps); xx.w -= lr * gg.w / (sqrtf(vv.w) + eps);
+        float4 vv = v4[i], xx = x4[i];
+        rmsprop4(xx, vv, g4[i], c, lr, alpha, om, eps);
         v4[i] = vv; x4[i] = xx;
     }
 }
 
-hipError_t launch_optimizer(int N, const Layout &L, const HParams &hp, float *x, float *v, const float *g,
-                            float *norm_part, float *stats, hipStream_t s, PhaseTimer *pt)
+hipError_t launch_grad_norm(int N, const Layout &L, const HParams &hp, const float *g, const float *norm_part,
+                            float *stats, hipStream_t s)
 {
-    hipLaunchKernelGGL(sumsq_kernel, dim3(NORM_BLOCKS, N), dim3(256), 0, s, g, L.d_pad, norm_part);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    pt->mark("grad_norm");
-    const int blocks = 128;
-    hipLaunchKernelGGL(rmsprop_kernel, dim3(blocks, N), dim3(256), 0, s, x, v, g, L.d_pad, norm_part,
-                       hp.max_grad_norm, hp.lr, hp.rms_alpha, hp.rms_eps, stats);
-    pt->mark("clip_rmsprop");
+    // the hidden layer's weights occupy [fcw, fcb) of a slice; every tensor starts on a multiple of 64 floats
+    hipLaunchKernelGGL(grad_norm_kernel, dim3(N), dim3(NORM_THREADS), 0, s, g, L.d_pad, L.fcw, L.fcb, norm_part,
+                       hp.max_grad_norm, stats);
+    return hipGetLastError();
+}
+
+hipError_t launch_rmsprop(int N, const Layout &L, const HParams &hp, float *x, float *v, const float *g,
+                          const float *stats, hipStream_t s)
+{
+    hipLaunchKernelGGL(rmsprop_kernel, dim3(128, N), dim3(256), 0, s, x, v, g, L.d_pad, stats, hp.lr, hp.rms_alpha,
+                       hp.rms_eps);
     return hipGetLastError();
 }
 
@@ -229,6 +249,93 @@ hipError_t launch_mix(int N, const Layout &L, const float *x_in, float *x_out, c
 {
     hipLaunchKernelGGL(mix_kernel, dim3(128, N), dim3(256), 0, s, x_in, x_out, hist, N, L.d_pad, tau, round,
                        phase, max_in, peer, delay, weight);
+    return hipGetLastError();
+}
+
+// Clip + RMSprop of every agent and the mixing step in one pass (Algorithm 1: optimise,
+// broadcast, average).  A workgroup owns COLS4 float4 columns of all N agents: the
+// post-update parameters are kept in LDS, so a message that was sent this round is read from
+// there and the parameters move through HBM once (read g, x, v; write v, x).  With delays the
+// post-update values are also stored into this round's history slot and older messages are
+// read from theirs.  Same arithmetic, in the same order, as rmsprop_kernel + mix_kernel.
+// LDS use is N * COLS4 * 16 bytes.
+constexpr int FUSED_LDS_BYTES = 64 * 1024;
+
+template <int COLS4>
+__global__ __launch_bounds__(256) void rmsprop_mix_kernel(float *x, float *v, const float *__restrict__ g,
+                                                          float *hist, int N, long d_pad, int tau, long round,
+                                                          int phase, int max_in, const int32_t *__restrict__ peer,
+                                                          const int32_t *__restrict__ delay,
+                                                          const float *__restrict__ weight,
+                                                          const float *__restrict__ stats, float lr, float alpha,
+                                                          float eps)
+{
+    extern __shared__ float4 u[];                                  // [N][COLS4]
+    constexpr int GROUPS = 256 / COLS4;                            // agents in flight per pass
+    const int col = threadIdx.x % COLS4;
+    int q = threadIdx.x / COLS4;                                   // agents q, q + GROUPS, ...
+    if constexpr (COLS4 == 64) q = __builtin_amdgcn_readfirstlane(q);   // one agent per wavefront: scalar table reads
+    const long e = (long)blockIdx.x * COLS4 + col;                 // float4 index inside an agent's slice
+    const long n4 = d_pad / 4;
+    const float om = 1.f - alpha;
+    float4 *slot = tau > 0 ? reinterpret_cast<float4 *>(hist + (round % (tau + 1)) * (long)N * d_pad) : nullptr;
+    for (int i = q; i < N; i += GROUPS) {
+        const long at = (long)i * n4 + e;
+        float4 vv = reinterpret_cast<float4 *>(v)[at], xx = reinterpret_cast<float4 *>(x)[at];
+        rmsprop4(xx, vv, reinterpret_cast<const float4 *>(g)[at], stats[i * 5 + 4], lr, alpha, om, eps);
+        reinterpret_cast<float4 *>(v)[at] = vv;
+        u[i * COLS4 + col] = xx;
+        if (slot) slot[at] = xx;
+    }
+    __syncthreads();
+    for (int i = q; i < N; i += GROUPS) {
+        const long tab = ((long)phase * N + i) * max_in;
+        bool complete = true;
+        for (int s = 0; s < max_in; ++s)
+            if (peer[tab + s] >= 0 && round - delay[tab + s] < 0) complete = false;
+        float4 a = u[i * COLS4 + col];
+        const float w_self = complete ? weight[((long)phase * N + i) * (max_in + 1)] : 1.f;
+        a.x *= w_self; a.y *= w_self; a.z *= w_self; a.w *= w_self;
+        if (complete)
+            for (int s = 0; s < max_in; ++s) {
+                const int j = peer[tab + s];
+                if (j < 0) continue;
+                const int dl = delay[tab + s];
+                const float w = weight[((long)phase * N + i) * (max_in + 1) + 1 + s];
+                const float4 m = dl == 0 ? u[j * COLS4 + col]
+                                         : reinterpret_cast<const float4 *>(
+                                               hist + ((round - dl) % (tau + 1)) * (long)N * d_pad)[(long)j * n4 + e];
+                a.x += w * m.x; a.y += w * m.y; a.z += w * m.z; a.w += w * m.w;
+            }
+        reinterpret_cast<float4 *>(x)[(long)i * n4 + e] = a;
+    }
+}
+
+// widest column block whose LDS tile stays within FUSED_LDS_BYTES; 0 = too many agents
+static int fused_cols4(int N)
+{
+    for (int c = 64; c >= 16; c >>= 1)
+        if ((long)N * c * 16 <= FUSED_LDS_BYTES) return c;
+    return 0;
+}
+
+bool fused_mix_available(int N) { return fused_cols4(N) != 0; }
+
+hipError_t launch_rmsprop_mix(int N, const Layout &L, const HParams &hp, float *x, float *v, const float *g,
+                              float *hist, int tau, long round, int phase, int max_in, const int32_t *peer,
+                              const int32_t *delay, const float *weight, const float *stats, hipStream_t s)
+{
+    const int c4 = fused_cols4(N);
+    const int blocks = (int)(L.d_pad / 4 / c4);                    // d_pad is a multiple of 256 floats
+    const size_t lds = (size_t)N * c4 * sizeof(float4);
+#define FUSED_LAUNCH(C4)                                                                                          \
+    hipLaunchKernelGGL(rmsprop_mix_kernel<C4>, dim3(blocks), dim3(256), lds, s, x, v, g, hist, N, L.d_pad, tau,   \
+                       round, phase, max_in, peer, delay, weight, stats, hp.lr, hp.rms_alpha, hp.rms_eps)
+    if (c4 == 64) FUSED_LAUNCH(64);
+    else if (c4 == 32) FUSED_LAUNCH(32);
+    else if (c4 == 16) FUSED_LAUNCH(16);
+    else return hipErrorInvalidValue;
+#undef FUSED_LAUNCH
     return hipGetLastError();
 }
 

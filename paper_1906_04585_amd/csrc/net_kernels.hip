@@ -59,6 +59,7 @@ struct ProblemBase {
     typedef OffCtx CtxA;
     typedef OffCtx CtxB;
     static constexpr bool SUM_A = false, SUM_B = false, HAS_AUX = false, A_ZERO = false, B_ZERO = false;
+    static constexpr bool SUMSQ = false;
     static constexpr bool MFMA16 = GALA_MFMA16;
     int tiles_m, tiles_n, splits;
     int k0, k1;
@@ -70,6 +71,8 @@ struct ProblemBase {
     template <bool CHECK> __device__ float4 aux4(int, int) const { return make_float4(0.f, 0.f, 0.f, 0.f); }
     __device__ void store_sum_a(int, float) const {}
     __device__ void store_sum_b(int, float) const {}
+    template <bool CHECK> __device__ float sumsq4(int, int, float4) const { return 0.f; }
+    __device__ void store_sumsq(int, float) const {}
 };
 
 // ---- conv1 forward: bytes -> a1 ------------------------------------------------------
@@ -240,22 +243,31 @@ struct FcWgrad : ProblemBase {
     static constexpr int BM = 128, BN = 128, BK = 16, WM = 2, WN = 2;
     static constexpr bool A_KC = false, B_KC = false;
     static constexpr bool SUM_A = true, A_ZERO = true, B_ZERO = true;
+    static constexpr bool SUMSQ = true;      // this tensor is 95 % of the parameters: its share of ||g||^2
+    static constexpr int TILES = (FC / BM) * ((FLAT + BN - 1) / BN);
+    static_assert(TILES == FC_WGRAD_TILES && TILES <= NORM_PARTS, "one gradient-norm partial per tile");
     struct CtxA { unsigned off; int kl; };
     struct CtxB { unsigned off; int kl; bool col_ok; };
     const float *dzh, *a3;
-    float *g;
+    float *g, *norm_part;
     long d_pad, w_off, b_off;
     int M, F;
     const float *a_, *b_;
-    float *out_, *bias_;
+    float *out_, *bias_, *ssq_;
     __device__ void bind(int agent, int)
     {
         a_ = dzh + (long)agent * M * FC;
         b_ = a3 + (long)agent * F * FLAT;
         out_ = g + agent * d_pad + w_off;
         bias_ = g + agent * d_pad + b_off;
+        ssq_ = norm_part + agent * NORM_PARTS;
         k0 = 0; k1 = M;
     }
+    template <bool CHECK> __device__ float sumsq4(int, int n, float4 v) const
+    {
+        return (!CHECK || n < FLAT) ? (v.x * v.x + v.y * v.y) + (v.z * v.z + v.w * v.w) : 0.f;
+    }
+    __device__ void store_sumsq(int tile, float v) const { ssq_[tile] = v; }
     __device__ void store_sum_a(int m, float v) const { bias_[m] = v; }
     __device__ void prep_a(CtxA &c, int m, int kl) const { c.off = (unsigned)((kl * FC + m) * 4); c.kl = kl; }
     __device__ float4 fetch_a(CtxA &c, int kt0, bool &ok) const
@@ -750,7 +762,7 @@ hipError_t launch_backward(const NetArgs &a, hipStream_t s, PhaseTimer *pt)
     {
         FcWgrad p{};
         p.dzh = a.b.dzh; p.a3 = a.b.a3; p.g = a.b.g; p.d_pad = L.d_pad; p.w_off = L.fcw; p.b_off = L.fcb;
-        p.M = a.M; p.F = a.F;
+        p.norm_part = a.b.norm_part; p.M = a.M; p.F = a.F;
         p.tiles_m = FC / FcWgrad::BM; p.tiles_n = cdiv(FLAT, FcWgrad::BN); p.splits = 1;
         GALA_TRY(igemm_launch(p, a.N, s, a.bf16));
         pt->mark("fc_wgrad");

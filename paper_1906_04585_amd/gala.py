@@ -16,7 +16,7 @@ _LIB_PATH = os.environ.get("GALA_LIBRARY", os.path.join(_PKG, "libgala.so"))
 EXPORTS = [
     "gala_create", "gala_destroy", "gala_param_count", "gala_last_error",
     "gala_set_params", "gala_get_params", "gala_set_opt_state", "gala_get_opt_state",
-    "gala_learner_step", "gala_gossip", "gala_get_grads", "gala_get_step_stats",
+    "gala_learner_step", "gala_gossip", "gala_round", "gala_get_grads", "gala_get_step_stats",
     "gala_get_outputs", "gala_consensus_distance", "gala_get_peer_table",
     "gala_set_profiling", "gala_get_phase_times", "gala_get_activations",
 ]
@@ -71,6 +71,7 @@ def load_library():
             getattr(L, name).argtypes = [C.c_void_p, C.c_void_p, C.c_int]
         L.gala_learner_step.argtypes = [C.c_void_p] * 6
         L.gala_gossip.argtypes = [C.c_void_p, C.c_int64]
+        L.gala_round.argtypes = [C.c_void_p] * 6 + [C.c_int64]
         L.gala_get_step_stats.argtypes = [C.c_void_p, C.c_void_p]
         L.gala_get_outputs.argtypes = [C.c_void_p] * 5
         L.gala_consensus_distance.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
@@ -183,14 +184,21 @@ class Gala:
     def get_grads(self, out=None):
         return self._get(self._lib.gala_get_grads, out)
 
-    def learner_step(self, obs_u8, actions, rewards, dones, bootstrap_obs):
+    def _rollout_ptrs(self, obs_u8, actions, rewards, dones, bootstrap_obs):
         import torch
         N, T, B = self.N, self.T, self.B
         fr = 4 * 84 * 84
+        return (_dev_ptr(obs_u8, torch.uint8, N * T * B * fr), _dev_ptr(actions, torch.int32, N * T * B),
+                _dev_ptr(rewards, torch.float32, N * T * B), _dev_ptr(dones, torch.uint8, N * T * B),
+                _dev_ptr(bootstrap_obs, torch.uint8, N * B * fr))
+
+    def learner_step(self, obs_u8, actions, rewards, dones, bootstrap_obs):
         self._check(self._lib.gala_learner_step(
-            self._h, _dev_ptr(obs_u8, torch.uint8, N * T * B * fr), _dev_ptr(actions, torch.int32, N * T * B),
-            _dev_ptr(rewards, torch.float32, N * T * B), _dev_ptr(dones, torch.uint8, N * T * B),
-            _dev_ptr(bootstrap_obs, torch.uint8, N * B * fr)))
+            self._h, *self._rollout_ptrs(obs_u8, actions, rewards, dones, bootstrap_obs)))
+
+    def round(self, obs_u8, actions, rewards, dones, bootstrap_obs, rnd: int):
+        self._check(self._lib.gala_round(
+            self._h, *self._rollout_ptrs(obs_u8, actions, rewards, dones, bootstrap_obs), int(rnd)))
 
     def gossip(self, rnd: int):
         self._check(self._lib.gala_gossip(self._h, int(rnd)))

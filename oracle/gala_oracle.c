@@ -486,6 +486,46 @@ void orc_learner_step(const orc_net *n, const orc_hparams *hp, int N, double *X,
     free(g); free(r);
 }
 
+/* Synchronous A2C with gradient averaging across agents (Sec. 5 "Experimental
+ * setup": individual A2C agents average their gradients with AllReduce before
+ * each update; Eq. (5) is the batched update this equals for identical
+ * replicas).  Every agent computes its own gradient at its own parameters,
+ * gbar = (1/N) sum_i g_i is clipped once, and every agent applies RMSprop with
+ * gbar to its own X and V rows.  grads_out [N][d]: the agents' own pre-average
+ * gradients; gbar_out [d] pre-clip average (either may be NULL); stats [N][5] as
+ * in orc_learner_step with the norm and clip scale of gbar in every row. */
+void orc_a2c_allreduce_step(const orc_net *n, const orc_hparams *hp, int N, double *X, double *V,
+                            const uint8_t *obs, const int32_t *actions, const float *rewards,
+                            const uint8_t *dones, const uint8_t *boot_obs,
+                            double *grads_out, double *gbar_out, double *stats, const uint8_t *gates)
+{
+    orc_shape s; shape_of(n, &s);
+    const int M = hp->T * hp->B;
+    double *g = (double *)malloc(sizeof(double) * s.d);
+    double *gbar = (double *)calloc(s.d, sizeof(double));
+    double *r = (double *)malloc(sizeof(double) * M);
+    for (int i = 0; i < N; ++i) {
+        for (int m = 0; m < M; ++m) r[m] = (double)rewards[(long)i * M + m];
+        double terms[3];
+        orc_agent_gradient(n, hp, X + (long)i * s.d, obs + (long)i * M * s.in_size,
+                           actions + (long)i * M, r, dones + (long)i * M,
+                           boot_obs + (long)i * hp->B * s.in_size, g, terms, NULL, NULL, NULL, NULL,
+                           gates ? gates + (long)i * M * s.act_size : NULL);
+        if (grads_out) memcpy(grads_out + (long)i * s.d, g, sizeof(double) * s.d);
+        for (long k = 0; k < s.d; ++k) gbar[k] += g[k];
+        if (stats) { stats[i * 5 + 0] = terms[0]; stats[i * 5 + 1] = terms[1]; stats[i * 5 + 2] = terms[2]; }
+    }
+    for (long k = 0; k < s.d; ++k) gbar[k] /= (double)N;
+    if (gbar_out) memcpy(gbar_out, gbar, sizeof(double) * s.d);
+    double scale;
+    const double norm = orc_clip_grad_norm(gbar, s.d, hp->max_grad_norm, &scale);
+    for (int i = 0; i < N; ++i) {
+        orc_rmsprop(X + (long)i * s.d, V + (long)i * s.d, gbar, s.d, hp->lr, hp->rms_alpha, hp->rms_eps);
+        if (stats) { stats[i * 5 + 3] = norm; stats[i * 5 + 4] = scale; }
+    }
+    free(g); free(gbar); free(r);
+}
+
 /* ---- gossip -------------------------------------------------------------- */
 
 /* The single in-peer of agent i at a given round (integer table).

@@ -64,6 +64,7 @@ def lib():
         L.orc_agent_gradient.argtypes = [C.c_void_p] * 15
         L.orc_agent_loss.argtypes = [C.c_void_p] * 11
         L.orc_learner_step.argtypes = [C.c_void_p, C.c_void_p, C.c_int] + [C.c_void_p] * 10
+        L.orc_a2c_allreduce_step.argtypes = [C.c_void_p, C.c_void_p, C.c_int] + [C.c_void_p] * 11
         L.orc_mix_uniform.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_long, C.c_void_p]
         L.orc_mix_weighted.argtypes = [C.c_void_p, C.c_double, C.c_void_p, C.c_void_p,
                                        C.c_int, C.c_long, C.c_void_p]
@@ -324,6 +325,23 @@ class OracleGala:
                                _p(obs), _p(actions), _p(rewards), _p(dones), _p(boot_obs),
                                _p(self.grads), _p(self.stats),
                                _p(None if gates is None else np.ascontiguousarray(gates, dtype=np.uint8)))
+
+    def a2c_allreduce_step(self, obs, actions, rewards, dones, boot_obs, gates=None):
+        """Synchronous A2C comparator: the agents' gradients are averaged, clipped once and
+        applied by every agent (Sec. 5, "Experimental setup")."""
+        n, h = c_net(self.net), c_hparams(self.T, self.B, self.hp)
+        obs = np.ascontiguousarray(obs, dtype=np.uint8)
+        boot_obs = np.ascontiguousarray(boot_obs, dtype=np.uint8)
+        actions = np.ascontiguousarray(actions, dtype=np.int32)
+        rewards = np.ascontiguousarray(rewards, dtype=np.float32)
+        dones = np.ascontiguousarray(dones, dtype=np.uint8)
+        self.grads = np.empty((self.N, self.d))
+        self.gbar = np.empty(self.d)
+        self.stats = np.empty((self.N, 5))
+        lib().orc_a2c_allreduce_step(C.byref(n), C.byref(h), self.N, _p(self.X), _p(self.V),
+                                     _p(obs), _p(actions), _p(rewards), _p(dones), _p(boot_obs),
+                                     _p(self.grads), _p(self.gbar), _p(self.stats),
+                                     _p(None if gates is None else np.ascontiguousarray(gates, dtype=np.uint8)))
 
     def gossip(self, rnd: int):
         """Broadcast the post-update parameters, then every agent that holds a

@@ -88,8 +88,9 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=4, help="workload shape 1..5 (default: 32 agents)")
     ap.add_argument("--dtype", choices=["f32", "bf16"], default="f32",
                     help="matrix-instruction operand type of the conv/fc kernels (parameters stay fp32)")
-    ap.add_argument("--mode", choices=["fused", "split"], default="fused",
-                    help="one gala_round call per step, or gala_learner_step + gala_gossip")
+    ap.add_argument("--mode", choices=["fused", "split", "a2c_allreduce"], default="fused",
+                    help="one gala_round call per step, or gala_learner_step + gala_gossip; a2c_allreduce times "
+                         "the synchronous comparator (gradients averaged over agents, no gossip) instead")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-rounds", type=int, default=20)
     args = ap.parse_args()
@@ -126,6 +127,8 @@ def main() -> int:
         d = pool[r % len(pool)]
         if args.mode == "fused":
             gpu.round(d["obs"], d["actions"], d["rewards"], d["dones"], d["boot_obs"], r)
+        elif args.mode == "a2c_allreduce":
+            gpu.a2c_allreduce_step(d["obs"], d["actions"], d["rewards"], d["dones"], d["boot_obs"])
         else:
             gpu.learner_step(d["obs"], d["actions"], d["rewards"], d["dones"], d["boot_obs"])
             gpu.gossip(r)
@@ -155,6 +158,9 @@ def main() -> int:
             acc[k] = acc.get(k, 0.0) + v / args.profile_rounds
     gpu.set_profiling(False)
     work = kernel_work(N, M, F, gpu.d, cfg["max_delay"])
+    if args.mode == "a2c_allreduce":
+        work["grad_mean_norm"] = ("hbm", 4.0 * gpu.d * N)      # read every agent's gradient once
+        work["clip_rmsprop"] = ("hbm", 16.0 * gpu.d * N)       # read x, v; write x, v (the mean stays in cache)
     kernels = {}
     for k, ms in acc.items():
         ent = {"ms": round(ms, 5)}
@@ -207,7 +213,8 @@ def main() -> int:
                                    f"{n_s * n_r * M} frames, fp64, {cpu_t:.2f} s wall on {threads} threads")
 
     out = {
-        "metric": "agent learner-steps/sec (one learner step + one gossip round per agent)",
+        "metric": "agent learner-steps/sec (one learner step + one gossip round per agent)"
+                  if args.mode != "a2c_allreduce" else "agent learner-steps/sec (synchronous A2C, gradients averaged)",
         "value": agent_steps,
         "unit": "agent-steps/s",
         "env_frames_per_s": frames,
@@ -225,7 +232,8 @@ def main() -> int:
                                f"{'fp32' if args.dtype == 'f32' else 'bf16 operands / fp32 accumulation'}",
                    "n_agents": N, "T": T, "B": B, "n_actions": A, "topology": cfg["topology"],
                    "max_delay": cfg["max_delay"],
-                   "calls": "gala_round" if args.mode == "fused" else "gala_learner_step + gala_gossip"},
+                   "calls": {"fused": "gala_round", "split": "gala_learner_step + gala_gossip",
+                             "a2c_allreduce": "gala_a2c_allreduce_step (comparator, not GALA)"}[args.mode]},
         "roofline": roofline,
         "phases": phase_summary,
         "kernels": kernels,

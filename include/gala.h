@@ -134,6 +134,20 @@ int gala_gossip(gala_ctx *ctx, int64_t round);
 int gala_round(gala_ctx *ctx, const uint8_t *obs_u8, const int32_t *actions, const float *rewards,
                const uint8_t *dones, const uint8_t *bootstrap_obs, int64_t round);
 
+/* Synchronous A2C with gradient averaging, the method GALA-A2C is compared with (Sec. 5,
+ * "Experimental setup": every agent averages its gradient with all others before each
+ * update, which for identical replicas is the batched update of Eq. (5) over all agents'
+ * simulators).  Same inputs as gala_learner_step.  Every agent's gradient is computed at its
+ * own parameters; gbar = (1/N) sum_i g_i (agents added in index order) is clipped once by its
+ * own global norm and applied by every agent with RMSprop to its own parameters and state.
+ * No gossip follows.  Afterwards gala_get_grads returns the agents' own gradients,
+ * gala_get_mean_grad returns gbar, and the norm / clip columns of gala_get_step_stats hold
+ * gbar's values in every row. */
+int gala_a2c_allreduce_step(gala_ctx *ctx, const uint8_t *obs_u8, const int32_t *actions,
+                            const float *rewards, const uint8_t *dones, const uint8_t *bootstrap_obs);
+/* Pre-clip average gradient of the last gala_a2c_allreduce_step, [d] float canonical. */
+int gala_get_mean_grad(gala_ctx *ctx, float *dst, int dst_is_device);
+
 /* ---- diagnostics used by tests and logging -------------------------------------- */
 
 /* Pre-clip gradients of the last learner step, [N][d] canonical. */

@@ -191,6 +191,7 @@ extern "C" int gala_create(gala_ctx **out, int n_agents, const gala_topology *to
 #undef ALLOC_ZP
     ALLOC(b.ws, workspace_floats(c->N, c->M, c->F), false);
     ALLOC(b.norm_part, N * NORM_PARTS, true);
+    ALLOC(b.gbar, dp, true); ALLOC(b.gbar_part, (size_t)grad_mean_blocks(c->L), true);
     ALLOC(b.stats, N * 5, true);
     ALLOC(b.cons_part, N * ((dp + CONS_COLS - 1) / CONS_COLS) + 2, true);
     ALLOC(b.peer, c->h_peer.size(), false); ALLOC(b.delay, c->h_delay.size(), false);
@@ -252,9 +253,21 @@ extern "C" int gala_set_opt_state(gala_ctx *c, const float *src, int dev) { retu
 extern "C" int gala_get_opt_state(gala_ctx *c, float *dst, int dev) { return c ? export_arena(c, c->b.v, dst, dev) : GALA_EINVAL; }
 extern "C" int gala_get_grads(gala_ctx *c, float *dst, int dev) { return c ? export_arena(c, c->b.g, dst, dev) : GALA_EINVAL; }
 
+extern "C" int gala_get_mean_grad(gala_ctx *c, float *dst, int dst_is_device)
+{
+    if (!c || !dst) return fail(c, GALA_EINVAL, "null argument");
+    float *stage = dst_is_device ? dst : c->canon;
+    HIP_OK(c, launch_permute(1, c->L, c->seg, stage, c->b.gbar, 0, c->stream));
+    if (!dst_is_device) {
+        HIP_OK(c, hipMemcpyAsync(dst, stage, (size_t)c->L.d * 4, hipMemcpyDeviceToHost, c->stream));
+        HIP_OK(c, hipStreamSynchronize(c->stream));
+    }
+    return GALA_OK;
+}
+
 // forward, loss, backward and the per-agent gradient norm / clip factor
 static int enqueue_gradients(gala_ctx *c, const uint8_t *obs_u8, const int32_t *actions, const float *rewards,
-                             const uint8_t *dones, const uint8_t *bootstrap_obs)
+                             const uint8_t *dones, const uint8_t *bootstrap_obs, bool own_norm = true)
 {
     if (!obs_u8 || !actions || !rewards || !dones || !bootstrap_obs) return fail(c, GALA_EINVAL, "null input buffer");
     if ((reinterpret_cast<uintptr_t>(obs_u8) | reinterpret_cast<uintptr_t>(bootstrap_obs)) & 3)
@@ -269,8 +282,10 @@ static int enqueue_gradients(gala_ctx *c, const uint8_t *obs_u8, const int32_t *
     HIP_OK(c, launch_loss(a, c->hp, actions, rewards, dones, c->stream));
     pt->mark("returns_loss");
     HIP_OK(c, launch_backward(a, c->stream, pt));
-    HIP_OK(c, launch_grad_norm(c->N, c->L, c->hp, c->b.g, c->b.norm_part, c->b.stats, c->stream));
-    pt->mark("grad_norm");
+    if (own_norm) {
+        HIP_OK(c, launch_grad_norm(c->N, c->L, c->hp, c->b.g, c->b.norm_part, c->b.stats, c->stream));
+        pt->mark("grad_norm");
+    }
     return GALA_OK;
 }
 
@@ -292,7 +307,20 @@ extern "C" int gala_learner_step(gala_ctx *c, const uint8_t *obs_u8, const int32
     if (!c) return GALA_EINVAL;
     int rc = enqueue_gradients(c, obs_u8, actions, rewards, dones, bootstrap_obs);
     if (rc != GALA_OK) return rc;
-    HIP_OK(c, launch_rmsprop(c->N, c->L, c->hp, c->b.x[c->cur], c->b.v, c->b.g, c->b.stats, c->stream));
+    HIP_OK(c, launch_rmsprop(c->N, c->L, c->hp, c->b.x[c->cur], c->b.v, c->b.g, false, c->b.stats, c->stream));
+    c->timer.mark("clip_rmsprop");
+    return GALA_OK;
+}
+
+extern "C" int gala_a2c_allreduce_step(gala_ctx *c, const uint8_t *obs_u8, const int32_t *actions,
+                                       const float *rewards, const uint8_t *dones, const uint8_t *bootstrap_obs)
+{
+    if (!c) return GALA_EINVAL;
+    int rc = enqueue_gradients(c, obs_u8, actions, rewards, dones, bootstrap_obs, false);
+    if (rc != GALA_OK) return rc;
+    HIP_OK(c, launch_grad_mean(c->N, c->L, c->hp, c->b.g, c->b.gbar, c->b.gbar_part, c->b.stats, c->stream));
+    c->timer.mark("grad_mean_norm");
+    HIP_OK(c, launch_rmsprop(c->N, c->L, c->hp, c->b.x[c->cur], c->b.v, c->b.gbar, true, c->b.stats, c->stream));
     c->timer.mark("clip_rmsprop");
     return GALA_OK;
 }

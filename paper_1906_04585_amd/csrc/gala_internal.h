@@ -82,6 +82,7 @@ struct Buffers {
     float *dzh, *dz3, *dz2, *dz1;     // [N][M][..] pre-activation gradients
     float *ws;                        // split-K partial sums
     float *norm_part;                 // [N][NORM_PARTS]
+    float *gbar, *gbar_part;          // [d_pad] gradient averaged over agents, [grad_mean_blocks] its squares
     float *stats;                     // [N][5]
     float *cons_part;                 // [N][CONS_CHUNKS] + 2 results
     int32_t *peer, *delay;            // [phases][N][max_in]
@@ -139,7 +140,10 @@ size_t workspace_floats(int N, int M, int F);
 hipError_t launch_grad_norm(int N, const Layout &L, const HParams &hp, const float *g, const float *norm_part,
                             float *stats, hipStream_t s);
 hipError_t launch_rmsprop(int N, const Layout &L, const HParams &hp, float *x, float *v, const float *g,
-                          const float *stats, hipStream_t s);
+                          bool shared_gradient, const float *stats, hipStream_t s);
+int grad_mean_blocks(const Layout &L);
+hipError_t launch_grad_mean(int N, const Layout &L, const HParams &hp, const float *g, float *gbar, float *part,
+                            float *stats, hipStream_t s);
 bool fused_mix_available(int N);
 hipError_t launch_rmsprop_mix(int N, const Layout &L, const HParams &hp, float *x, float *v, const float *g,
                               float *hist, int tau, long round, int phase, int max_in, const int32_t *peer,

@@ -148,16 +148,17 @@ static __device__ __forceinline__ void rmsprop4(float4 &xx, float4 &vv, float4 g
     xx.z -= lr * gg.z / (sqrtf(vv.z) + eps); xx.w -= lr * gg.w / (sqrtf(vv.w) + eps);
 }
 
+// g_stride = d_pad: every agent applies its own gradient; 0: all agents apply the same one.
 __global__ __launch_bounds__(256) void rmsprop_kernel(float *x, float *v, const float *__restrict__ g, long d_pad,
-                                                      const float *__restrict__ stats, float lr, float alpha,
-                                                      float eps)
+                                                      long g_stride, const float *__restrict__ stats, float lr,
+                                                      float alpha, float eps)
 {
     const int agent = blockIdx.y;
     const float c = stats[agent * 5 + 4];
     const long n4 = d_pad / 4;
     float4 *x4 = reinterpret_cast<float4 *>(x + agent * d_pad);
     float4 *v4 = reinterpret_cast<float4 *>(v + agent * d_pad);
-    const float4 *g4 = reinterpret_cast<const float4 *>(g + agent * d_pad);
+    const float4 *g4 = reinterpret_cast<const float4 *>(g + agent * g_stride);
     const float om = 1.f - alpha;
     for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < n4; i += (long)gridDim.x * 256) {
         float4 vv = v4[i], xx = x4[i];
@@ -176,10 +177,66 @@ hipError_t launch_grad_norm(int N, const Layout &L, const HParams &hp, const flo
 }
 
 hipError_t launch_rmsprop(int N, const Layout &L, const HParams &hp, float *x, float *v, const float *g,
-                          const float *stats, hipStream_t s)
+                          bool shared_gradient, const float *stats, hipStream_t s)
 {
-    hipLaunchKernelGGL(rmsprop_kernel, dim3(128, N), dim3(256), 0, s, x, v, g, L.d_pad, stats, hp.lr, hp.rms_alpha,
-                       hp.rms_eps);
+    hipLaunchKernelGGL(rmsprop_kernel, dim3(128, N), dim3(256), 0, s, x, v, g, L.d_pad,
+                       shared_gradient ? 0L : L.d_pad, stats, hp.lr, hp.rms_alpha, hp.rms_eps);
+    return hipGetLastError();
+}
+
+// ---- synchronous A2C with gradient averaging (Sec. 5, "Experimental setup"; Eq. (5)) --------------------
+// gbar = (1/N) sum_i g_i, one thread per float4 column, agents added in index order; every
+// workgroup also leaves the sum of squares of its part of gbar.
+__global__ __launch_bounds__(256) void grad_mean_kernel(const float *__restrict__ g, int N, long d_pad,
+                                                        float *__restrict__ gbar, float *__restrict__ part)
+{
+    __shared__ float red[4];
+    const long n4 = d_pad / 4;
+    const long e = (long)blockIdx.x * 256 + threadIdx.x;
+    float ss = 0.f;
+    if (e < n4) {
+        float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll 8
+        for (int i = 0; i < N; ++i) {
+            const float4 t = reinterpret_cast<const float4 *>(g)[(long)i * n4 + e];
+            a.x += t.x; a.y += t.y; a.z += t.z; a.w += t.w;
+        }
+        const float inv = 1.f / (float)N;
+        a.x *= inv; a.y *= inv; a.z *= inv; a.w *= inv;
+        reinterpret_cast<float4 *>(gbar)[e] = a;
+        ss = (a.x * a.x + a.y * a.y) + (a.z * a.z + a.w * a.w);
+    }
+    ss = block_sum_256(ss, red);
+    if (threadIdx.x == 0) part[blockIdx.x] = ss;
+}
+
+// norm of gbar and the one clip factor, written into every agent's statistics row
+__global__ __launch_bounds__(1024) void mean_norm_kernel(const float *__restrict__ part, int n_part, int N,
+                                                         float max_norm, float *stats)
+{
+    __shared__ float red[16];
+    float acc = 0.f;
+    for (int i = threadIdx.x; i < n_part; i += 1024) acc += part[i];
+    acc = wave_sum(acc);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    float ss = 0.f;
+    for (int w = 0; w < 16; ++w) ss += red[w];
+    const float norm = sqrtf(ss);
+    const float c = fminf(1.f, max_norm / (norm + 1e-6f));
+    for (int i = threadIdx.x; i < N; i += 1024) { stats[i * 5 + 3] = norm; stats[i * 5 + 4] = c; }
+}
+
+int grad_mean_blocks(const Layout &L) { return (int)((L.d_pad / 4 + 255) / 256); }
+
+hipError_t launch_grad_mean(int N, const Layout &L, const HParams &hp, const float *g, float *gbar, float *part,
+                            float *stats, hipStream_t s)
+{
+    const int blocks = grad_mean_blocks(L);
+    hipLaunchKernelGGL(grad_mean_kernel, dim3(blocks), dim3(256), 0, s, g, N, L.d_pad, gbar, part);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(mean_norm_kernel, dim3(1), dim3(1024), 0, s, part, blocks, N, hp.max_grad_norm, stats);
     return hipGetLastError();
 }
 

@@ -16,7 +16,7 @@ _LIB_PATH = os.environ.get("GALA_LIBRARY", os.path.join(_PKG, "libgala.so"))
 EXPORTS = [
     "gala_create", "gala_destroy", "gala_param_count", "gala_last_error",
     "gala_set_params", "gala_get_params", "gala_set_opt_state", "gala_get_opt_state",
-    "gala_learner_step", "gala_gossip", "gala_round", "gala_get_grads", "gala_get_step_stats",
+    "gala_learner_step", "gala_gossip", "gala_round", "gala_a2c_allreduce_step", "gala_get_mean_grad", "gala_get_grads", "gala_get_step_stats",
     "gala_get_outputs", "gala_consensus_distance", "gala_get_peer_table",
     "gala_set_profiling", "gala_get_phase_times", "gala_get_activations",
 ]
@@ -72,6 +72,8 @@ def load_library():
         L.gala_learner_step.argtypes = [C.c_void_p] * 6
         L.gala_gossip.argtypes = [C.c_void_p, C.c_int64]
         L.gala_round.argtypes = [C.c_void_p] * 6 + [C.c_int64]
+        L.gala_a2c_allreduce_step.argtypes = [C.c_void_p] * 6
+        L.gala_get_mean_grad.argtypes = [C.c_void_p, C.c_void_p, C.c_int]
         L.gala_get_step_stats.argtypes = [C.c_void_p, C.c_void_p]
         L.gala_get_outputs.argtypes = [C.c_void_p] * 5
         L.gala_consensus_distance.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
@@ -199,6 +201,15 @@ class Gala:
     def round(self, obs_u8, actions, rewards, dones, bootstrap_obs, rnd: int):
         self._check(self._lib.gala_round(
             self._h, *self._rollout_ptrs(obs_u8, actions, rewards, dones, bootstrap_obs), int(rnd)))
+
+    def a2c_allreduce_step(self, obs_u8, actions, rewards, dones, bootstrap_obs):
+        self._check(self._lib.gala_a2c_allreduce_step(
+            self._h, *self._rollout_ptrs(obs_u8, actions, rewards, dones, bootstrap_obs)))
+
+    def get_mean_grad(self) -> np.ndarray:
+        a = np.empty(self.d, dtype=np.float32)
+        self._check(self._lib.gala_get_mean_grad(self._h, a.ctypes.data_as(C.c_void_p), 0))
+        return a
 
     def gossip(self, rnd: int):
         self._check(self._lib.gala_gossip(self._h, int(rnd)))

@@ -567,6 +567,39 @@ int orc_edge_delay(uint64_t seed, int N, int phase, int i, int max_delay)
     return (int)(mix64(seed + (uint64_t)phase * (uint64_t)N + (uint64_t)i) % (uint64_t)(max_delay + 1));
 }
 
+/* ---- acting (Algorithm 1: "take actions according to pi") ------------------- */
+
+/* Uniform variate in [0, 1) with 24 random bits: the top 24 bits of the
+ * splitmix64 output for the state seed + counter (counter-based, so any draw can
+ * be made on its own).  2^-24 spacing makes it exact in single precision too. */
+double orc_uniform24(uint64_t seed, uint64_t counter)
+{
+    return (double)(mix64(seed + counter) >> 40) * (1.0 / 16777216.0);
+}
+
+/* One draw from the categorical distribution pi = softmax(logits) by inverting
+ * its distribution function: the smallest a with pi_0 + ... + pi_a > u (the last
+ * action if rounding leaves the total below u).  logp_out: log pi(a); cdf_out [A]:
+ * the running sums (either may be NULL). */
+int orc_categorical_sample(int A, const double *logits, double u, double *logp_out, double *cdf_out)
+{
+    double zmax = logits[0];
+    for (int k = 1; k < A; ++k) if (logits[k] > zmax) zmax = logits[k];
+    double se = 0.0;
+    for (int k = 0; k < A; ++k) se += exp(logits[k] - zmax);
+    const double lse = zmax + log(se);
+    double run = 0.0;
+    int a = -1;
+    for (int k = 0; k < A; ++k) {
+        run += exp(logits[k] - lse);
+        if (cdf_out) cdf_out[k] = run;
+        if (a < 0 && run > u) a = k;
+    }
+    if (a < 0) a = A - 1;
+    if (logp_out) *logp_out = logits[a] - lse;
+    return a;
+}
+
 /* The mixing step of Algorithm 1 for one agent with uniform weights:
  * out = (x + sum_j msgs[j]) / (1 + n_msgs). */
 void orc_mix_uniform(const double *x, const double *const *msgs, int n_msgs, long d, double *out)

@@ -65,6 +65,9 @@ def lib():
         L.orc_agent_loss.argtypes = [C.c_void_p] * 11
         L.orc_learner_step.argtypes = [C.c_void_p, C.c_void_p, C.c_int] + [C.c_void_p] * 10
         L.orc_a2c_allreduce_step.argtypes = [C.c_void_p, C.c_void_p, C.c_int] + [C.c_void_p] * 11
+        L.orc_uniform24.restype = C.c_double
+        L.orc_uniform24.argtypes = [C.c_uint64, C.c_uint64]
+        L.orc_categorical_sample.argtypes = [C.c_int, C.c_void_p, C.c_double, C.c_void_p, C.c_void_p]
         L.orc_mix_uniform.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_long, C.c_void_p]
         L.orc_mix_weighted.argtypes = [C.c_void_p, C.c_double, C.c_void_p, C.c_void_p,
                                        C.c_int, C.c_long, C.c_void_p]
@@ -255,6 +258,42 @@ def peer_table(kind: str, N: int, rnd: int, max_delay: int = 0, delay_seed: int 
     peer = np.array([in_peer(kind, N, rnd, i) for i in range(N)], dtype=np.int32)
     delay = np.array([edge_delay(delay_seed, N, phase, i, max_delay) for i in range(N)], dtype=np.int32)
     return peer, delay
+
+
+def uniform24(seed: int, counter: int) -> float:
+    return float(lib().orc_uniform24(seed % 2 ** 64, counter % 2 ** 64))
+
+
+def categorical_sample(logits, u: float):
+    """(action, log pi(action), running sums of pi) for one draw with the uniform variate u."""
+    z = np.ascontiguousarray(logits, dtype=np.float64)
+    cdf = np.empty(z.size)
+    lp = C.c_double()
+    a = lib().orc_categorical_sample(z.size, _p(z), float(u), C.byref(lp), _p(cdf))
+    return int(a), lp.value, cdf
+
+
+def act_counter(step: int, n_agents: int, B: int, agent: int, env: int) -> int:
+    """Index of the uniform variate of (acting step, agent, simulator)."""
+    return (step * n_agents + agent) * B + env
+
+
+def act(net: dict, X: np.ndarray, obs: np.ndarray, seed: int, step: int):
+    """Acting step of Algorithm 1 for all agents: obs uint8 [N, B, C, H, W] -> sampled actions
+    [N, B], values [N, B], log pi(a|s) [N, B], the uniform variates and running sums used."""
+    N, B = obs.shape[:2]
+    A = net["n_actions"]
+    actions = np.empty((N, B), dtype=np.int32)
+    values = np.empty((N, B))
+    logp = np.empty((N, B))
+    us = np.empty((N, B))
+    cdfs = np.empty((N, B, A))
+    for i in range(N):
+        logits, values[i] = forward(net, np.asarray(X[i], dtype=np.float64), obs[i])
+        for b in range(B):
+            us[i, b] = uniform24(seed, act_counter(step, N, B, i, b))
+            actions[i, b], logp[i, b], cdfs[i, b] = categorical_sample(logits[b], us[i, b])
+    return actions, values, logp, us, cdfs
 
 
 def mix_uniform(x: np.ndarray, msgs: list[np.ndarray]) -> np.ndarray:

@@ -195,6 +195,24 @@ def main() -> int:
                               frac_hbm=round(hbm_bytes / (hbm_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)),
         other_ms=round(sum(acc.values()) - mfma_ms - hbm_ms, 4))
 
+    # acting step of Algorithm 1 (policy forward + categorical draw for every agent's B simulators);
+    # reported beside the learner-side metric, not part of `value`
+    act_out = torch.empty((N, B), dtype=torch.int32, device="cuda")
+    val_out = torch.empty((N, B), dtype=torch.float32, device="cuda")
+    for s_ in range(10):
+        gpu.act(pool[0]["boot_obs"], 1, s_, act_out, val_out)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    n_act = 200
+    for s_ in range(n_act):
+        gpu.act(pool[s_ % len(pool)]["boot_obs"], 1, 10 + s_, act_out, val_out)
+    torch.cuda.synchronize()
+    act_s = (time.perf_counter() - t0) / n_act
+    acting = dict(call="gala_act", us_per_call=round(act_s * 1e6, 1), frames_per_call=N * B,
+                  frames_per_s=round(N * B / act_s, 1),
+                  round_with_acting_ms=round(ms_per_step + T * act_s * 1e3, 4),
+                  note=f"a full actor-learner round = {T} acting steps + 1 learner/gossip step")
+
     cpu_baseline = None
     if not args.no_cpu_baseline:
         from oracle import gala_oracle as orc
@@ -237,6 +255,7 @@ def main() -> int:
         "roofline": roofline,
         "phases": phase_summary,
         "kernels": kernels,
+        "acting": acting,
         "cpu_baseline": cpu_baseline,
     }
     print(json.dumps(out))

@@ -148,6 +148,21 @@ int gala_a2c_allreduce_step(gala_ctx *ctx, const uint8_t *obs_u8, const int32_t 
 /* Pre-clip average gradient of the last gala_a2c_allreduce_step, [d] float canonical. */
 int gala_get_mean_grad(gala_ctx *ctx, float *dst, int dst_is_device);
 
+/* Acting step of Algorithm 1 ("take actions according to pi") for every agent's B simulators:
+ * a forward pass of the current parameters over one state per simulator, then one draw per
+ * state from pi = softmax(logits).  All pointers dev:
+ *   obs_u8  uint8 [N][B][4][84][84]   current states
+ *   actions int32 [N][B]              out: sampled actions
+ *   values  float [N][B]              out: V(s) (may be NULL)
+ *   logp    float [N][B]              out: log pi(a|s) of the sampled action (may be NULL)
+ * The draw inverts the distribution function: with u = (top 24 bits of
+ * splitmix64(seed + counter)) / 2^24, counter = (step * N + agent) * B + simulator, the action is
+ * the first one whose running sum pi_0 + ... + pi_a exceeds u.  The same (seed, step) always
+ * gives the same actions.  The call reuses the activation buffers of the learner step: the
+ * outputs and activations of the previous gala_learner_step are no longer readable afterwards. */
+int gala_act(gala_ctx *ctx, const uint8_t *obs_u8, uint64_t seed, int64_t step, int32_t *actions,
+             float *values, float *logp);
+
 /* ---- diagnostics used by tests and logging -------------------------------------- */
 
 /* Pre-clip gradients of the last learner step, [N][d] canonical. */

@@ -364,6 +364,27 @@ extern "C" int gala_round(gala_ctx *c, const uint8_t *obs_u8, const int32_t *act
     return GALA_OK;
 }
 
+extern "C" int gala_act(gala_ctx *c, const uint8_t *obs_u8, uint64_t seed, int64_t step, int32_t *actions,
+                        float *values, float *logp)
+{
+    if (!c) return GALA_EINVAL;
+    if (!obs_u8 || !actions) return fail(c, GALA_EINVAL, "null observation or action buffer");
+    if (reinterpret_cast<uintptr_t>(obs_u8) & 3) return fail(c, GALA_EINVAL, "observation buffer must be 4-byte aligned");
+    if (step < 0) return fail(c, GALA_EINVAL, "negative acting step");
+    // forward pass over B frames per agent: all of them take the policy head, none is a bootstrap state
+    NetArgs a{};
+    a.N = c->N; a.M = c->hp.B; a.F = c->hp.B; a.Bn = 0; a.L = c->L;
+    a.x = c->b.x[c->cur]; a.b = c->b; a.obs = obs_u8; a.boot = obs_u8;
+    a.bf16 = c->hp.compute_dtype == 1;
+    PhaseTimer *pt = &c->timer;
+    pt->begin();
+    HIP_OK(c, launch_forward(a, c->stream, pt));
+    HIP_OK(c, launch_sample(c->N, c->hp.B, c->L.n_actions, c->b.logits, c->b.values, seed, (long)step, actions,
+                            values, logp, c->stream));
+    pt->mark("sample");
+    return GALA_OK;
+}
+
 extern "C" int gala_get_step_stats(gala_ctx *c, float *dst_host)
 {
     if (!c || !dst_host) return fail(c, GALA_EINVAL, "null argument");

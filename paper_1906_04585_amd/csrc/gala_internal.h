@@ -134,6 +134,8 @@ struct NetArgs {
 hipError_t launch_forward(const NetArgs &a, hipStream_t s, PhaseTimer *pt);
 hipError_t launch_loss(const NetArgs &a, const HParams &hp, const int32_t *actions, const float *rewards,
                        const uint8_t *dones, hipStream_t s);
+hipError_t launch_sample(int N, int Bn, int A, const float *logits, const float *values, uint64_t seed, long step,
+                         int32_t *actions, float *values_out, float *logp_out, hipStream_t s);
 hipError_t launch_backward(const NetArgs &a, hipStream_t s, PhaseTimer *pt);
 size_t workspace_floats(int N, int M, int F);
 

@@ -99,6 +99,56 @@ hipError_t launch_loss(const NetArgs &a, const HParams &hp, const int32_t *actio
     return hipGetLastError();
 }
 
+// ---- acting (Algorithm 1: take actions according to pi) ------------------------------------------------
+// One wavefront per (agent, simulator), one lane per action.  u = top 24 bits of
+// splitmix64(seed + counter) / 2^24 with counter = (step * N + agent) * B + simulator; the action is
+// the first one whose running sum of exp(z - max z) exceeds u times the total.
+static __device__ __forceinline__ uint64_t splitmix64_dev(uint64_t z)
+{
+    z += 0x9E3779B97F4A7C15ull;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+__global__ __launch_bounds__(256) void sample_kernel(int N, int Bn, int A, const float *__restrict__ logits,
+                                                     const float *__restrict__ values, uint64_t seed, long step,
+                                                     int32_t *actions, float *values_out, float *logp_out)
+{
+    const int lane = threadIdx.x & 63;
+    const int s = blockIdx.x * 4 + (threadIdx.x >> 6);          // uniform per wavefront
+    if (s >= N * Bn) return;
+    const bool on = lane < A;
+    const float z = on ? logits[(long)s * A + lane] : -INFINITY;
+    float zmax = z;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) zmax = fmaxf(zmax, __shfl_xor(zmax, off, 64));
+    float c = on ? expf(z - zmax) : 0.f;                        // becomes the inclusive running sum
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const float t = __shfl_up(c, off, 64);
+        if (lane >= off) c += t;
+    }
+    const float total = __shfl(c, 63, 64);
+    const float u = (float)(splitmix64_dev(seed + (uint64_t)((long)step * N * Bn + s)) >> 40) * (1.0f / 16777216.0f);
+    const unsigned long long above = __ballot(on && c > u * total);
+    const int a = above ? __ffsll(above) - 1 : A - 1;
+    const float lp = __shfl(z, a, 64) - (zmax + logf(total));
+    if (lane == 0) {
+        actions[s] = a;
+        if (values_out) values_out[s] = values[s];
+        if (logp_out) logp_out[s] = lp;
+    }
+}
+
+hipError_t launch_sample(int N, int Bn, int A, const float *logits, const float *values, uint64_t seed, long step,
+                         int32_t *actions, float *values_out, float *logp_out, hipStream_t s)
+{
+    hipLaunchKernelGGL(sample_kernel, dim3((N * Bn + 3) / 4), dim3(256), 0, s, N, Bn, A, logits, values, seed, step,
+                       actions, values_out, logp_out);
+    return hipGetLastError();
+}
+
 // ---- global gradient norm per agent and clip factor (Table 2: clip global gradient norm) ----------
 // The hidden layer's weight gradient (95 % of the parameters) arrives as per-tile sums of
 // squares from the kernel that produced it; this kernel adds the squares of everything in

@@ -172,9 +172,12 @@ using Conv2Fwd = ConvFwd<C1, H1, W1, C2, H2, W2, K2, S2>;
 using Conv3Fwd = ConvFwd<C2, H2, W2, C3, H3, W3, K3, S3>;
 
 // ---- hidden layer forward (split over k; partial sums to the workspace) -------------------
-// m = f, n = j, k = flattened a3.
-struct FcFwd : ProblemBase {
-    static constexpr int BM = 96, BN = 128, BK = 16, WM = 1, WN = 4;
+// m = f, n = j, k = flattened a3.  The row tile is chosen by the number of frames: 96 for a
+// learner step (T*B + B frames), 16 or 32 for an acting step (B frames), where the layer is
+// bound by streaming its weights and a tall tile would be mostly padding.
+template <int BM_>
+struct FcFwdT : ProblemBase {
+    static constexpr int BM = BM_, BN = 128, BK = 16, WM = 1, WN = 4;
     static constexpr bool A_KC = true, B_KC = true;
     const float *a3, *x;
     float *ws;
@@ -200,6 +203,7 @@ struct FcFwd : ProblemBase {
         if (!CHECK || m < F) st4(out_ + (long)m * FC + n, v);
     }
 };
+using FcFwd = FcFwdT<96>;
 
 // ---- hidden layer: gradient to a3 (masked by its ReLU) ---------------------------------------
 // m = f, n = flattened a3 index, k = j.
@@ -695,12 +699,15 @@ __global__ __launch_bounds__(256) void heads_wgrad_kernel(const float *__restric
 static inline int cdiv(long a, long b) { return (int)((a + b - 1) / b); }
 
 constexpr int FC_KCHUNK = 448;          // 3136 = 7 * 448
+constexpr int FC_KCHUNK_SMALL = 224;    // few frames: twice the splits, so that enough workgroups stream the weights
+constexpr int FC_SMALL_FRAMES = 32;
 constexpr int FPS_CONV1 = 2, FPS_CONV2 = 8, FPS_CONV3 = 16;   // frames per split of the weight gradients
 
 size_t workspace_floats(int N, int M, int F)
 {
     size_t need = (size_t)N * cdiv(FLAT, FC_KCHUNK) * F * FC;
     auto mx = [&](size_t v) { if (v > need) need = v; };
+    mx((size_t)N * cdiv(FLAT, FC_KCHUNK_SMALL) * FC_SMALL_FRAMES * FC);
     mx((size_t)N * cdiv(M, FPS_CONV1) * Conv1Wgrad::PART);
     mx((size_t)N * cdiv(M, FPS_CONV2) * Conv2Wgrad::PART);
     mx((size_t)N * cdiv(M, FPS_CONV3) * Conv3Wgrad::PART);
@@ -735,15 +742,21 @@ hipError_t launch_forward(const NetArgs &a, hipStream_t s, PhaseTimer *pt)
         pt->mark("conv3_fwd");
     }
     {
-        FcFwd p{};
-        p.a3 = a.b.a3; p.x = a.x; p.ws = a.b.ws; p.d_pad = L.d_pad; p.w_off = L.fcw; p.F = a.F;
-        p.kchunk = FC_KCHUNK;
-        p.tiles_m = cdiv(a.F, FcFwd::BM); p.tiles_n = FC / FcFwd::BN; p.splits = cdiv(FLAT, FC_KCHUNK);
-        GALA_TRY(igemm_launch(p, a.N, s, a.bf16));
-        pt->mark("fc_fwd");
-        hipLaunchKernelGGL(fc_reduce_heads_kernel, dim3(a.F, a.N), dim3(128), 0, s, a.b.ws, p.splits, a.x, L,
-                           a.M, a.F, a.b.h, a.b.logits, a.b.values);
-        pt->mark("fc_reduce_heads");
+        auto run = [&](auto p, int kchunk) -> hipError_t {
+            typedef decltype(p) P;
+            p.a3 = a.b.a3; p.x = a.x; p.ws = a.b.ws; p.d_pad = L.d_pad; p.w_off = L.fcw; p.F = a.F;
+            p.kchunk = kchunk;
+            p.tiles_m = cdiv(a.F, P::BM); p.tiles_n = FC / P::BN; p.splits = cdiv(FLAT, kchunk);
+            GALA_TRY(igemm_launch(p, a.N, s, a.bf16));
+            pt->mark("fc_fwd");
+            hipLaunchKernelGGL(fc_reduce_heads_kernel, dim3(a.F, a.N), dim3(128), 0, s, a.b.ws, p.splits, a.x, L,
+                               a.M, a.F, a.b.h, a.b.logits, a.b.values);
+            pt->mark("fc_reduce_heads");
+            return hipGetLastError();
+        };
+        if (a.F <= 16) GALA_TRY(run(FcFwdT<16>{}, FC_KCHUNK_SMALL));
+        else if (a.F <= FC_SMALL_FRAMES) GALA_TRY(run(FcFwdT<32>{}, FC_KCHUNK_SMALL));
+        else GALA_TRY(run(FcFwd{}, FC_KCHUNK));
     }
     return hipGetLastError();
 }

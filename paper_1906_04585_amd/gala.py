@@ -16,7 +16,7 @@ _LIB_PATH = os.environ.get("GALA_LIBRARY", os.path.join(_PKG, "libgala.so"))
 EXPORTS = [
     "gala_create", "gala_destroy", "gala_param_count", "gala_last_error",
     "gala_set_params", "gala_get_params", "gala_set_opt_state", "gala_get_opt_state",
-    "gala_learner_step", "gala_gossip", "gala_round", "gala_a2c_allreduce_step", "gala_get_mean_grad", "gala_get_grads", "gala_get_step_stats",
+    "gala_learner_step", "gala_gossip", "gala_round", "gala_a2c_allreduce_step", "gala_get_mean_grad", "gala_act", "gala_get_grads", "gala_get_step_stats",
     "gala_get_outputs", "gala_consensus_distance", "gala_get_peer_table",
     "gala_set_profiling", "gala_get_phase_times", "gala_get_activations",
 ]
@@ -74,6 +74,7 @@ def load_library():
         L.gala_round.argtypes = [C.c_void_p] * 6 + [C.c_int64]
         L.gala_a2c_allreduce_step.argtypes = [C.c_void_p] * 6
         L.gala_get_mean_grad.argtypes = [C.c_void_p, C.c_void_p, C.c_int]
+        L.gala_act.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p]
         L.gala_get_step_stats.argtypes = [C.c_void_p, C.c_void_p]
         L.gala_get_outputs.argtypes = [C.c_void_p] * 5
         L.gala_consensus_distance.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
@@ -210,6 +211,16 @@ class Gala:
         a = np.empty(self.d, dtype=np.float32)
         self._check(self._lib.gala_get_mean_grad(self._h, a.ctypes.data_as(C.c_void_p), 0))
         return a
+
+    def act(self, obs_u8, seed: int, step: int, actions, values=None, logp=None):
+        """actions int32 [N][B] (and optionally values, logp float32 [N][B]) are CUDA tensors written in place."""
+        import torch
+        n = self.N * self.B
+        self._check(self._lib.gala_act(
+            self._h, _dev_ptr(obs_u8, torch.uint8, n * 4 * 84 * 84), C.c_uint64(seed % 2 ** 64), int(step),
+            _dev_ptr(actions, torch.int32, n),
+            None if values is None else _dev_ptr(values, torch.float32, n),
+            None if logp is None else _dev_ptr(logp, torch.float32, n)))
 
     def gossip(self, rnd: int):
         self._check(self._lib.gala_gossip(self._h, int(rnd)))

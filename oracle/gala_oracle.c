@@ -639,3 +639,52 @@ void orc_consensus_distance(const double *X, int N, long d, double *max_row, dou
     free(mean);
     *max_row = mx; *frob = sqrt(tot);
 }
+
+/* ---- diagnostics of Sec. 5 "Effects of gossip" ---------------------------------- */
+
+/* Pair-wise cosine similarity of the agents' gradients (Fig. 2b):
+ * out[i][j] = <g_i, g_j> / (||g_i|| ||g_j||); a zero gradient gives 0. */
+void orc_cosine_matrix(const double *G, int N, long d, double *out)
+{
+    double *nrm = (double *)malloc(sizeof(double) * (size_t)N);
+    for (int i = 0; i < N; ++i) {
+        double ss = 0.0;
+        for (long e = 0; e < d; ++e) ss += G[(long)i * d + e] * G[(long)i * d + e];
+        nrm[i] = sqrt(ss);
+    }
+    for (int i = 0; i < N; ++i)
+        for (int j = 0; j < N; ++j) {
+            double dot = 0.0;
+            for (long e = 0; e < d; ++e) dot += G[(long)i * d + e] * G[(long)j * d + e];
+            out[(long)i * N + j] = (nrm[i] > 0.0 && nrm[j] > 0.0) ? dot / (nrm[i] * nrm[j]) : 0.0;
+        }
+    free(nrm);
+}
+
+/* Size of one round's local updates in the notation of Prop. 1: the update matrix
+ * alpha G^(k) has rows x_i(before the optimiser step) - x_i(after it, before
+ * mixing).  row_norms[i] = ||alpha g_i||_2 (may be NULL); returns ||alpha G||_F. */
+double orc_update_norm(const double *X_before, const double *X_after, int N, long d, double *row_norms)
+{
+    double tot = 0.0;
+    for (int i = 0; i < N; ++i) {
+        double ss = 0.0;
+        for (long e = 0; e < d; ++e) {
+            const double t = X_before[(long)i * d + e] - X_after[(long)i * d + e];
+            ss += t * t;
+        }
+        if (row_norms) row_norms[i] = sqrt(ss);
+        tot += ss;
+    }
+    return sqrt(tot);
+}
+
+/* Right-hand side of Prop. 1 after k + 1 rounds for agents that started from
+ * identical parameters: sum_{s=0..k} beta^(k+1-s) ||alpha G^(s)||, with
+ * update_norms[s] = ||alpha G^(s)|| (n = k + 1 entries). */
+double orc_prop1_bound(double beta, const double *update_norms, int n)
+{
+    double acc = 0.0;
+    for (int s = 0; s < n; ++s) acc += pow(beta, (double)(n - s)) * update_norms[s];
+    return acc;
+}

@@ -72,6 +72,11 @@ def lib():
         L.orc_mix_weighted.argtypes = [C.c_void_p, C.c_double, C.c_void_p, C.c_void_p,
                                        C.c_int, C.c_long, C.c_void_p]
         L.orc_consensus_distance.argtypes = [C.c_void_p, C.c_int, C.c_long, C.c_void_p, C.c_void_p]
+        L.orc_cosine_matrix.argtypes = [C.c_void_p, C.c_int, C.c_long, C.c_void_p]
+        L.orc_update_norm.restype = C.c_double
+        L.orc_update_norm.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_long, C.c_void_p]
+        L.orc_prop1_bound.restype = C.c_double
+        L.orc_prop1_bound.argtypes = [C.c_double, C.c_void_p, C.c_int]
         _lib = L
     return _lib
 
@@ -320,6 +325,28 @@ def consensus_distance(X: np.ndarray):
     mx, fr = C.c_double(0.0), C.c_double(0.0)
     lib().orc_consensus_distance(_p(X), X.shape[0], X.shape[1], C.byref(mx), C.byref(fr))
     return float(mx.value), float(fr.value)
+
+
+def cosine_matrix(G: np.ndarray) -> np.ndarray:
+    """Pair-wise cosine similarity [N, N] of the rows of G (Fig. 2b)."""
+    G = np.ascontiguousarray(G, dtype=np.float64)
+    out = np.empty((G.shape[0], G.shape[0]))
+    lib().orc_cosine_matrix(_p(G), G.shape[0], G.shape[1], _p(out))
+    return out
+
+
+def update_norm(X_before: np.ndarray, X_after: np.ndarray):
+    """(||alpha G||_F, per-agent ||alpha g_i||_2) of one round's optimiser step (Prop. 1)."""
+    a = np.ascontiguousarray(X_before, dtype=np.float64)
+    b = np.ascontiguousarray(X_after, dtype=np.float64)
+    rows = np.empty(a.shape[0])
+    fr = lib().orc_update_norm(_p(a), _p(b), a.shape[0], a.shape[1], _p(rows))
+    return float(fr), rows
+
+
+def prop1_bound(beta: float, update_norms) -> float:
+    u = np.ascontiguousarray(update_norms, dtype=np.float64)
+    return float(lib().orc_prop1_bound(float(beta), _p(u), u.size))
 
 
 # ---- Algorithm 1 for N agents ------------------------------------------------

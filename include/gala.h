@@ -176,6 +176,20 @@ int gala_get_step_stats(gala_ctx *ctx, float *dst_host);
 int gala_get_outputs(gala_ctx *ctx, float *logits, float *values, float *returns, float *advantages);
 /* Distance from consensus (Prop. 1): max_i ||x_i - mean||_2 and ||X - mean||_F, host floats. */
 int gala_consensus_distance(gala_ctx *ctx, float *max_dist, float *frob);
+/* Pair-wise cosine similarity of the agents' gradients of the last learner step (Fig. 2b):
+ * cos[i][j] = <g_i, g_j> / (||g_i|| ||g_j||), pre-clip gradients, host float [N][N]; rows and
+ * columns of an agent whose gradient is zero are 0.  One pass over the gradient arena. */
+int gala_grad_cosine(gala_ctx *ctx, float *cos_host);
+/* Size of the last optimiser step in the notation of Prop. 1: row i of the update matrix
+ * alpha G is x_i before the step minus x_i after it (before mixing).  row_norms_host: float [N]
+ * = ||alpha g_i||_2 (may be NULL); *frob_host = ||alpha G||_F.  Valid after gala_learner_step,
+ * gala_round or gala_a2c_allreduce_step and before the next of them. */
+int gala_update_norm(gala_ctx *ctx, float *row_norms_host, float *frob_host);
+/* Right-hand side of Prop. 1 for agents that started from identical parameters:
+ * *bound = sum_{s=0..n-1} beta^(n-s) update_norms[s], where update_norms[s] = ||alpha G^(s)||
+ * of round s (gala_update_norm) and beta in [0, 1] is the contraction factor of the mixing
+ * matrices (cos(pi/N) for the directed ring with weights 1/2).  Host arithmetic only. */
+int gala_prop1_bound(double beta, const double *update_norms, int n, double *bound);
 /* In-peer and delay tables the library will use at `round`, host int32 [N][max_in] each
  * (max_in = 1 for ring and exponential graphs). */
 int gala_get_peer_table(gala_ctx *ctx, int64_t round, int32_t *peer, int32_t *delay);

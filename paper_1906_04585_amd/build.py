@@ -9,7 +9,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libgala.so")
-SOURCES = ["gala_api.hip", "net_kernels.hip", "loss_optim_kernels.hip"]
+SOURCES = ["gala_api.hip", "net_kernels.hip", "loss_optim_kernels.hip", "diag_kernels.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

@@ -26,6 +26,7 @@ struct gala_ctx {
     int cur = 0;                 // which of b.x[] holds the current parameters
     float *canon = nullptr;      // [N][d] staging for get/set through host pointers
     int64_t last_round = -1;
+    bool shared_gradient = false;   // the last optimiser step applied the averaged gradient
     hipStream_t stream = nullptr;
     int device = 0;
     std::vector<void *> allocs;
@@ -191,6 +192,9 @@ extern "C" int gala_create(gala_ctx **out, int n_agents, const gala_topology *to
 #undef ALLOC_ZP
     ALLOC(b.ws, workspace_floats(c->N, c->M, c->F), false);
     ALLOC(b.norm_part, N * NORM_PARTS, true);
+    ALLOC(b.gram_part, (size_t)gram_pairs(c->N) * gram_chunks(c->N) * GRAM_T * GRAM_T, false);
+    ALLOC(b.gram, N * N, true); ALLOC(b.cosm, N * N, true);
+    ALLOC(b.upd_part, N * UPDATE_NORM_BLOCKS, true); ALLOC(b.upd_norm, N + 2, true); ALLOC(b.row_ss, N, true);
     ALLOC(b.gbar, dp, true); ALLOC(b.gbar_part, (size_t)grad_mean_blocks(c->L), true);
     ALLOC(b.stats, N * 5, true);
     ALLOC(b.cons_part, N * ((dp + CONS_COLS - 1) / CONS_COLS) + 2, true);
@@ -309,6 +313,7 @@ extern "C" int gala_learner_step(gala_ctx *c, const uint8_t *obs_u8, const int32
     if (rc != GALA_OK) return rc;
     HIP_OK(c, launch_rmsprop(c->N, c->L, c->hp, c->b.x[c->cur], c->b.v, c->b.g, false, c->b.stats, c->stream));
     c->timer.mark("clip_rmsprop");
+    c->shared_gradient = false;
     return GALA_OK;
 }
 
@@ -322,6 +327,7 @@ extern "C" int gala_a2c_allreduce_step(gala_ctx *c, const uint8_t *obs_u8, const
     c->timer.mark("grad_mean_norm");
     HIP_OK(c, launch_rmsprop(c->N, c->L, c->hp, c->b.x[c->cur], c->b.v, c->b.gbar, true, c->b.stats, c->stream));
     c->timer.mark("clip_rmsprop");
+    c->shared_gradient = true;
     return GALA_OK;
 }
 
@@ -360,6 +366,7 @@ extern "C" int gala_round(gala_ctx *c, const uint8_t *obs_u8, const int32_t *act
     HIP_OK(c, launch_rmsprop_mix(c->N, c->L, c->hp, c->b.x[c->cur], c->b.v, c->b.g, c->b.hist, c->tau, (long)round,
                                  phase, c->max_in, c->b.peer, c->b.delay, c->b.weight, c->b.stats, c->stream));
     c->timer.mark("clip_rmsprop_mix");
+    c->shared_gradient = false;
     c->last_round = round;
     return GALA_OK;
 }
@@ -410,11 +417,49 @@ extern "C" int gala_consensus_distance(gala_ctx *c, float *max_dist, float *frob
     if (!c || !max_dist || !frob) return fail(c, GALA_EINVAL, "null argument");
     const size_t chunks = (c->L.d_pad + CONS_COLS - 1) / CONS_COLS;
     float *result = c->b.cons_part + (size_t)c->N * chunks;
-    HIP_OK(c, launch_consensus(c->N, c->L, c->b.x[c->cur], c->b.cons_part, result, c->stream));
+    c->timer.mark("diag_begin");
+    HIP_OK(c, launch_consensus(c->N, c->L, c->b.x[c->cur], c->b.cons_part, c->b.row_ss, result, c->stream));
+    c->timer.mark("consensus_distance");
     float r[2];
     HIP_OK(c, hipMemcpyAsync(r, result, 8, hipMemcpyDeviceToHost, c->stream));
     HIP_OK(c, hipStreamSynchronize(c->stream));
     *max_dist = r[0]; *frob = r[1];
+    return GALA_OK;
+}
+
+extern "C" int gala_grad_cosine(gala_ctx *c, float *cos_host)
+{
+    if (!c || !cos_host) return fail(c, GALA_EINVAL, "null argument");
+    c->timer.mark("diag_begin");
+    HIP_OK(c, launch_grad_cosine(c->N, c->L, c->b.g, c->b.gram_part, c->b.gram, c->b.cosm, c->stream));
+    c->timer.mark("grad_cosine");
+    HIP_OK(c, hipMemcpyAsync(cos_host, c->b.cosm, (size_t)c->N * c->N * 4, hipMemcpyDeviceToHost, c->stream));
+    HIP_OK(c, hipStreamSynchronize(c->stream));
+    return GALA_OK;
+}
+
+extern "C" int gala_update_norm(gala_ctx *c, float *row_norms_host, float *frob_host)
+{
+    if (!c || !frob_host) return fail(c, GALA_EINVAL, "null argument");
+    c->timer.mark("diag_begin");
+    HIP_OK(c, launch_update_norm(c->N, c->L, c->hp, c->shared_gradient ? c->b.gbar : c->b.g, c->shared_gradient,
+                                 c->b.v, c->b.stats, c->b.upd_part, c->b.row_ss, c->b.upd_norm, c->stream));
+    c->timer.mark("update_norm");
+    if (row_norms_host)
+        HIP_OK(c, hipMemcpyAsync(row_norms_host, c->b.upd_norm, (size_t)c->N * 4, hipMemcpyDeviceToHost, c->stream));
+    HIP_OK(c, hipMemcpyAsync(frob_host, c->b.upd_norm + c->N + 1, 4, hipMemcpyDeviceToHost, c->stream));
+    HIP_OK(c, hipStreamSynchronize(c->stream));
+    return GALA_OK;
+}
+
+extern "C" int gala_prop1_bound(double beta, const double *update_norms, int n, double *bound)
+{
+    if (!update_norms || !bound || n < 0 || !(beta >= 0.0 && beta <= 1.0))
+        return fail(nullptr, GALA_EINVAL, "need update norms, 0 <= beta <= 1, n >= 0");
+    // sum_{s < n} beta^(n - s) u_s by Horner's rule: B <- beta (B + u_s)
+    double b = 0.0;
+    for (int s = 0; s < n; ++s) b = beta * (b + update_norms[s]);
+    *bound = b;
     return GALA_OK;
 }
 

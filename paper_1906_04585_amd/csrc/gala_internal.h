@@ -83,8 +83,11 @@ struct Buffers {
     float *ws;                        // split-K partial sums
     float *norm_part;                 // [N][NORM_PARTS]
     float *gbar, *gbar_part;          // [d_pad] gradient averaged over agents, [grad_mean_blocks] its squares
+    float *gram_part, *gram, *cosm;   // [pairs][chunks][GRAM_T^2] partial Gram tiles, [N][N] Gram, [N][N] cosine
+    float *upd_part, *upd_norm;       // [N][UPDATE_NORM_BLOCKS], [N] row norms + [2] (largest row, Frobenius)
     float *stats;                     // [N][5]
     float *cons_part;                 // [N][CONS_CHUNKS] + 2 results
+    float *row_ss;                    // [N] scratch of the norm reductions
     int32_t *peer, *delay;            // [phases][N][max_in]
     float *weight;                    // [phases][N][max_in+1]
 };
@@ -154,8 +157,21 @@ hipError_t launch_publish(int N, const Layout &L, const float *x, float *hist_sl
 hipError_t launch_mix(int N, const Layout &L, const float *x_in, float *x_out, const float *hist, int tau,
                       long round, int phase, int max_in, const int32_t *peer, const int32_t *delay,
                       const float *weight, hipStream_t s);
+// diagnostics (Sec. 5 "Effects of gossip")
+constexpr int GRAM_T = 32;                 // agents per tile side of the gradient Gram matrix
+constexpr int UPDATE_NORM_BLOCKS = 64;
+int gram_pairs(int N);
+int gram_chunks(int N);
+hipError_t launch_grad_cosine(int N, const Layout &L, const float *g, float *part, float *gram, float *cosm,
+                              hipStream_t s);
+hipError_t launch_update_norm(int N, const Layout &L, const HParams &hp, const float *g, bool shared_gradient,
+                              const float *v, const float *stats, float *part, float *row_ss, float *out,
+                              hipStream_t s);
 constexpr int CONS_COLS = 1024;   // columns per workgroup of the consensus kernel
-hipError_t launch_consensus(int N, const Layout &L, const float *x, float *part, float *result, hipStream_t s);
+hipError_t launch_row_norms(const float *part, int rows, int cols, float *row_ss, float *row_norm, float *result,
+                            hipStream_t s);
+hipError_t launch_consensus(int N, const Layout &L, const float *x, float *part, float *row_ss, float *result,
+                            hipStream_t s);
 hipError_t launch_permute(int N, const Layout &L, const SegmentTable &tab, float *canon, float *intern,
                           int to_internal, hipStream_t s);
 

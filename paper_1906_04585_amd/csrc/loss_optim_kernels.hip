@@ -478,29 +478,60 @@ __global__ __launch_bounds__(256) void consensus_kernel(const float *__restrict_
     }
 }
 
-__global__ __launch_bounds__(256) void consensus_final_kernel(const float *__restrict__ part, int N, int chunks,
-                                                              float *result)
+// Row sums of a [rows][cols] array of partial sums of squares, one wavefront per row, and the
+// norms made of them: row_norm[i] = sqrt(row sum) (optional), result[0] = sqrt(largest row sum),
+// result[1] = sqrt(total).  Fixed summation order.
+__global__ __launch_bounds__(64) void row_sums_kernel(const float *__restrict__ part, int cols, float *row_ss)
 {
-    __shared__ float red[4];
-    float mx = 0.f, tot = 0.f;
-    for (int i = 0; i < N; ++i) {
-        float acc = 0.f;
-        for (int c = threadIdx.x; c < chunks; c += 256) acc += part[(long)i * chunks + c];
-        acc = block_sum_256(acc, red);
-        mx = fmaxf(mx, acc);
-        tot += acc;
-    }
-    if (threadIdx.x == 0) { result[0] = sqrtf(mx); result[1] = sqrtf(tot); }
+    const float *p = part + (long)blockIdx.x * cols;
+    float acc = 0.f;
+    for (int c = threadIdx.x; c < cols; c += 64) acc += p[c];
+    acc = wave_sum(acc);
+    if (threadIdx.x == 0) row_ss[blockIdx.x] = acc;
 }
 
-hipError_t launch_consensus(int N, const Layout &L, const float *x, float *part, float *result, hipStream_t s)
+__global__ __launch_bounds__(256) void norms_finish_kernel(const float *__restrict__ row_ss, int rows, float *row_norm,
+                                                           float *result)
+{
+    __shared__ float red_max[4], red_sum[4];
+    float mx = 0.f, tot = 0.f;
+    for (int i = threadIdx.x; i < rows; i += 256) {
+        const float ss = row_ss[i];
+        if (row_norm) row_norm[i] = sqrtf(ss);
+        mx = fmaxf(mx, ss);
+        tot += ss;
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        mx = fmaxf(mx, __shfl_xor(mx, off, 64));
+        tot += __shfl_xor(tot, off, 64);
+    }
+    if ((threadIdx.x & 63) == 0) { red_max[threadIdx.x >> 6] = mx; red_sum[threadIdx.x >> 6] = tot; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        result[0] = sqrtf(fmaxf(fmaxf(red_max[0], red_max[1]), fmaxf(red_max[2], red_max[3])));
+        result[1] = sqrtf((red_sum[0] + red_sum[1]) + (red_sum[2] + red_sum[3]));
+    }
+}
+
+hipError_t launch_row_norms(const float *part, int rows, int cols, float *row_ss, float *row_norm, float *result,
+                            hipStream_t s)
+{
+    hipLaunchKernelGGL(row_sums_kernel, dim3(rows), dim3(64), 0, s, part, cols, row_ss);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(norms_finish_kernel, dim3(1), dim3(256), 0, s, row_ss, rows, row_norm, result);
+    return hipGetLastError();
+}
+
+hipError_t launch_consensus(int N, const Layout &L, const float *x, float *part, float *row_ss, float *result,
+                            hipStream_t s)
 {
     const int chunks = (int)((L.d_pad + CONS_COLS - 1) / CONS_COLS);
     hipLaunchKernelGGL(consensus_kernel, dim3(chunks), dim3(256), 0, s, x, N, L.d_pad, chunks, part);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(consensus_final_kernel, dim3(1), dim3(256), 0, s, part, N, chunks, result);
-    return hipGetLastError();
+    return launch_row_norms(part, N, chunks, row_ss, nullptr, result, s);
 }
 
 // ---- canonical <-> internal order --------------------------------------------------------------------------

@@ -16,7 +16,7 @@ _LIB_PATH = os.environ.get("GALA_LIBRARY", os.path.join(_PKG, "libgala.so"))
 EXPORTS = [
     "gala_create", "gala_destroy", "gala_param_count", "gala_last_error",
     "gala_set_params", "gala_get_params", "gala_set_opt_state", "gala_get_opt_state",
-    "gala_learner_step", "gala_gossip", "gala_round", "gala_a2c_allreduce_step", "gala_get_mean_grad", "gala_act", "gala_get_grads", "gala_get_step_stats",
+    "gala_learner_step", "gala_gossip", "gala_round", "gala_a2c_allreduce_step", "gala_get_mean_grad", "gala_act", "gala_grad_cosine", "gala_update_norm", "gala_prop1_bound", "gala_get_grads", "gala_get_step_stats",
     "gala_get_outputs", "gala_consensus_distance", "gala_get_peer_table",
     "gala_set_profiling", "gala_get_phase_times", "gala_get_activations",
 ]
@@ -74,6 +74,9 @@ def load_library():
         L.gala_round.argtypes = [C.c_void_p] * 6 + [C.c_int64]
         L.gala_a2c_allreduce_step.argtypes = [C.c_void_p] * 6
         L.gala_get_mean_grad.argtypes = [C.c_void_p, C.c_void_p, C.c_int]
+        L.gala_grad_cosine.argtypes = [C.c_void_p, C.c_void_p]
+        L.gala_update_norm.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
+        L.gala_prop1_bound.argtypes = [C.c_double, C.c_void_p, C.c_int, C.c_void_p]
         L.gala_act.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p]
         L.gala_get_step_stats.argtypes = [C.c_void_p, C.c_void_p]
         L.gala_get_outputs.argtypes = [C.c_void_p] * 5
@@ -222,6 +225,17 @@ class Gala:
             None if values is None else _dev_ptr(values, torch.float32, n),
             None if logp is None else _dev_ptr(logp, torch.float32, n)))
 
+    def grad_cosine(self) -> np.ndarray:
+        a = np.empty((self.N, self.N), dtype=np.float32)
+        self._check(self._lib.gala_grad_cosine(self._h, a.ctypes.data_as(C.c_void_p)))
+        return a
+
+    def update_norm(self):
+        rows = np.empty(self.N, dtype=np.float32)
+        fr = C.c_float()
+        self._check(self._lib.gala_update_norm(self._h, rows.ctypes.data_as(C.c_void_p), C.byref(fr)))
+        return float(fr.value), rows
+
     def gossip(self, rnd: int):
         self._check(self._lib.gala_gossip(self._h, int(rnd)))
 
@@ -273,3 +287,12 @@ class Gala:
         a = np.empty((self.N, F) + self._ACT_SHAPES[layer], dtype=np.float32)
         self._check(self._lib.gala_get_activations(self._h, layer, a.ctypes.data_as(C.c_void_p)))
         return a
+
+
+def prop1_bound(beta: float, update_norms) -> float:
+    u = np.ascontiguousarray(update_norms, dtype=np.float64)
+    out = C.c_double()
+    rc = load_library().gala_prop1_bound(float(beta), u.ctypes.data_as(C.c_void_p), int(u.size), C.byref(out))
+    if rc != 0:
+        raise GalaError(rc, load_library().gala_last_error(None).decode())
+    return float(out.value)

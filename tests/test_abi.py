@@ -89,3 +89,15 @@ def test_parameter_count_formula():
     # d = 1 684 128 + 513 + 513 A  (trunk + value head + policy head)
     assert gs.param_count(gs.make_net(6)) == 1_687_719
     assert gs.param_count(gs.make_net(18)) == 1_693_875
+
+
+def test_prop1_bound_is_host_arithmetic_and_matches_the_oracle():
+    from oracle import gala_oracle as orc
+    from paper_1906_04585_amd.gala import GalaError, prop1_bound
+    u = np.array([0.3, 1.1, 0.7, 2.0, 0.05])
+    for beta in (0.0, 0.31, np.cos(np.pi / 4), 1.0):
+        for n in range(u.size + 1):
+            want = orc.prop1_bound(beta, u[:n])
+            assert abs(prop1_bound(beta, u[:n]) - want) <= 1e-14 * max(want, 1.0)
+    with pytest.raises(GalaError):
+        prop1_bound(1.5, u)

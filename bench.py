@@ -213,6 +213,26 @@ def main() -> int:
                   round_with_acting_ms=round(ms_per_step + T * act_s * 1e3, 4),
                   note=f"a full actor-learner round = {T} acting steps + 1 learner/gossip step")
 
+    # diagnostics of Sec. 5 (gradient cosine matrix, update norm, consensus distance): event-timed per call
+    gpu.set_profiling(True)
+    dacc: dict[str, float] = {}
+    n_diag = 10
+    for _ in range(n_diag):
+        one_round(rnd)
+        rnd += 1
+        gpu.grad_cosine()
+        gpu.update_norm()
+        gpu.consensus_distance()
+        for k, v in gpu.get_phase_times().items():
+            if k in ("grad_cosine", "update_norm", "consensus_distance"):
+                dacc[k] = dacc.get(k, 0.0) + v / n_diag
+    gpu.set_profiling(False)
+    # algorithmic bytes: every gradient (parameter) read once; update norm reads g and v
+    diag_bytes = {"grad_cosine": 4.0 * gpu.d * N, "update_norm": 8.0 * gpu.d * N, "consensus_distance": 4.0 * gpu.d * N}
+    diagnostics = {k: dict(ms=round(ms, 5), bound="hbm", achieved=round(diag_bytes[k] / (ms * 1e-3) / 1e9, 1),
+                           unit="GB/s", frac=round(diag_bytes[k] / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4))
+                   for k, ms in dacc.items()}
+
     cpu_baseline = None
     if not args.no_cpu_baseline:
         from oracle import gala_oracle as orc
@@ -256,6 +276,7 @@ def main() -> int:
         "phases": phase_summary,
         "kernels": kernels,
         "acting": acting,
+        "diagnostics": diagnostics,
         "cpu_baseline": cpu_baseline,
     }
     print(json.dumps(out))

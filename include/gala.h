@@ -93,7 +93,12 @@ typedef struct {
 
 /* Create a context for n_agents agents.  hip_stream is a hipStream_t (NULL = the
  * default stream) on which all work is enqueued.  Parameters start at zero and the
- * RMSprop state at zero; call gala_set_params before the first learner step. */
+ * RMSprop state at zero; call gala_set_params before the first learner step.
+ * The context also owns one internal stream of default priority on which the weight-gradient
+ * kernels of a learner step run beside the data-gradient chain; it is forked from and joined
+ * back into hip_stream inside every call, so callers only ever order against hip_stream.
+ * Setting the environment variable GALA_SINGLE_STREAM before gala_create keeps everything on
+ * hip_stream (same kernels, same results). */
 int gala_create(gala_ctx **out, int n_agents, const gala_topology *topo,
                 const gala_net_dims *net, const gala_hparams *hp, void *hip_stream);
 int gala_destroy(gala_ctx *ctx);

@@ -7,6 +7,7 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -31,6 +32,7 @@ struct gala_ctx {
     int device = 0;
     std::vector<void *> allocs;
     PhaseTimer timer;
+    SideStream side;             // weight gradients run here next to the data-gradient chain
     char err[512] = {0};
 };
 
@@ -207,6 +209,12 @@ extern "C" int gala_create(gala_ctx **out, int n_agents, const gala_topology *to
     if (he == hipSuccess) he = hipMemcpyAsync(b.weight, c->h_weight.data(), c->h_weight.size() * 4, hipMemcpyHostToDevice, c->stream);
     if (he == hipSuccess) he = hipStreamSynchronize(c->stream);
     if (he != hipSuccess) { fail(c, GALA_EHIP, "table upload: %s", hipGetErrorString(he)); return bail(GALA_EHIP); }
+    if (!getenv("GALA_SINGLE_STREAM")) {
+        he = hipStreamCreateWithFlags(&c->side.stream, hipStreamNonBlocking);
+        for (int i = 0; i < 4 && he == hipSuccess; ++i) he = hipEventCreateWithFlags(&c->side.fork[i], hipEventDisableTiming);
+        if (he == hipSuccess) he = hipEventCreateWithFlags(&c->side.join, hipEventDisableTiming);
+        if (he != hipSuccess) { fail(c, GALA_EHIP, "side stream: %s", hipGetErrorString(he)); return bail(GALA_EHIP); }
+    }
     *out = c;
     return GALA_OK;
 }
@@ -214,7 +222,11 @@ extern "C" int gala_create(gala_ctx **out, int n_agents, const gala_topology *to
 extern "C" int gala_destroy(gala_ctx *c)
 {
     if (!c) return GALA_OK;
+    if (c->side.stream) (void)hipStreamSynchronize(c->side.stream);
     if (c->stream || !c->allocs.empty()) (void)hipStreamSynchronize(c->stream);
+    for (hipEvent_t e : c->side.fork) if (e) (void)hipEventDestroy(e);
+    if (c->side.join) (void)hipEventDestroy(c->side.join);
+    if (c->side.stream) (void)hipStreamDestroy(c->side.stream);
     for (void *p : c->allocs) (void)hipFree(p);
     for (hipEvent_t e : c->timer.ev) (void)hipEventDestroy(e);
     delete c;
@@ -285,7 +297,7 @@ static int enqueue_gradients(gala_ctx *c, const uint8_t *obs_u8, const int32_t *
     HIP_OK(c, launch_forward(a, c->stream, pt));
     HIP_OK(c, launch_loss(a, c->hp, actions, rewards, dones, c->stream));
     pt->mark("returns_loss");
-    HIP_OK(c, launch_backward(a, c->stream, pt));
+    HIP_OK(c, launch_backward(a, c->stream, pt, &c->side));
     if (own_norm) {
         HIP_OK(c, launch_grad_norm(c->N, c->L, c->hp, c->b.g, c->b.norm_part, c->b.stats, c->stream));
         pt->mark("grad_norm");

@@ -139,7 +139,13 @@ hipError_t launch_loss(const NetArgs &a, const HParams &hp, const int32_t *actio
                        const uint8_t *dones, hipStream_t s);
 hipError_t launch_sample(int N, int Bn, int A, const float *logits, const float *values, uint64_t seed, long step,
                          int32_t *actions, float *values_out, float *logp_out, hipStream_t s);
-hipError_t launch_backward(const NetArgs &a, hipStream_t s, PhaseTimer *pt);
+// Second stream (default priority) and the events that order it against the context's stream.
+struct SideStream {
+    hipStream_t stream = nullptr;
+    hipEvent_t fork[4] = {nullptr, nullptr, nullptr, nullptr};
+    hipEvent_t join = nullptr;
+};
+hipError_t launch_backward(const NetArgs &a, hipStream_t s, PhaseTimer *pt, const SideStream *side);
 size_t workspace_floats(int N, int M, int F);
 
 hipError_t launch_grad_norm(int N, const Layout &L, const HParams &hp, const float *g, const float *norm_part,

@@ -761,14 +761,29 @@ hipError_t launch_forward(const NetArgs &a, hipStream_t s, PhaseTimer *pt)
     return hipGetLastError();
 }
 
-hipError_t launch_backward(const NetArgs &a, hipStream_t s, PhaseTimer *pt)
+// The data-gradient chain heads -> fc -> conv3 -> conv2 is sequential; a layer's weight
+// gradient needs only that layer's output gradient.  With a side stream the weight-gradient
+// kernels run next to the chain, so that the partly filled last round of workgroups of one
+// kernel overlaps work of the other; the same kernels run in both modes, results are identical.
+hipError_t launch_backward(const NetArgs &a, hipStream_t s, PhaseTimer *pt, const SideStream *side)
 {
     const Layout &L = a.L;
+    const bool fork = side && side->stream && !pt->on;     // per-phase timing needs one stream
+    hipStream_t w = fork ? side->stream : s;                // where weight gradients go
+    int n_ev = 0;
+    // everything enqueued on `s` so far is visible to later work on `w`
+    auto publish = [&]() -> hipError_t {
+        if (!fork) return hipSuccess;
+        hipEvent_t e = side->fork[n_ev++];
+        GALA_TRY(hipEventRecord(e, s));
+        return hipStreamWaitEvent(w, e, 0);
+    };
     hipLaunchKernelGGL(heads_dgrad_kernel, dim3(a.M, a.N), dim3(256), 0, s, a.b.h, a.x, L, a.M, a.F,
                        a.b.dlogits, a.b.dvalues, a.b.dzh);
     GALA_TRY(hipGetLastError());
     pt->mark("heads_dgrad");
-    hipLaunchKernelGGL(heads_wgrad_kernel, dim3(L.n_actions + 1, a.N, FC / 256), dim3(256), 0, s, a.b.h, L, a.M, a.F,
+    GALA_TRY(publish());
+    hipLaunchKernelGGL(heads_wgrad_kernel, dim3(L.n_actions + 1, a.N, FC / 256), dim3(256), 0, w, a.b.h, L, a.M, a.F,
                        a.b.dlogits, a.b.dvalues, a.b.g);
     GALA_TRY(hipGetLastError());
     pt->mark("heads_wgrad");
@@ -777,7 +792,7 @@ hipError_t launch_backward(const NetArgs &a, hipStream_t s, PhaseTimer *pt)
         p.dzh = a.b.dzh; p.a3 = a.b.a3; p.g = a.b.g; p.d_pad = L.d_pad; p.w_off = L.fcw; p.b_off = L.fcb;
         p.norm_part = a.b.norm_part; p.M = a.M; p.F = a.F;
         p.tiles_m = FC / FcWgrad::BM; p.tiles_n = cdiv(FLAT, FcWgrad::BN); p.splits = 1;
-        GALA_TRY(igemm_launch(p, a.N, s, a.bf16));
+        GALA_TRY(igemm_launch(p, a.N, w, a.bf16));
         pt->mark("fc_wgrad");
     }
     {
@@ -788,14 +803,15 @@ hipError_t launch_backward(const NetArgs &a, hipStream_t s, PhaseTimer *pt)
         GALA_TRY(igemm_launch(p, a.N, s, a.bf16));
         pt->mark("fc_dgrad");
     }
+    GALA_TRY(publish());
     // conv3
     {
         Conv3Wgrad p{};
         p.in = a.b.a2; p.dz = a.b.dz3; p.ws = a.b.ws; p.M = a.M; p.F = a.F; p.fps = FPS_CONV3;
         p.tiles_m = cdiv(KW3, Conv3Wgrad::BM); p.tiles_n = 1; p.splits = cdiv(a.M, FPS_CONV3);
-        GALA_TRY(igemm_launch(p, a.N, s, a.bf16));
+        GALA_TRY(igemm_launch(p, a.N, w, a.bf16));
         pt->mark("conv3_wgrad");
-        GALA_TRY(reduce_splits(a.b.ws, p.splits, Conv3Wgrad::PART, a.N, a.b.g + L.w3, L.d_pad, nullptr, 0, 1, s));
+        GALA_TRY(reduce_splits(a.b.ws, p.splits, Conv3Wgrad::PART, a.N, a.b.g + L.w3, L.d_pad, nullptr, 0, 1, w));
         pt->mark("conv3_wgrad_reduce");
     }
     {
@@ -806,14 +822,15 @@ hipError_t launch_backward(const NetArgs &a, hipStream_t s, PhaseTimer *pt)
         GALA_TRY(igemm_launch(p, a.N, s, a.bf16));
         pt->mark("conv3_dgrad");
     }
+    GALA_TRY(publish());
     // conv2
     {
         Conv2Wgrad p{};
         p.in = a.b.a1; p.dz = a.b.dz2; p.ws = a.b.ws; p.M = a.M; p.F = a.F; p.fps = FPS_CONV2;
         p.tiles_m = cdiv(KW2, Conv2Wgrad::BM); p.tiles_n = 1; p.splits = cdiv(a.M, FPS_CONV2);
-        GALA_TRY(igemm_launch(p, a.N, s, a.bf16));
+        GALA_TRY(igemm_launch(p, a.N, w, a.bf16));
         pt->mark("conv2_wgrad");
-        GALA_TRY(reduce_splits(a.b.ws, p.splits, Conv2Wgrad::PART, a.N, a.b.g + L.w2, L.d_pad, nullptr, 0, 1, s));
+        GALA_TRY(reduce_splits(a.b.ws, p.splits, Conv2Wgrad::PART, a.N, a.b.g + L.w2, L.d_pad, nullptr, 0, 1, w));
         pt->mark("conv2_wgrad_reduce");
     }
     {
@@ -824,15 +841,20 @@ hipError_t launch_backward(const NetArgs &a, hipStream_t s, PhaseTimer *pt)
         GALA_TRY(igemm_launch(p, a.N, s, a.bf16));
         pt->mark("conv2_dgrad");
     }
+    GALA_TRY(publish());
     // conv1 (the input needs no gradient)
     {
         Conv1Wgrad p{};
         p.obs = a.obs; p.dz1 = a.b.dz1; p.ws = a.b.ws; p.M = a.M; p.fps = FPS_CONV1;
         p.tiles_m = 1; p.tiles_n = 1; p.splits = cdiv(a.M, FPS_CONV1);
-        GALA_TRY(igemm_launch(p, a.N, s, a.bf16));
+        GALA_TRY(igemm_launch(p, a.N, w, a.bf16));
         pt->mark("conv1_wgrad");
-        GALA_TRY(reduce_splits(a.b.ws, p.splits, Conv1Wgrad::PART, a.N, a.b.g + L.w1, L.d_pad, nullptr, 0, 1, s));
+        GALA_TRY(reduce_splits(a.b.ws, p.splits, Conv1Wgrad::PART, a.N, a.b.g + L.w1, L.d_pad, nullptr, 0, 1, w));
         pt->mark("conv1_wgrad_reduce");
+    }
+    if (fork) {                                             // the gradient is complete once both streams are
+        GALA_TRY(hipEventRecord(side->join, w));
+        GALA_TRY(hipStreamWaitEvent(s, side->join, 0));
     }
     return hipSuccess;
 }

@@ -20,6 +20,10 @@
 //   int tiles_m, tiles_n, splits            filled by the host
 //   void bind(int agent, int split)         per-agent pointers and the split's k-range
 //   int  k_begin(), k_end()
+//   void bind_tile(int m0, int n0)          optional per-tile set-up after bind (uniform)
+//   int  n_ktiles(int bk), ktile_k0(i, bk)  the k-tiles this workgroup visits, in order: by default
+//                                           every BK-th k from k_begin(); a functor may leave out tiles
+//                                           that are zero for all rows of the workgroup's tile
 //   typedef ARaw, BRaw                      what one global load of a group returns (float4, or a
 //                                           uint32_t of four bytes)
 //   typedef CtxA, CtxB                      per-thread, per-group state prepared once before the
@@ -155,6 +159,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void i
     const int split = tile;
     p.bind(agent, split);
     const int m0 = tm * BM, n0 = tn * BN;
+    p.bind_tile(m0, n0);
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -179,7 +184,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void i
     for (int i = 0; i < PB; ++i) sum_b[i][0] = sum_b[i][1] = sum_b[i][2] = sum_b[i][3] = 0.f;
     const bool do_sum_a = P::SUM_A && tn == 0, do_sum_b = P::SUM_B && tm == 0;
 
-    const int kb = p.k_begin(), ke = p.k_end();
 
     // Group g of an operand read "4 consecutive m (n)" -> (local k, quad index).  When a k-row
     // holds at least 256/BK quads, 256/BK consecutive threads share one k and a thread keeps
@@ -308,9 +312,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void i
             for (int v = 0; v < NV; ++v) acc[i][j][v] = 0.f;
 
     const int lr = lane % MB, lk = lane / MB;
-    const int nkt = (ke - kb + BK - 1) / BK;
+    const int nkt = p.n_ktiles(BK);
     if (nkt > 0) {
-        fetch(kb);
+        fetch(p.ktile_k0(0, BK));
         stage(std::integral_constant<int, 0>{});
     }
     __syncthreads();
@@ -319,7 +323,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void i
     // unrolled by two) so that every LDS address is a per-lane base plus an immediate.
     auto tile_step = [&](auto bufc, int kt) {
         constexpr int buf = decltype(bufc)::value;
-        if (kt + 1 < nkt) fetch(kb + (kt + 1) * BK);
+        if (kt + 1 < nkt) fetch(p.ktile_k0(kt + 1, BK));
         // keep the global loads of the next tile ahead of this tile's MFMAs: without the fence
         // the scheduler sinks them next to their first use and their latency is exposed
         __builtin_amdgcn_sched_barrier(0);

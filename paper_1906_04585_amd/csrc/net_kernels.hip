@@ -65,6 +65,9 @@ struct ProblemBase {
     int k0, k1;
     __device__ int k_begin() const { return k0; }
     __device__ int k_end() const { return k1; }
+    __device__ void bind_tile(int, int) {}
+    __device__ int n_ktiles(int bk) const { return (k1 - k0 + bk - 1) / bk; }
+    __device__ int ktile_k0(int i, int bk) const { return k0 + i * bk; }
     __device__ void decode_a(float (&r)[4], float4 v, bool) const { unpack(r, v); }
     __device__ void decode_b(float (&r)[4], float4 v, bool) const { unpack(r, v); }
     __device__ float4 col_value4(int) const { return make_float4(0.f, 0.f, 0.f, 0.f); }
@@ -300,21 +303,29 @@ struct FcWgrad : ProblemBase {
 struct TapCtx { unsigned off; unsigned mask; };
 
 // ---- conv3: gradient to a2 (stride 1: full correlation with the flipped kernel) -----------------
-// m = (f, iy, ix), n = c, k = (kh, kw, o); a tile of 16 consecutive k lies inside one tap.  Taps
-// that fall outside the 7x7 output are read from the zero page in front of dz3.
+// m = (iy, ix, f), n = c, k = (kh, kw, o); a tile of 16 consecutive k lies inside one tap.
+// Rows are ordered position-major so that a workgroup's rows share one or two input positions:
+// the taps that fall outside the 7x7 output for all of them (40 % of all taps on average) are
+// left out of its k-loop; a tap that is outside for only some rows is read from the zero page
+// in front of dz3 for those rows.  (Sorting the positions by their tap sets would leave out
+// another 7 %, but the table look-ups it needs in the epilogue cost more than that: measured.)
+// Row -> (position, frame) divides by the runtime frame count with a multiply-high by
+// mdiv = 2^32 / M + 1, exact for rows below 2^32 / M (M = 1 needs no division).
 struct Conv3Dgrad : ProblemBase {
-    static constexpr int BM = 128, BN = 64, BK = 16, WM = 2, WN = 2;
+    static constexpr int BM = GALA_MFMA16 ? 160 : 128, BN = 64, BK = 16, WM = 2, WN = 2;
     static constexpr bool A_KC = true, B_KC = true;
     static constexpr bool HAS_AUX = true;
+    static constexpr int TILES_PER_TAP = C3 / BK;
     typedef TapCtx CtxA;
     const float *dz3, *x, *a2;      // dz3 points at the data; ZERO_PAGE zeros precede the allocation's data
     float *dz2;
     long d_pad, w_off;
     int M, F;
+    unsigned mdiv;                  // 2^32 / M + 1
     const float *zp_, *w_, *act_;
     float *out_;
     int rows_;
-    unsigned abase_;
+    unsigned abase_, taps_;         // taps_: taps that are inside for at least one row of the tile
     __device__ void bind(int agent, int)
     {
         zp_ = dz3 - ZERO_PAGE;
@@ -325,17 +336,35 @@ struct Conv3Dgrad : ProblemBase {
         rows_ = M * P2;
         k0 = 0; k1 = K3 * K3 * C3;
     }
-    __device__ void prep_a(CtxA &c, int m, int kl) const
+    static __device__ unsigned tap_mask(int pos)
     {
-        const int f = m / P2, p = m % P2, iy = p / W2, ix = p % W2;
-        c.off = abase_ + (unsigned)((((f * H3 + iy) * W3 + ix) * C3 + kl) * 4);
+        const int iy = pos / W2, ix = pos % W2;
         unsigned mask = 0;
 #pragma unroll
         for (int t = 0; t < K3 * K3; ++t) {
             const int oy = iy - t / K3, ox = ix - t % K3;
             if (oy >= 0 && oy < H3 && ox >= 0 && ox < W3) mask |= 1u << t;
         }
-        c.mask = m < rows_ ? mask : 0u;
+        return mask;
+    }
+    __device__ void bind_tile(int m0, int)
+    {
+        const int last = min(m0 + BM, rows_) - 1;
+        taps_ = 0;
+        for (int pos = m0 / M; pos <= last / M; ++pos) taps_ |= tap_mask(pos);
+    }
+    __device__ int n_ktiles(int) const { return __popc(taps_) * TILES_PER_TAP; }
+    __device__ int ktile_k0(int i, int) const
+    {
+        unsigned rest = taps_;
+        for (int s = i / TILES_PER_TAP; s > 0; --s) rest &= rest - 1;        // drop the lowest set bits
+        return (__ffs(rest) - 1) * C3 + (i % TILES_PER_TAP) * BK;
+    }
+    __device__ void prep_a(CtxA &c, int m, int kl) const
+    {
+        const int pos = (M == 1 ? m : (int)__umulhi((unsigned)m, mdiv)), f = m - pos * M, iy = pos / W2, ix = pos % W2;
+        c.off = abase_ + (unsigned)((((f * H3 + iy) * W3 + ix) * C3 + kl) * 4);
+        c.mask = m < rows_ ? tap_mask(pos) : 0u;
     }
     __device__ float4 fetch_a(CtxA &c, int kt0, bool &) const
     {
@@ -350,13 +379,19 @@ struct Conv3Dgrad : ProblemBase {
         return ldg4b(w_ + t * (C2 * C3) + o0, c.off);
     }
     __device__ bool tile_full(int m0, int) const { return m0 + BM <= rows_; }
+    // row (position, frame) -> element offset of its channel vector in a [frame][position][C2] tensor
+    __device__ unsigned row_off(int m) const
+    {
+        const int pos = (M == 1 ? m : (int)__umulhi((unsigned)m, mdiv)), f = m - pos * M;
+        return (unsigned)((f * P2 + pos) * C2);
+    }
     template <bool CHECK> __device__ float4 aux4(int m, int n) const
     {
-        return ldg4b(act_, (!CHECK || m < rows_) ? (unsigned)((m * C2 + n) * 4) : 0u);
+        return ldg4b(act_, (!CHECK || m < rows_) ? (row_off(m < rows_ ? m : 0) + (unsigned)n) * 4u : 0u);
     }
     template <bool CHECK> __device__ void store4(int m, int n, float4 v, float4, float4 act) const
     {
-        if (!CHECK || m < rows_) st4(out_ + (long)m * C2 + n, relu_mask4(v, act));
+        if (!CHECK || m < rows_) st4(out_ + row_off(m) + n, relu_mask4(v, act));
     }
 };
 
@@ -817,7 +852,7 @@ hipError_t launch_backward(const NetArgs &a, hipStream_t s, PhaseTimer *pt, cons
     {
         Conv3Dgrad p{};
         p.dz3 = a.b.dz3; p.x = a.x; p.a2 = a.b.a2; p.dz2 = a.b.dz2; p.d_pad = L.d_pad; p.w_off = L.w3;
-        p.M = a.M; p.F = a.F;
+        p.M = a.M; p.F = a.F; p.mdiv = (unsigned)((1ull << 32) / (unsigned)a.M + 1ull);
         p.tiles_m = cdiv((long)a.M * P2, Conv3Dgrad::BM); p.tiles_n = 1; p.splits = 1;
         GALA_TRY(igemm_launch(p, a.N, s, a.bf16));
         pt->mark("conv3_dgrad");

@@ -92,10 +92,12 @@ struct Buffers {
     float *weight;                    // [phases][N][max_in+1]
 };
 
-// Per-agent partial sums of squared gradients written by the hidden layer's weight-gradient
-// kernel, one per output tile (the first FC_WGRAD_TILES entries of a row are used).
-constexpr int NORM_PARTS = 128;
+// Per-agent partial sums of squared gradients written by the kernels that produce the gradient:
+// one per output tile of the hidden layer's weight gradient, then one per workgroup of the
+// convolutions' split reductions.  NORM_USED of the NORM_PARTS entries of a row are in use.
+constexpr int NORM_PARTS = 256;
 constexpr int FC_WGRAD_TILES = 100;
+constexpr int NORM_USED = 179;
 // Activation and gradient buffers (a1, a2, a3, h, dz1..dz3, dzh) are allocated with this many
 // zero floats in front of the data.  Kernels that must treat a group as zero (a padding tap
 // of a transposed convolution, the tail of a k-range) read it from there instead of masking.

@@ -150,30 +150,25 @@ hipError_t launch_sample(int N, int Bn, int A, const float *logits, const float 
 }
 
 // ---- global gradient norm per agent and clip factor (Table 2: clip global gradient norm) ----------
-// The hidden layer's weight gradient (95 % of the parameters) arrives as per-tile sums of
-// squares from the kernel that produced it; this kernel adds the squares of everything in
-// front of and behind that tensor and turns the total into
-//   c = min(1, max_norm / (||g|| + 1e-6)).
-// One workgroup per agent, fixed summation order.
-constexpr int NORM_THREADS = 1024;
+// The convolution and hidden-layer weight gradients (with their biases, 99 % of the parameters)
+// arrive as partial sums of squares from the kernels that produced them; this kernel adds the
+// squares of the tensors behind them in the slice (hidden-layer bias, both heads) and turns the total
+// into  c = min(1, max_norm / (||g|| + 1e-6)).  One workgroup per agent, fixed summation order.
+constexpr int NORM_THREADS = 256;
 
-__global__ __launch_bounds__(NORM_THREADS) void grad_norm_kernel(const float *__restrict__ g, long d_pad, long fcw_begin,
-                                                                 long fcw_end, const float *__restrict__ part,
-                                                                 float max_norm, float *stats)
+__global__ __launch_bounds__(NORM_THREADS) void grad_norm_kernel(const float *__restrict__ g, long d_pad, long tail_begin,
+                                                                 const float *__restrict__ part, float max_norm,
+                                                                 float *stats)
 {
     __shared__ float red[NORM_THREADS / 64];
     const int agent = blockIdx.x;
     const float4 *p = reinterpret_cast<const float4 *>(g + agent * d_pad);
     float acc = 0.f;
-    for (long i = threadIdx.x; i < fcw_begin / 4; i += NORM_THREADS) {
+    for (long i = tail_begin / 4 + threadIdx.x; i < d_pad / 4; i += NORM_THREADS) {
         const float4 v = p[i];
         acc += (v.x * v.x + v.y * v.y) + (v.z * v.z + v.w * v.w);
     }
-    for (long i = fcw_end / 4 + threadIdx.x; i < d_pad / 4; i += NORM_THREADS) {
-        const float4 v = p[i];
-        acc += (v.x * v.x + v.y * v.y) + (v.z * v.z + v.w * v.w);
-    }
-    if (threadIdx.x < FC_WGRAD_TILES) acc += part[agent * NORM_PARTS + threadIdx.x];
+    if (threadIdx.x < NORM_USED) acc += part[agent * NORM_PARTS + threadIdx.x];
     acc = wave_sum(acc);
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = acc;
     __syncthreads();
@@ -220,8 +215,9 @@ __global__ __launch_bounds__(256) void rmsprop_kernel(float *x, float *v, const 
 hipError_t launch_grad_norm(int N, const Layout &L, const HParams &hp, const float *g, const float *norm_part,
                             float *stats, hipStream_t s)
 {
-    // the hidden layer's weights occupy [fcw, fcb) of a slice; every tensor starts on a multiple of 64 floats
-    hipLaunchKernelGGL(grad_norm_kernel, dim3(N), dim3(NORM_THREADS), 0, s, g, L.d_pad, L.fcw, L.fcb, norm_part,
+    // everything from the hidden layer's bias on is summed here; every tensor starts on a multiple of 64 floats
+    static_assert(NORM_USED <= NORM_THREADS, "one partial per thread");
+    hipLaunchKernelGGL(grad_norm_kernel, dim3(N), dim3(NORM_THREADS), 0, s, g, L.d_pad, L.fcb, norm_part,
                        hp.max_grad_norm, stats);
     return hipGetLastError();
 }

@@ -603,33 +603,39 @@ struct Conv1Wgrad : ProblemBase {
 };
 
 // ---- sum of split-K partials ----------------------------------------------------------------------
-// out[agent][i] = sum_s part[agent][s][i]  (+ bias[i % bias_n], ReLU when bias != nullptr)
-__global__ void reduce_splits_kernel(const float *__restrict__ part, int S, long len, float *out,
-                                     long out_stride, const float *bias, long bias_stride, int bias_n)
+// out[agent][i] = sum_s part[agent][s][i].  Every workgroup also leaves the sum of squares of what
+// it wrote in ssq[agent * NORM_PARTS + ssq_slot + blockIdx.x]: its share of the gradient norm.
+__global__ __launch_bounds__(256) void reduce_splits_kernel(const float *__restrict__ part, int S, long len, float *out,
+                                                            long out_stride, float *ssq, int ssq_slot)
 {
+    __shared__ float red[4];
     const int agent = blockIdx.y;
-    const long i = ((long)blockIdx.x * blockDim.x + threadIdx.x) * 4;
-    if (i >= len) return;
-    const float *p = part + (long)agent * S * len + i;
-    float4 acc = *reinterpret_cast<const float4 *>(p);
-    for (int s = 1; s < S; ++s) {
-        const float4 t = *reinterpret_cast<const float4 *>(p + (long)s * len);
-        acc.x += t.x; acc.y += t.y; acc.z += t.z; acc.w += t.w;
+    const long i = ((long)blockIdx.x * 256 + threadIdx.x) * 4;
+    float sq = 0.f;
+    if (i < len) {
+        const float *p = part + (long)agent * S * len + i;
+        float4 acc = *reinterpret_cast<const float4 *>(p);
+        for (int s = 1; s < S; ++s) {
+            const float4 t = *reinterpret_cast<const float4 *>(p + (long)s * len);
+            acc.x += t.x; acc.y += t.y; acc.z += t.z; acc.w += t.w;
+        }
+        *reinterpret_cast<float4 *>(out + agent * out_stride + i) = acc;
+        sq = (acc.x * acc.x + acc.y * acc.y) + (acc.z * acc.z + acc.w * acc.w);
     }
-    if (bias) {
-        const float *b = bias + agent * bias_stride + (i % bias_n);
-        acc.x = fmaxf(acc.x + b[0], 0.f); acc.y = fmaxf(acc.y + b[1], 0.f);
-        acc.z = fmaxf(acc.z + b[2], 0.f); acc.w = fmaxf(acc.w + b[3], 0.f);
-    }
-    *reinterpret_cast<float4 *>(out + agent * out_stride + i) = acc;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) sq += __shfl_xor(sq, off, 64);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = sq;
+    __syncthreads();
+    if (threadIdx.x == 0) ssq[agent * NORM_PARTS + ssq_slot + blockIdx.x] = (red[0] + red[1]) + (red[2] + red[3]);
 }
 
+static constexpr int reduce_blocks(long len) { return (int)((len / 4 + 255) / 256); }
+
 static hipError_t reduce_splits(const float *part, int S, long len, int N, float *out, long out_stride,
-                                const float *bias, long bias_stride, int bias_n, hipStream_t s)
+                                float *ssq, int ssq_slot, hipStream_t s)
 {
-    const int blocks = (int)((len / 4 + 255) / 256);
-    hipLaunchKernelGGL(reduce_splits_kernel, dim3(blocks, N), dim3(256), 0, s, part, S, len, out,
-                       out_stride, bias, bias_stride, bias_n);
+    hipLaunchKernelGGL(reduce_splits_kernel, dim3(reduce_blocks(len), N), dim3(256), 0, s, part, S, len, out,
+                       out_stride, ssq, ssq_slot);
     return hipGetLastError();
 }
 
@@ -675,20 +681,43 @@ __global__ __launch_bounds__(128) void fc_reduce_heads_kernel(const float *__res
     }
 }
 
+constexpr int HEAD_FRAMES = 8;
+
 // dzh[f][j] = (sum_a W_pi[a][j] dlogits[f][a] + w_v[j] dvalue[f]) * (h[f][j] > 0)
+// One workgroup per (HEAD_FRAMES frames, agent): a thread owns two columns j, reads each head
+// weight once and applies it to all eight frames, whose output gradients sit in LDS.
 __global__ __launch_bounds__(256) void heads_dgrad_kernel(const float *__restrict__ h, const float *__restrict__ x,
                                                           Layout L, int M, int F, const float *__restrict__ dlogits,
                                                           const float *__restrict__ dvalues, float *dzh)
 {
-    const int f = blockIdx.x, agent = blockIdx.y;
+    __shared__ float dl[HEAD_FRAMES][65];                 // [frame][action], value gradient in the last used slot
+    const int f0 = blockIdx.x * HEAD_FRAMES, agent = blockIdx.y, t = threadIdx.x;
     const float *xa = x + agent * L.d_pad;
     const int A = L.n_actions;
-    const float *dl = dlogits + ((long)agent * M + f) * A;
-    const float dv = dvalues[(long)agent * M + f];
-    for (int j = threadIdx.x; j < FC; j += blockDim.x) {
-        float acc = xa[L.vw + j] * dv;
-        for (int a = 0; a < A; ++a) acc += xa[L.piw + (long)a * FC + j] * dl[a];
-        dzh[((long)agent * M + f) * FC + j] = h[((long)agent * F + f) * FC + j] > 0.f ? acc : 0.f;
+    for (int e = t; e < HEAD_FRAMES * (A + 1); e += 256) {
+        const int fi = e / (A + 1), a = e % (A + 1), f = f0 + fi;
+        float v = 0.f;
+        if (f < M) v = a < A ? dlogits[((long)agent * M + f) * A + a] : dvalues[(long)agent * M + f];
+        dl[fi][a] = v;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int jj = 0; jj < FC / 256; ++jj) {
+        const int j = t + jj * 256;
+        float acc[HEAD_FRAMES];
+        const float wv = xa[L.vw + j];
+#pragma unroll
+        for (int fi = 0; fi < HEAD_FRAMES; ++fi) acc[fi] = wv * dl[fi][A];
+        for (int a = 0; a < A; ++a) {
+            const float w = xa[L.piw + (long)a * FC + j];
+#pragma unroll
+            for (int fi = 0; fi < HEAD_FRAMES; ++fi) acc[fi] += w * dl[fi][a];
+        }
+#pragma unroll
+        for (int fi = 0; fi < HEAD_FRAMES; ++fi) {
+            const int f = f0 + fi;
+            if (f < M) dzh[((long)agent * M + f) * FC + j] = h[((long)agent * F + f) * FC + j] > 0.f ? acc[fi] : 0.f;
+        }
     }
 }
 
@@ -748,6 +777,13 @@ size_t workspace_floats(int N, int M, int F)
     mx((size_t)N * cdiv(M, FPS_CONV3) * Conv3Wgrad::PART);
     return need + 1024;
 }
+
+// Slots of a row of gradient-norm partials: the hidden layer's tiles, then the workgroups of the
+// three convolution weight-gradient reductions.
+constexpr int SSQ_CONV1 = FC_WGRAD_TILES;
+constexpr int SSQ_CONV2 = SSQ_CONV1 + reduce_blocks(Conv1Wgrad::PART);
+constexpr int SSQ_CONV3 = SSQ_CONV2 + reduce_blocks(Conv2Wgrad::PART);
+static_assert(SSQ_CONV3 + reduce_blocks(Conv3Wgrad::PART) == NORM_USED, "gradient-norm partial slots");
 
 #define GALA_TRY(expr) do { hipError_t e_ = (expr); if (e_ != hipSuccess) return e_; } while (0)
 
@@ -813,8 +849,8 @@ hipError_t launch_backward(const NetArgs &a, hipStream_t s, PhaseTimer *pt, cons
         GALA_TRY(hipEventRecord(e, s));
         return hipStreamWaitEvent(w, e, 0);
     };
-    hipLaunchKernelGGL(heads_dgrad_kernel, dim3(a.M, a.N), dim3(256), 0, s, a.b.h, a.x, L, a.M, a.F,
-                       a.b.dlogits, a.b.dvalues, a.b.dzh);
+    hipLaunchKernelGGL(heads_dgrad_kernel, dim3(cdiv(a.M, HEAD_FRAMES), a.N), dim3(256), 0, s, a.b.h, a.x, L, a.M,
+                       a.F, a.b.dlogits, a.b.dvalues, a.b.dzh);
     GALA_TRY(hipGetLastError());
     pt->mark("heads_dgrad");
     GALA_TRY(publish());
@@ -846,7 +882,7 @@ hipError_t launch_backward(const NetArgs &a, hipStream_t s, PhaseTimer *pt, cons
         p.tiles_m = cdiv(KW3, Conv3Wgrad::BM); p.tiles_n = 1; p.splits = cdiv(a.M, FPS_CONV3);
         GALA_TRY(igemm_launch(p, a.N, w, a.bf16));
         pt->mark("conv3_wgrad");
-        GALA_TRY(reduce_splits(a.b.ws, p.splits, Conv3Wgrad::PART, a.N, a.b.g + L.w3, L.d_pad, nullptr, 0, 1, w));
+        GALA_TRY(reduce_splits(a.b.ws, p.splits, Conv3Wgrad::PART, a.N, a.b.g + L.w3, L.d_pad, a.b.norm_part, SSQ_CONV3, w));
         pt->mark("conv3_wgrad_reduce");
     }
     {
@@ -865,7 +901,7 @@ hipError_t launch_backward(const NetArgs &a, hipStream_t s, PhaseTimer *pt, cons
         p.tiles_m = cdiv(KW2, Conv2Wgrad::BM); p.tiles_n = 1; p.splits = cdiv(a.M, FPS_CONV2);
         GALA_TRY(igemm_launch(p, a.N, w, a.bf16));
         pt->mark("conv2_wgrad");
-        GALA_TRY(reduce_splits(a.b.ws, p.splits, Conv2Wgrad::PART, a.N, a.b.g + L.w2, L.d_pad, nullptr, 0, 1, w));
+        GALA_TRY(reduce_splits(a.b.ws, p.splits, Conv2Wgrad::PART, a.N, a.b.g + L.w2, L.d_pad, a.b.norm_part, SSQ_CONV2, w));
         pt->mark("conv2_wgrad_reduce");
     }
     {
@@ -884,7 +920,7 @@ hipError_t launch_backward(const NetArgs &a, hipStream_t s, PhaseTimer *pt, cons
         p.tiles_m = 1; p.tiles_n = 1; p.splits = cdiv(a.M, FPS_CONV1);
         GALA_TRY(igemm_launch(p, a.N, w, a.bf16));
         pt->mark("conv1_wgrad");
-        GALA_TRY(reduce_splits(a.b.ws, p.splits, Conv1Wgrad::PART, a.N, a.b.g + L.w1, L.d_pad, nullptr, 0, 1, w));
+        GALA_TRY(reduce_splits(a.b.ws, p.splits, Conv1Wgrad::PART, a.N, a.b.g + L.w1, L.d_pad, a.b.norm_part, SSQ_CONV1, w));
         pt->mark("conv1_wgrad_reduce");
     }
     if (fork) {                                             // the gradient is complete once both streams are

@@ -91,6 +91,8 @@ def main() -> int:
     ap.add_argument("--mode", choices=["fused", "split", "a2c_allreduce"], default="fused",
                     help="one gala_round call per step, or gala_learner_step + gala_gossip; a2c_allreduce times "
                          "the synchronous comparator (gradients averaged over agents, no gossip) instead")
+    ap.add_argument("--extras", choices=["on", "off"], default="on",
+                    help="off: skip the acting and diagnostics measurements (profiling runs of the headline path)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-rounds", type=int, default=20)
     args = ap.parse_args()
@@ -195,43 +197,45 @@ def main() -> int:
                               frac_hbm=round(hbm_bytes / (hbm_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)),
         other_ms=round(sum(acc.values()) - mfma_ms - hbm_ms, 4))
 
-    # acting step of Algorithm 1 (policy forward + categorical draw for every agent's B simulators);
-    # reported beside the learner-side metric, not part of `value`
-    act_out = torch.empty((N, B), dtype=torch.int32, device="cuda")
-    val_out = torch.empty((N, B), dtype=torch.float32, device="cuda")
-    for s_ in range(10):
-        gpu.act(pool[0]["boot_obs"], 1, s_, act_out, val_out)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    n_act = 200
-    for s_ in range(n_act):
-        gpu.act(pool[s_ % len(pool)]["boot_obs"], 1, 10 + s_, act_out, val_out)
-    torch.cuda.synchronize()
-    act_s = (time.perf_counter() - t0) / n_act
-    acting = dict(call="gala_act", us_per_call=round(act_s * 1e6, 1), frames_per_call=N * B,
-                  frames_per_s=round(N * B / act_s, 1),
-                  round_with_acting_ms=round(ms_per_step + T * act_s * 1e3, 4),
-                  note=f"a full actor-learner round = {T} acting steps + 1 learner/gossip step")
+    acting = diagnostics = None
+    if args.extras == "on":
+        # acting step of Algorithm 1 (policy forward + categorical draw for every agent's B simulators);
+        # reported beside the learner-side metric, not part of `value`
+        act_out = torch.empty((N, B), dtype=torch.int32, device="cuda")
+        val_out = torch.empty((N, B), dtype=torch.float32, device="cuda")
+        for s_ in range(10):
+            gpu.act(pool[0]["boot_obs"], 1, s_, act_out, val_out)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        n_act = 200
+        for s_ in range(n_act):
+            gpu.act(pool[s_ % len(pool)]["boot_obs"], 1, 10 + s_, act_out, val_out)
+        torch.cuda.synchronize()
+        act_s = (time.perf_counter() - t0) / n_act
+        acting = dict(call="gala_act", us_per_call=round(act_s * 1e6, 1), frames_per_call=N * B,
+                      frames_per_s=round(N * B / act_s, 1),
+                      round_with_acting_ms=round(ms_per_step + T * act_s * 1e3, 4),
+                      note=f"a full actor-learner round = {T} acting steps + 1 learner/gossip step")
 
-    # diagnostics of Sec. 5 (gradient cosine matrix, update norm, consensus distance): event-timed per call
-    gpu.set_profiling(True)
-    dacc: dict[str, float] = {}
-    n_diag = 10
-    for _ in range(n_diag):
-        one_round(rnd)
-        rnd += 1
-        gpu.grad_cosine()
-        gpu.update_norm()
-        gpu.consensus_distance()
-        for k, v in gpu.get_phase_times().items():
-            if k in ("grad_cosine", "update_norm", "consensus_distance"):
-                dacc[k] = dacc.get(k, 0.0) + v / n_diag
-    gpu.set_profiling(False)
-    # algorithmic bytes: every gradient (parameter) read once; update norm reads g and v
-    diag_bytes = {"grad_cosine": 4.0 * gpu.d * N, "update_norm": 8.0 * gpu.d * N, "consensus_distance": 4.0 * gpu.d * N}
-    diagnostics = {k: dict(ms=round(ms, 5), bound="hbm", achieved=round(diag_bytes[k] / (ms * 1e-3) / 1e9, 1),
-                           unit="GB/s", frac=round(diag_bytes[k] / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4))
-                   for k, ms in dacc.items()}
+        # diagnostics of Sec. 5 (gradient cosine matrix, update norm, consensus distance): event-timed per call
+        gpu.set_profiling(True)
+        dacc: dict[str, float] = {}
+        n_diag = 10
+        for _ in range(n_diag):
+            one_round(rnd)
+            rnd += 1
+            gpu.grad_cosine()
+            gpu.update_norm()
+            gpu.consensus_distance()
+            for k, v in gpu.get_phase_times().items():
+                if k in ("grad_cosine", "update_norm", "consensus_distance"):
+                    dacc[k] = dacc.get(k, 0.0) + v / n_diag
+        gpu.set_profiling(False)
+        # algorithmic bytes: every gradient (parameter) read once; update norm reads g and v
+        diag_bytes = {"grad_cosine": 4.0 * gpu.d * N, "update_norm": 8.0 * gpu.d * N, "consensus_distance": 4.0 * gpu.d * N}
+        diagnostics = {k: dict(ms=round(ms, 5), bound="hbm", achieved=round(diag_bytes[k] / (ms * 1e-3) / 1e9, 1),
+                               unit="GB/s", frac=round(diag_bytes[k] / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4))
+                       for k, ms in dacc.items()}
 
     cpu_baseline = None
     if not args.no_cpu_baseline:

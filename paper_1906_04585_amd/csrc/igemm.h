@@ -110,13 +110,33 @@ static __device__ __forceinline__ unsigned gala_pack_bf16(float lo, float hi)
     return *reinterpret_cast<unsigned *>(&b);
 }
 
-// BF16 = true: the same tiling with operands rounded to bf16 when they are staged into LDS
-// (fp32 in HBM, fp32 accumulation): LDS tiles become [row][k] with k contiguous, one lane
-// reads its four consecutive k as 8 bytes, and each 16x16 block takes one
-// v_mfma_f32_16x16x16_bf16 per 16 k.
-template <class P, bool BF16>
+// fp32 value -> three bf16 values whose sum is the value to 24 significant bits (each piece is
+// the round-to-nearest bf16 of what the previous pieces left over; the leftovers are exact).
+static __device__ __forceinline__ void gala_split3_bf16(float v, unsigned short &hi, unsigned short &mid,
+                                                        unsigned short &lo)
+{
+    const unsigned h = gala_pack_bf16(v, 0.f) & 0xffffu;
+    const float r1 = v - __uint_as_float(h << 16);
+    const unsigned m = gala_pack_bf16(r1, 0.f) & 0xffffu;
+    const float r2 = r1 - __uint_as_float(m << 16);
+    hi = (unsigned short)h; mid = (unsigned short)m; lo = (unsigned short)(gala_pack_bf16(r2, 0.f) & 0xffffu);
+}
+
+// MODE 0: fp32 MFMA as described above.
+// MODE 1: the same tiling with operands rounded to bf16 when they are staged into LDS (fp32 in
+//   HBM, fp32 accumulation): LDS tiles become [row][k] with k contiguous, one lane reads its four
+//   consecutive k as 8 bytes, and each 16x16 block takes one v_mfma_f32_16x16x16_bf16 per 16 k.
+// MODE 2: for problems whose A operand is exactly representable in bf16 (P::A_EXACT_BF16: byte
+//   images, integers 0..255 have eight significant bits).  A is staged as in MODE 1 without any
+//   rounding error, B is staged as three bf16 pieces that add up to the fp32 value, and each
+//   block takes three bf16 MFMAs per 16 k.  Every product is exact in fp32 and the accumulation
+//   is fp32, so the result is as accurate as the fp32 MFMA path at a fraction of its matrix time.
+template <class P, int MODE>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void igemm_kernel(P p, int n_agents)
 {
+    constexpr bool BF16 = MODE != 0;
+    constexpr int NB = MODE == 2 ? 3 : 1;       // bf16 pieces of the B operand
+    static_assert(MODE != 2 || P::A_EXACT_BF16, "three-piece mode needs an A operand that bf16 holds exactly");
     constexpr int BM = P::BM, BN = P::BN, BK = P::BK;
     // LDS tiles are k-major with a row padding of 4 floats: the transposing stores (four
     // k-rows per lane group) and the operand reads both spread over the banks.  Measured
@@ -143,10 +163,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void i
     static_assert(!BF16 || (P::MFMA16 && BK % 16 == 0), "bf16 path: 16x16x16 blocks");
     constexpr int BKP = BK + 4;
     constexpr int OFFBH = 2 * BM * BKP;
-    static_assert(!BF16 || (2 * (BM + BN) * BKP * 2 <= LDS_FLOATS * 4), "bf16 tiles fit the allocation");
+    static_assert(!BF16 || (2 * (BM + NB * BN) * BKP * 2 <= LDS_FLOATS * 4), "bf16 tiles fit the allocation");
     unsigned short *hs = reinterpret_cast<unsigned short *>(smem);
     auto Ah = [&](int buf, int m, int k) -> unsigned short & { return hs[(buf * BM + m) * BKP + k]; };
-    auto Bh = [&](int buf, int n, int k) -> unsigned short & { return hs[OFFBH + (buf * BN + n) * BKP + k]; };
+    auto Bh = [&](int buf, int piece, int n, int k) -> unsigned short & {
+        return hs[OFFBH + ((buf * NB + piece) * BN + n) * BKP + k];
+    };
 
     const int bid = blockIdx.x;
     const int xcd = bid & 7, slot = bid >> 3;
@@ -276,17 +298,34 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void i
 #pragma unroll
                     for (int j = 0; j < 4; ++j) r[j] = okb[i] ? r[j] : 0.f;
                 }
-                if (BF16 && P::B_KC) {
+                if (MODE == 2) {
+                    unsigned short pc[3][4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) gala_split3_bf16(r[j], pc[0][j], pc[1][j], pc[2][j]);
+                    if (P::B_KC) {
+                        const int col = g / (BK / 4), kq = g % (BK / 4);
+#pragma unroll
+                        for (int q = 0; q < 3; ++q)
+                            *reinterpret_cast<uint2 *>(&Bh(buf, q, col, kq * 4)) =
+                                make_uint2(pc[q][0] | ((unsigned)pc[q][1] << 16), pc[q][2] | ((unsigned)pc[q][3] << 16));
+                    } else {
+                        int k, nq; map_mc(QB{}, i, k, nq);
+#pragma unroll
+                        for (int q = 0; q < 3; ++q)
+#pragma unroll
+                            for (int j = 0; j < 4; ++j) Bh(buf, q, nq * 4 + j, k) = pc[q][j];
+                    }
+                } else if (BF16 && P::B_KC) {
                     const int col = g / (BK / 4), kq = g % (BK / 4);
-                    *reinterpret_cast<uint2 *>(&Bh(buf, col, kq * 4)) =
+                    *reinterpret_cast<uint2 *>(&Bh(buf, 0, col, kq * 4)) =
                         make_uint2(gala_pack_bf16(r[0], r[1]), gala_pack_bf16(r[2], r[3]));
                 } else if (BF16) {
                     int k, nq; map_mc(QB{}, i, k, nq);
                     const unsigned p01 = gala_pack_bf16(r[0], r[1]), p23 = gala_pack_bf16(r[2], r[3]);
-                    Bh(buf, nq * 4 + 0, k) = (unsigned short)(p01 & 0xffffu);
-                    Bh(buf, nq * 4 + 1, k) = (unsigned short)(p01 >> 16);
-                    Bh(buf, nq * 4 + 2, k) = (unsigned short)(p23 & 0xffffu);
-                    Bh(buf, nq * 4 + 3, k) = (unsigned short)(p23 >> 16);
+                    Bh(buf, 0, nq * 4 + 0, k) = (unsigned short)(p01 & 0xffffu);
+                    Bh(buf, 0, nq * 4 + 1, k) = (unsigned short)(p01 >> 16);
+                    Bh(buf, 0, nq * 4 + 2, k) = (unsigned short)(p23 & 0xffffu);
+                    Bh(buf, 0, nq * 4 + 3, k) = (unsigned short)(p23 >> 16);
                 } else if (P::B_KC) {
                     const int col = g / (BK / 4), kq = g % (BK / 4);
 #pragma unroll
@@ -330,18 +369,23 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void i
         if constexpr (BF16) {
 #pragma unroll
             for (int kk = 0; kk < BK; kk += 16) {
-                gala_s16x4 a[BI], b[BJ];
+                gala_s16x4 a[BI], b[NB][BJ];
 #pragma unroll
                 for (int i = 0; i < BI; ++i)
                     a[i] = *reinterpret_cast<const gala_s16x4 *>(&Ah(buf, wm0 + i * MB + lr, kk + lk * 4));
 #pragma unroll
-                for (int j = 0; j < BJ; ++j)
-                    b[j] = *reinterpret_cast<const gala_s16x4 *>(&Bh(buf, wn0 + j * MB + lr, kk + lk * 4));
-#pragma unroll
-                for (int i = 0; i < BI; ++i)
+                for (int q = 0; q < NB; ++q)
 #pragma unroll
                     for (int j = 0; j < BJ; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a[i], b[j], acc[i][j], 0, 0, 0);
+                        b[q][j] = *reinterpret_cast<const gala_s16x4 *>(&Bh(buf, q, wn0 + j * MB + lr, kk + lk * 4));
+                // smallest pieces first
+#pragma unroll
+                for (int q = NB - 1; q >= 0; --q)
+#pragma unroll
+                    for (int i = 0; i < BI; ++i)
+#pragma unroll
+                        for (int j = 0; j < BJ; ++j)
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a[i], b[q][j], acc[i][j], 0, 0, 0);
             }
         } else {
 #pragma unroll
@@ -454,12 +498,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void i
     }
 }
 
+// bf16 = false asks for fp32 accuracy: the fp32 MFMA path, or the three-piece bf16 path for
+// problems whose A operand bf16 holds exactly (same accuracy, less matrix time).
 template <class P>
 static inline hipError_t igemm_launch(const P &p, int n_agents, hipStream_t stream, bool bf16 = false)
 {
     const int agents_pad = (n_agents + 7) / 8 * 8;
     const int grid = agents_pad * p.tiles_m * p.tiles_n * p.splits;
-    if (bf16) hipLaunchKernelGGL((igemm_kernel<P, true>), dim3(grid), dim3(256), 0, stream, p, n_agents);
-    else hipLaunchKernelGGL((igemm_kernel<P, false>), dim3(grid), dim3(256), 0, stream, p, n_agents);
+    if (bf16) hipLaunchKernelGGL((igemm_kernel<P, 1>), dim3(grid), dim3(256), 0, stream, p, n_agents);
+    else if constexpr (P::A_EXACT_BF16 && P::MFMA16)
+        hipLaunchKernelGGL((igemm_kernel<P, 2>), dim3(grid), dim3(256), 0, stream, p, n_agents);
+    else hipLaunchKernelGGL((igemm_kernel<P, 0>), dim3(grid), dim3(256), 0, stream, p, n_agents);
     return hipGetLastError();
 }

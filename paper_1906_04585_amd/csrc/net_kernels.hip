@@ -60,6 +60,7 @@ struct ProblemBase {
     typedef OffCtx CtxB;
     static constexpr bool SUM_A = false, SUM_B = false, HAS_AUX = false, A_ZERO = false, B_ZERO = false;
     static constexpr bool SUMSQ = false;
+    static constexpr bool A_EXACT_BF16 = false;   // true: every A value is an integer 0..255 (a byte image)
     static constexpr bool MFMA16 = GALA_MFMA16;
     int tiles_m, tiles_n, splits;
     int k0, k1;
@@ -84,6 +85,7 @@ struct ProblemBase {
 struct Conv1Fwd : ProblemBase {
     static constexpr int BM = 256, BN = 32, BK = 16, WM = 4, WN = 1;
     static constexpr bool A_KC = true, B_KC = false;
+    static constexpr bool A_EXACT_BF16 = true;
     typedef uint32_t ARaw;
     struct CtxA { const uint8_t *ptr; };
     const uint8_t *obs, *boot;
@@ -545,6 +547,7 @@ struct Conv1Wgrad : ProblemBase {
     static constexpr int BM = 256, BN = 32, BK = 16, WM = 4, WN = 1;
     static constexpr bool A_KC = false, B_KC = false;
     static constexpr bool SUM_B = true;
+    static constexpr bool A_EXACT_BF16 = true;
     static constexpr int PART = KW1 * C1 + C1;
     typedef uint32_t ARaw;
     typedef WalkCtx CtxA;

@@ -219,6 +219,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void i
     };
     typedef std::integral_constant<int, BM / 4> QA;
     typedef std::integral_constant<int, BN / 4> QB;
+    // bf16 tiles are [row][k]: an m-contiguous A operand would scatter single bf16 values.  Where
+    // possible a thread therefore takes PA consecutive k of one quad of rows, so that it owns a
+    // 4 x PA block and stores PA consecutive bf16 per row in one piece.
+    constexpr bool KCONS_A = BF16 && !P::A_KC && !P::SUM_A && GA % 256 == 0 && 256 % (BM / 4) == 0 &&
+                             (PA == 2 || PA == 4);
+    constexpr int KT_A = KCONS_A ? 256 / (BM / 4) : 1;          // threads that share a quad of rows
+    auto map_a = [&](int i, int &kl, int &q) {
+        if (KCONS_A) { kl = (tid % KT_A) * PA + i; q = tid / KT_A; }
+        else map_mc(QA{}, i, kl, q);
+    };
 
 #pragma unroll
     for (int i = 0; i < PA; ++i) {
@@ -226,7 +236,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void i
         oka[i] = true;
         if (GA % 256 == 0 || g < GA) {
             if (P::A_KC) p.prep_a(ca[i], m0 + g / (BK / 4), (g % (BK / 4)) * 4);
-            else { int kl, q; map_mc(QA{}, i, kl, q); p.prep_a(ca[i], m0 + q * 4, kl); }
+            else { int kl, q; map_a(i, kl, q); p.prep_a(ca[i], m0 + q * 4, kl); }
         }
     }
 #pragma unroll
@@ -253,10 +263,30 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void i
     };
     auto stage = [&](auto bufc) {
         constexpr int buf = decltype(bufc)::value;
+        if constexpr (KCONS_A) {
+            float rr[PA][4];
+#pragma unroll
+            for (int i = 0; i < PA; ++i) {
+                p.decode_a(rr[i], ra[i], oka[i]);
+                if (P::A_ZERO) {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) rr[i][j] = oka[i] ? rr[i][j] : 0.f;
+                }
+            }
+            int kl, q; map_a(0, kl, q);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (PA == 4)
+                    *reinterpret_cast<uint2 *>(&Ah(buf, q * 4 + j, kl)) =
+                        make_uint2(gala_pack_bf16(rr[0][j], rr[1][j]), gala_pack_bf16(rr[2 % PA][j], rr[3 % PA][j]));
+                else
+                    *reinterpret_cast<unsigned *>(&Ah(buf, q * 4 + j, kl)) = gala_pack_bf16(rr[0][j], rr[1][j]);
+            }
+        }
 #pragma unroll
         for (int i = 0; i < PA; ++i) {
             const int g = tid + i * 256;
-            if (GA % 256 == 0 || g < GA) {
+            if (!KCONS_A && (GA % 256 == 0 || g < GA)) {
                 float r[4];
                 p.decode_a(r, ra[i], oka[i]);
                 if (P::A_ZERO) {
@@ -268,7 +298,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void i
                     *reinterpret_cast<uint2 *>(&Ah(buf, row, kq * 4)) =
                         make_uint2(gala_pack_bf16(r[0], r[1]), gala_pack_bf16(r[2], r[3]));
                 } else if (BF16) {
-                    int k, mq; map_mc(QA{}, i, k, mq);
+                    int k, mq; map_a(i, k, mq);
                     const unsigned p01 = gala_pack_bf16(r[0], r[1]), p23 = gala_pack_bf16(r[2], r[3]);
                     Ah(buf, mq * 4 + 0, k) = (unsigned short)(p01 & 0xffffu);
                     Ah(buf, mq * 4 + 1, k) = (unsigned short)(p01 >> 16);
@@ -279,7 +309,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void i
 #pragma unroll
                     for (int j = 0; j < 4; ++j) As(buf, kq * 4 + j, row) = r[j];
                 } else {
-                    int k, mq; map_mc(QA{}, i, k, mq);
+                    int k, mq; map_a(i, k, mq);
                     *reinterpret_cast<float4 *>(&As(buf, k, mq * 4)) = make_float4(r[0], r[1], r[2], r[3]);
                 }
                 if (!P::A_KC && P::SUM_A && do_sum_a) {     // summed here, not at fetch, so the loads stay in flight

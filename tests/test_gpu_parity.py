@@ -338,3 +338,27 @@ def test_edge_shapes_one_round(N, T, B, A, topology, tweak):
     gpu.gossip(0)
     om.gossip(0)
     compare_params(gpu, om, net, "edge after gossip")
+
+
+def test_conv1_split_precision_is_fp32_level():
+    """The first convolution multiplies byte images (exact in bf16) with fp32 operands cut into
+    three bf16 pieces.  Its activations and its weight gradient must agree with the fp64 oracle as
+    closely as single-precision accumulation allows (1e-5 of the largest entry), far below what one
+    bf16 rounding (4e-3) would leave."""
+    cfg, net, gpu, om, X0 = _make(2)
+    N, T, B = cfg["n_agents"], cfg["T"], cfg["B"]
+    ro = gs.rollout(net, N, T, B, gs.round_seed(2, 77))
+    step_both(gpu, om, ro)
+    a1 = gpu.get_activations(1).transpose(0, 1, 4, 2, 3).reshape(N, T * B + B, -1)
+    off, shape = orc.act_offsets(net)["conv1"]
+    n = int(np.prod(shape))
+    sl = gs.segment_slices(net)
+    g = gpu.get_grads()
+    worst_a = worst_g = 0.0
+    for i in range(N):
+        obs = ro["obs"][i].reshape((T * B,) + ro["obs"].shape[3:])
+        _, _, acts = orc.forward_acts(net, X0[i].astype(np.float64), obs)
+        worst_a = max(worst_a, rel_err(a1[i, :T * B], acts[:, off:off + n]))
+        worst_g = max(worst_g, rel_err(g[i, sl["conv1.w"]], om.grads[i, sl["conv1.w"]]))
+    print(f"conv1 activation err {worst_a:.2e}, conv1.w gradient err {worst_g:.2e}")
+    assert worst_a <= 1e-5 and worst_g <= 1e-5

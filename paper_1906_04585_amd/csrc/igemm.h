@@ -57,6 +57,13 @@
 //                                           store_sum_b(n, v); needs the operand in "4 consecutive
 //                                           m (n)" mode.  Used for bias gradients, which are exactly
 //                                           these sums of an operand the weight-gradient GEMM reads.
+//   static constexpr int TABLE              optional: this many ints of LDS for the functor, filled by
+//                                           fill_table(int *tab, int tid) (all 256 threads, before the
+//                                           first fetch; a barrier follows) and read in fetch_a / fetch_b
+//   static constexpr bool BLOCK_FETCH_A     optional, used when a thread owns PA consecutive k of one
+//                                           quad of rows (bf16 tiles, m-contiguous A): one call
+//                                           fetch_a_block(ctx of the first group, k0, raw[PA], ok[PA])
+//                                           loads all of the thread's groups, group i at local k + i
 //   static constexpr bool SUMSQ             optional: the workgroup also delivers the sum of
 //                                           squares of what it stored, through
 //                                           template <bool CHECK> float sumsq4(m, n, v) (the share of
@@ -182,6 +189,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void i
     p.bind(agent, split);
     const int m0 = tm * BM, n0 = tn * BN;
     p.bind_tile(m0, n0);
+    __shared__ __attribute__((aligned(16))) int ftab[P::TABLE > 0 ? P::TABLE : 1];
+    if (P::TABLE > 0) {
+        p.fill_table(ftab, threadIdx.x);
+        __syncthreads();
+    }
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -250,10 +262,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void i
     }
 
     auto fetch = [&](int k0) {
+        if constexpr (KCONS_A && P::BLOCK_FETCH_A) p.fetch_a_block(ca[0], k0, ra, oka);
+        else {
 #pragma unroll
-        for (int i = 0; i < PA; ++i) {
-            const int g = tid + i * 256;
-            if (GA % 256 == 0 || g < GA) ra[i] = p.fetch_a(ca[i], k0, oka[i]);
+            for (int i = 0; i < PA; ++i) {
+                const int g = tid + i * 256;
+                if (GA % 256 == 0 || g < GA) ra[i] = p.fetch_a(ca[i], k0, oka[i]);
+            }
         }
 #pragma unroll
         for (int i = 0; i < PB; ++i) {

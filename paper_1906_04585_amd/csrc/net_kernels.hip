@@ -61,6 +61,9 @@ struct ProblemBase {
     static constexpr bool SUM_A = false, SUM_B = false, HAS_AUX = false, A_ZERO = false, B_ZERO = false;
     static constexpr bool SUMSQ = false;
     static constexpr bool A_EXACT_BF16 = false;   // true: every A value is an integer 0..255 (a byte image)
+    static constexpr int TABLE = 0;
+    static constexpr bool BLOCK_FETCH_A = false;
+    __device__ void fill_table(int *, int) {}
     static constexpr bool MFMA16 = GALA_MFMA16;
     int tiles_m, tiles_n, splits;
     int k0, k1;
@@ -484,6 +487,7 @@ struct ConvWgrad : ProblemBase {
     static constexpr int PART = MT * CO + CO;
     static constexpr int HW = HO * WO;
     static_assert(BK <= HW, "one wrap per tile at most");
+    static constexpr int TABLE = HW;  // output position -> byte offset of its window's corner in a frame
     typedef WalkCtx CtxA;
     struct CtxB { unsigned off; int k; };
     const float *in, *dz;           // both preceded by ZERO_PAGE zeros
@@ -491,7 +495,13 @@ struct ConvWgrad : ProblemBase {
     int M, F, fps;
     const float *zin_, *zdz_;
     float *out_;
+    const int *tab_;
     unsigned abase_, bbase_;
+    __device__ void fill_table(int *tab, int tid)
+    {
+        tab_ = tab;
+        for (int p = tid; p < HW; p += 256) tab[p] = (((p / WO) * ST) * WI + (p % WO) * ST) * CI * 4;
+    }
     __device__ void bind(int agent, int split)
     {
         zin_ = in - ZERO_PAGE;
@@ -512,8 +522,7 @@ struct ConvWgrad : ProblemBase {
     }
     __device__ float4 fetch_a(CtxA &c, int, bool &) const
     {
-        const int oy = c.p / WO, ox = c.p - oy * WO;
-        const unsigned off = c.moff + c.foff + (unsigned)(((oy * ST) * WI + ox * ST) * CI * 4);
+        const unsigned off = c.moff + c.foff + (unsigned)tab_[c.p];
         const float4 v = ldg4b(zin_, (c.k < k1 && c.moff != 0u) ? off : 0u);
         c.k += BK; c.p += BK;
         if (c.p >= HW) { c.p -= HW; c.foff += (unsigned)(HI * WI * CI * 4); }
@@ -549,6 +558,8 @@ struct Conv1Wgrad : ProblemBase {
     static constexpr bool SUM_B = true;
     static constexpr bool A_EXACT_BF16 = true;
     static constexpr int PART = KW1 * C1 + C1;
+    static constexpr int TABLE = P1;  // output position -> byte offset of its window's corner in a channel plane
+    static constexpr bool BLOCK_FETCH_A = true;
     typedef uint32_t ARaw;
     typedef WalkCtx CtxA;
     struct CtxB { unsigned off; int k; };
@@ -556,6 +567,7 @@ struct Conv1Wgrad : ProblemBase {
     const float *dz1;               // preceded by ZERO_PAGE zeros
     float *ws;
     int M, fps;
+    const int *tab_;
     const uint8_t *o_;
     const float *zdz_;
     float *out_;
@@ -576,14 +588,35 @@ struct Conv1Wgrad : ProblemBase {
         c.p = c.k % P1;
         c.foff = (unsigned)(c.k / P1) * (unsigned)FRAME;
     }
+    __device__ void fill_table(int *tab, int tid)
+    {
+        tab_ = tab;
+        for (int p = tid; p < P1; p += 256) tab[p] = ((p / W1) * S1) * W0 + (p % W1) * S1;
+    }
     __device__ uint32_t fetch_a(CtxA &c, int, bool &ok) const
     {
-        const int oy = c.p / W1, ox = c.p - oy * W1;
         ok = c.k < k1;
-        const uint32_t v = ldg_u32b(o_, ok ? c.moff + c.foff + (unsigned)((oy * S1) * W0 + ox * S1) : 0u);
+        const uint32_t v = ldg_u32b(o_, ok ? c.moff + c.foff + (unsigned)tab_[c.p] : 0u);
         c.k += BK; c.p += BK;
         if (c.p >= P1) { c.p -= P1; c.foff += (unsigned)FRAME; }
         return v;
+    }
+    // Four groups at consecutive k = four consecutive output positions starting at a multiple of
+    // four: they never straddle a frame (P1 and the k-range bounds are multiples of four), so one
+    // walk and one 16-byte table read serve all of them.
+    __device__ void fetch_a_block(CtxA &c, int, uint32_t (&raw)[4], bool (&ok)[4]) const
+    {
+        static_assert(P1 % 4 == 0 && BK % 4 == 0, "position quads");
+        const bool in = c.k < k1;
+        const int4 o = *reinterpret_cast<const int4 *>(tab_ + c.p);
+        const unsigned base = c.moff + c.foff;
+        raw[0] = ldg_u32b(o_, in ? base + (unsigned)o.x : 0u);
+        raw[1] = ldg_u32b(o_, in ? base + (unsigned)o.y : 0u);
+        raw[2] = ldg_u32b(o_, in ? base + (unsigned)o.z : 0u);
+        raw[3] = ldg_u32b(o_, in ? base + (unsigned)o.w : 0u);
+        ok[0] = ok[1] = ok[2] = ok[3] = in;
+        c.k += BK; c.p += BK;
+        if (c.p >= P1) { c.p -= P1; c.foff += (unsigned)FRAME; }
     }
     __device__ void decode_a(float (&r)[4], uint32_t w, bool ok) const { unpack_u8(r, ok ? w : 0u); }
     __device__ void prep_b(CtxB &c, int kl, int n) const

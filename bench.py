@@ -27,16 +27,24 @@ PEAK_MFMA_TFLOPS = {"f32": 157.3, "bf16": 2500.0}     # dense matrix-instruction
 PEAK_HBM_GBS = 8000.0
 
 # event-timed phase -> kernel name in the rocprofv3 summaries under profiles/
-KERNEL_OF_PHASE = {
-    "conv1_fwd": "igemm_kernel<Conv1Fwd>",
-    "conv2_fwd": "igemm_kernel<ConvFwd<32, 20, 20, 64, 9, 9, 4, 2> >",
-    "conv3_fwd": "igemm_kernel<ConvFwd<64, 9, 9, 64, 7, 7, 3, 1> >",
-    "fc_fwd": "igemm_kernel<FcFwd>", "fc_wgrad": "igemm_kernel<FcWgrad>", "fc_dgrad": "igemm_kernel<FcDgrad>",
-    "conv3_wgrad": "igemm_kernel<ConvWgrad<64, 9, 9, 64, 7, 7, 3, 1, 64> >", "conv3_dgrad": "igemm_kernel<Conv3Dgrad>",
-    "conv2_wgrad": "igemm_kernel<ConvWgrad<32, 20, 20, 64, 9, 9, 4, 2, 128> >", "conv2_dgrad": "igemm_kernel<Conv2Dgrad>",
-    "conv1_wgrad": "igemm_kernel<Conv1Wgrad>", "grad_norm": "sumsq_kernel", "clip_rmsprop": "rmsprop_kernel",
-    "gossip_mix": "mix_kernel", "gossip_publish": "copy_kernel", "clip_rmsprop_mix": "rmsprop_mix_kernel<64>",
-}
+def kernel_of_phase(dtype: str) -> dict:
+    """Event-timed phase -> kernel name as the rocprofv3 summaries under profiles/ print it.  The last
+    template argument is the MFMA mode: 0 = fp32, 1 = bf16 operands, 2 = byte operand exact in bf16 and
+    the fp32 operand as three bf16 pieces (the first convolution in an fp32 run)."""
+    m, m1 = ("0", "2") if dtype == "f32" else ("1", "1")
+    return {
+        "conv1_fwd": f"igemm_kernel<Conv1Fwd, {m1}>",
+        "conv2_fwd": f"igemm_kernel<ConvFwd<32, 20, 20, 64, 9, 9, 4, 2>, {m}>",
+        "conv3_fwd": f"igemm_kernel<ConvFwd<64, 9, 9, 64, 7, 7, 3, 1>, {m}>",
+        "fc_fwd": f"igemm_kernel<FcFwdT<96>, {m}>", "fc_wgrad": f"igemm_kernel<FcWgrad, {m}>",
+        "fc_dgrad": f"igemm_kernel<FcDgrad, {m}>",
+        "conv3_wgrad": f"igemm_kernel<ConvWgrad<64, 9, 9, 64, 7, 7, 3, 1, 64>, {m}>",
+        "conv3_dgrad": f"igemm_kernel<Conv3Dgrad, {m}>",
+        "conv2_wgrad": f"igemm_kernel<ConvWgrad<32, 20, 20, 64, 9, 9, 4, 2, 128>, {m}>",
+        "conv2_dgrad": f"igemm_kernel<Conv2Dgrad, {m}>", "conv1_wgrad": f"igemm_kernel<Conv1Wgrad, {m1}>",
+        "grad_norm": "grad_norm_kernel", "clip_rmsprop": "rmsprop_kernel", "gossip_mix": "mix_kernel",
+        "gossip_publish": "copy_kernel", "clip_rmsprop_mix": "rmsprop_mix_kernel<64>",
+    }
 
 
 def measured_traffic(phase: str, config: int, dtype: str):
@@ -58,16 +66,20 @@ def measured_traffic(phase: str, config: int, dtype: str):
         sha.update(open(fn, "rb").read())
     if sha.hexdigest() != rec["source_sha256"]:
         return None
-    k = rec["kernels"].get(KERNEL_OF_PHASE.get(phase, ""))
+    k = rec["kernels"].get(kernel_of_phase(dtype).get(phase, ""))
     return k["bytes"] if k else None
 
 
-def kernel_work(N: int, M: int, F: int, d: int, tau: int) -> dict:
-    """Algorithmic work of one launch of each kernel: ('mfma', flop) or ('hbm', bytes)."""
+def kernel_work(N: int, M: int, F: int, d: int, tau: int, dtype: str) -> dict:
+    """Algorithmic work of one launch of each kernel: ('mfma', flop), ('mfma3', flop) or ('hbm', bytes).
+    'mfma3': the first convolution in an fp32 run.  Its byte operand is exact in bf16 and its fp32
+    operand is cut into three bf16 pieces, so it executes three bf16 matrix instructions per
+    algorithmic one and is priced against the bf16 matrix peak with 3 x the algorithmic flops."""
     w = {}
     for layer, macs in MACS.items():
-        w[f"{layer}_fwd"] = ("mfma", 2.0 * macs * F * N)
-        w[f"{layer}_wgrad"] = ("mfma", 2.0 * macs * M * N)
+        kind = "mfma3" if (layer == "conv1" and dtype == "f32") else "mfma"
+        w[f"{layer}_fwd"] = (kind, 2.0 * macs * F * N)
+        w[f"{layer}_wgrad"] = (kind, 2.0 * macs * M * N)
         if layer != "conv1":                     # the input needs no gradient
             w[f"{layer}_dgrad"] = ("mfma", 2.0 * macs * M * N)
     # the gradient norm is assembled from partial sums the weight-gradient kernels emit: no pass over g
@@ -159,7 +171,7 @@ def main() -> int:
         for k, v in gpu.get_phase_times().items():
             acc[k] = acc.get(k, 0.0) + v / args.profile_rounds
     gpu.set_profiling(False)
-    work = kernel_work(N, M, F, gpu.d, cfg["max_delay"])
+    work = kernel_work(N, M, F, gpu.d, cfg["max_delay"], args.dtype)
     if args.mode == "a2c_allreduce":
         work["grad_mean_norm"] = ("hbm", 4.0 * gpu.d * N)      # read every agent's gradient once
         work["clip_rmsprop"] = ("hbm", 16.0 * gpu.d * N)       # read x, v; write x, v (the mean stays in cache)
@@ -171,6 +183,10 @@ def main() -> int:
             if kind == "mfma":
                 ent.update(bound="mfma", achieved=round(amount / (ms * 1e-3) / 1e12, 2), unit="TFLOP/s",
                            frac=round(amount / (ms * 1e-3) / 1e12 / peak_mfma, 4))
+            elif kind == "mfma3":
+                ent.update(bound="mfma", dtype="bf16 x3 (fp32-exact)", algorithmic_tflops=round(amount / (ms * 1e-3) / 1e12, 2),
+                           achieved=round(3 * amount / (ms * 1e-3) / 1e12, 2), unit="TFLOP/s",
+                           frac=round(3 * amount / (ms * 1e-3) / 1e12 / PEAK_MFMA_TFLOPS["bf16"], 4))
             else:
                 ent.update(bound="hbm", achieved=round(amount / (ms * 1e-3) / 1e9, 1), unit="GB/s",
                            frac=round(amount / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4))
@@ -178,9 +194,10 @@ def main() -> int:
     dominant = max((k for k in acc if k in work), key=lambda k: acc[k])
     kind, amount = work[dominant]
     dur = acc[dominant] * 1e-3
-    if kind == "mfma":
-        roofline = dict(kernel=dominant, bound="mfma", achieved=amount / dur / 1e12, peak=peak_mfma,
-                        unit="TFLOP/s", frac=amount / dur / 1e12 / peak_mfma,
+    if kind in ("mfma", "mfma3"):
+        mult, pk = (3.0, PEAK_MFMA_TFLOPS["bf16"]) if kind == "mfma3" else (1.0, peak_mfma)
+        roofline = dict(kernel=dominant, bound="mfma", achieved=mult * amount / dur / 1e12, peak=pk,
+                        unit="TFLOP/s", frac=mult * amount / dur / 1e12 / pk,
                         traffic=measured_traffic(dominant, args.config, args.dtype), avg_launch_ms=acc[dominant])
     else:
         roofline = dict(kernel=dominant, bound="hbm", achieved=amount / dur / 1e9, peak=PEAK_HBM_GBS,
@@ -188,6 +205,8 @@ def main() -> int:
                         traffic=measured_traffic(dominant, args.config, args.dtype), avg_launch_ms=acc[dominant])
     mfma_ms = sum(acc[k] for k in acc if k in work and work[k][0] == "mfma")
     mfma_flop = sum(work[k][1] for k in acc if k in work and work[k][0] == "mfma")
+    m3_ms = sum(acc[k] for k in acc if k in work and work[k][0] == "mfma3")
+    m3_flop = sum(work[k][1] for k in acc if k in work and work[k][0] == "mfma3")
     hbm_ms = sum(acc[k] for k in acc if k in work and work[k][0] == "hbm")
     hbm_bytes = sum(work[k][1] for k in acc if k in work and work[k][0] == "hbm")
     phase_summary = dict(
@@ -195,7 +214,12 @@ def main() -> int:
                      frac_mfma=round(mfma_flop / (mfma_ms * 1e-3) / 1e12 / peak_mfma, 4)),
         optimizer_gossip=dict(ms=round(hbm_ms, 4), gbs=round(hbm_bytes / (hbm_ms * 1e-3) / 1e9, 1),
                               frac_hbm=round(hbm_bytes / (hbm_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)),
-        other_ms=round(sum(acc.values()) - mfma_ms - hbm_ms, 4))
+        other_ms=round(sum(acc.values()) - mfma_ms - m3_ms - hbm_ms, 4))
+    if m3_ms > 0:
+        # the first convolution: algorithmic (fp32-equivalent) rate, and all conv/fc kernels together
+        phase_summary["conv1_bf16x3"] = dict(ms=round(m3_ms, 4), algorithmic_tflops=round(m3_flop / (m3_ms * 1e-3) / 1e12, 2))
+        phase_summary["conv_fc_all"] = dict(ms=round(mfma_ms + m3_ms, 4),
+                                            algorithmic_tflops=round((mfma_flop + m3_flop) / ((mfma_ms + m3_ms) * 1e-3) / 1e12, 2))
 
     acting = diagnostics = None
     if args.extras == "on":

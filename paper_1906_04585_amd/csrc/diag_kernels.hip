@@ -112,9 +112,17 @@ __global__ __launch_bounds__(256) void gram_reduce_kernel(const float *__restric
     const int tj = ti + rest;
     const int r = blockIdx.y, c = threadIdx.x % GRAM_T, q = threadIdx.x / GRAM_T;
     const float *p = part + (long)blockIdx.x * chunks * (GRAM_T * GRAM_T) + r * GRAM_T + c;
-    float acc = 0.f;
-    for (int k = q; k < chunks; k += 8) acc += p[(long)k * (GRAM_T * GRAM_T)];
-    red[q][c] = acc;
+    // four independent chains keep the loads of a thread in flight; combined in a fixed order
+    float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+    int k = q;
+    for (; k + 24 < chunks; k += 32) {
+        a0 += p[(long)k * (GRAM_T * GRAM_T)];
+        a1 += p[(long)(k + 8) * (GRAM_T * GRAM_T)];
+        a2 += p[(long)(k + 16) * (GRAM_T * GRAM_T)];
+        a3 += p[(long)(k + 24) * (GRAM_T * GRAM_T)];
+    }
+    for (; k < chunks; k += 8) a0 += p[(long)k * (GRAM_T * GRAM_T)];
+    red[q][c] = (a0 + a1) + (a2 + a3);
     __syncthreads();
     if (q == 0) {
         float t = 0.f;
@@ -141,7 +149,7 @@ int gram_tiles(int N) { return (N + GRAM_T - 1) / GRAM_T; }
 int gram_pairs(int N) { const int t = gram_tiles(N); return t * (t + 1) / 2; }
 int gram_chunks(int N)
 {
-    int c = 512 / gram_pairs(N);
+    int c = 256 / gram_pairs(N);
     return c < 1 ? 1 : c;
 }
 

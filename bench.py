@@ -218,8 +218,9 @@ def main() -> int:
     if m3_ms > 0:
         # the first convolution: algorithmic (fp32-equivalent) rate, and all conv/fc kernels together
         phase_summary["conv1_bf16x3"] = dict(ms=round(m3_ms, 4), algorithmic_tflops=round(m3_flop / (m3_ms * 1e-3) / 1e12, 2))
-        phase_summary["conv_fc_all"] = dict(ms=round(mfma_ms + m3_ms, 4),
-                                            algorithmic_tflops=round((mfma_flop + m3_flop) / ((mfma_ms + m3_ms) * 1e-3) / 1e12, 2))
+        all_tf = (mfma_flop + m3_flop) / ((mfma_ms + m3_ms) * 1e-3) / 1e12
+        phase_summary["conv_fc_all"] = dict(ms=round(mfma_ms + m3_ms, 4), algorithmic_tflops=round(all_tf, 2),
+                                            frac_of_fp32_mfma_peak=round(all_tf / PEAK_MFMA_TFLOPS["f32"], 4))
 
     acting = diagnostics = None
     if args.extras == "on":

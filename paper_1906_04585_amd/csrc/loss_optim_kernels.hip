@@ -27,6 +27,7 @@ static __device__ __forceinline__ float block_sum_256(float v, float *red)
 //   G_t = r_t + gamma (1 - done_t) G_{t+1},  G_T = V(state after the last action);  A_t = G_t - V_t
 //   loss = mean(-log pi(a_t|s_t) A_t) + c_v mean((G_t - V_t)^2) - eta mean(H_t),  G and A constants
 //   dloss/dz_k = [A (pi_k - 1[k = a]) + eta pi_k (log pi_k + H)] / M,   dloss/dV = -2 c_v (G - V) / M
+// (pi_a - 1 is formed as -sum_{k != a} pi_k)
 constexpr int MAX_ACTIONS = 64;
 constexpr int LOSS_THREADS = 1024;
 
@@ -66,19 +67,24 @@ __global__ __launch_bounds__(LOSS_THREADS) void loss_kernel(int T, int Bn, int A
         float zmax = z;
 #pragma unroll
         for (int off = 32; off > 0; off >>= 1) zmax = fmaxf(zmax, __shfl_xor(zmax, off, 64));
-        const float se = wave_sum(on ? expf(z - zmax) : 0.f);
-        const float lp = z - (zmax + logf(se));
+        // log-sum-exp as zmax + log1p(sum over the other actions): stays accurate when one action
+        // dominates (a nearly deterministic policy), where log(1 + tiny) would lose the tiny part
+        const int top = __ffsll(__ballot(on && z == zmax)) - 1;
+        const float others = wave_sum((on && lane != top) ? expf(z - zmax) : 0.f);
+        const float lp = z - (zmax + log1pf(others));
         const float p = on ? expf(lp) : 0.f;
         const float H = -wave_sum(on ? p * lp : 0.f);
         const int act = actions[(long)agent * M + m];      // integer gather of the taken action
         const float lp_act = __shfl(lp, act, 64);
+        // pi_a - 1 for the taken action as minus the sum of the other probabilities (no cancellation)
+        const float not_act = wave_sum((on && lane != act) ? p : 0.f);
         const float Am = Ad[m], Gm = G[m], Vm = V[m];
         pg += -lp_act * Am;
         td += (Gm - Vm) * (Gm - Vm);
         ent += H;
         if (on)
             dlogits[((long)agent * M + m) * A + lane] =
-                (Am * (p - (lane == act ? 1.f : 0.f)) + ent_coef * p * (lp + H)) * inv_m;
+                (Am * (lane == act ? -not_act : p) + ent_coef * p * (lp + H)) * inv_m;
         if (lane == 0) dvalues[(long)agent * M + m] = -2.f * vf_coef * (Gm - Vm) * inv_m;
     }
     if (lane == 0) { red[0][wave] = pg; red[1][wave] = td; red[2][wave] = ent; }

@@ -6,14 +6,14 @@ import pytest
 
 import gala_synth as gs
 from oracle import gala_oracle as orc
-from parity_util import RTOL, grad_scale, rel_err, relu_gates, upload
+from parity_util import RTOL, grad_scale, pg_scale, rel_err, relu_gates, upload
 
 pytestmark = pytest.mark.gpu
 
 HP = gs.HPARAMS
 
 
-def _compare(gpu, om, net, tag):
+def _compare(gpu, om, net, tag, ro=None, X_before=None):
     sl = gs.segment_slices(net)
     g = gpu.get_grads()
     gbar = gpu.get_mean_grad()
@@ -28,10 +28,14 @@ def _compare(gpu, om, net, tag):
             assert rel_err(v[i, s], om.V[i, s], grad_scale(om.V[i], sl, name)) <= 2 * RTOL, f"{tag} rmsprop {name} agent {i}"
         for k in range(5):
             ref = om.stats[i, k]
-            assert abs(st[i, k] - ref) <= RTOL * max(abs(ref), 1e-2 if k < 2 else 1e-30), f"{tag} stat {k} agent {i}"
+            scale = max(abs(ref), 1e-2 if k < 3 else 1e-30)
+            if k == 0 and ro is not None:
+                scale = max(scale, pg_scale(net, om.hp, X_before[i], ro, i))
+            assert abs(st[i, k] - ref) <= RTOL * scale, f"{tag} stat {k} agent {i}"
 
 
 def _both(gpu, om, net, ro):
+    """Returns the pre-step parameters."""
     X = gpu.get_params()
     om.set_params(X)
     om.set_opt_state(gpu.get_opt_state())
@@ -40,6 +44,7 @@ def _both(gpu, om, net, ro):
     gates, marked = relu_gates(gpu, net, X, ro)
     om.a2c_allreduce_step(ro["obs"], ro["actions"], ro["rewards"], ro["dones"], ro["boot_obs"],
                           gates=gates if marked else None)
+    return X
 
 
 @pytest.mark.parametrize("shared", [True, False])
@@ -55,8 +60,9 @@ def test_allreduce_lockstep_against_oracle(shared):
     om = orc.OracleGala(net, N, T, B, hp, "ring")
     gpu.set_params(gs.init_params(net, N, seed=91, shared=shared, bias_scale=0.05))
     for r in range(3):
-        _both(gpu, om, net, gs.rollout(net, N, T, B, gs.round_seed(2, 200 + r)))
-        _compare(gpu, om, net, f"shared={shared} update {r}")
+        ro = gs.rollout(net, N, T, B, gs.round_seed(2, 200 + r))
+        X = _both(gpu, om, net, ro)
+        _compare(gpu, om, net, f"shared={shared} update {r}", ro, X)
     if shared:
         x = gpu.get_params()
         for i in range(1, N):
@@ -106,5 +112,6 @@ def test_allreduce_full_size_32_agents():
     gpu = Gala(N, A, T, B, HP, cfg["topology"])
     om = orc.OracleGala(net, N, T, B, HP, cfg["topology"])
     gpu.set_params(gs.init_params(net, N, seed=93, shared=True, bias_scale=0.05))
-    _both(gpu, om, net, gs.rollout(net, N, T, B, gs.round_seed(4, 300)))
-    _compare(gpu, om, net, "32 agents")
+    ro = gs.rollout(net, N, T, B, gs.round_seed(4, 300))
+    X = _both(gpu, om, net, ro)
+    _compare(gpu, om, net, "32 agents", ro, X)

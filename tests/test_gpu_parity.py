@@ -8,7 +8,7 @@ import pytest
 
 import gala_synth as gs
 from oracle import gala_oracle as orc
-from parity_util import RTOL, compare_learner_step, compare_params, grad_scale, rel_err, step_both, upload
+from parity_util import RTOL, compare_learner_step, compare_params, grad_scale, pg_scale, rel_err, step_both, upload
 
 pytestmark = pytest.mark.gpu
 
@@ -160,8 +160,9 @@ def test_config2_lockstep_rounds():
         om.set_params(gpu.get_params())
         om.set_opt_state(gpu.get_opt_state())
         ro = gs.rollout(net, N, T, B, gs.round_seed(2, r))
+        X = om.X.copy()
         step_both(gpu, om, ro)
-        compare_learner_step(gpu, om, net, f"cfg2 round {r}")
+        compare_learner_step(gpu, om, net, f"cfg2 round {r}", ro=ro, X_before=X)
         om.set_params(gpu.get_params())
         gpu.gossip(r)
         om.gossip(r)
@@ -179,8 +180,9 @@ def test_config3_delayed_gossip_lockstep():
         om.set_params(gpu.get_params())
         om.set_opt_state(gpu.get_opt_state())
         ro = gs.rollout(net, N, T, B, gs.round_seed(3, r))
+        X = om.X.copy()
         step_both(gpu, om, ro)
-        compare_learner_step(gpu, om, net, f"cfg3 round {r}")
+        compare_learner_step(gpu, om, net, f"cfg3 round {r}", ro=ro, X_before=X)
         # the oracle's message history must hold what the GPU actually broadcast
         om.set_params(gpu.get_params())
         gpu.gossip(r)
@@ -217,7 +219,10 @@ def _sampled_full_size(cfg_id, sample_agents, rounds=1):
                 e = rel_err(g[i, s], og[s], grad_scale(og, sl, name))
                 assert e <= RTOL, f"cfg{cfg_id} round {r} grad {name} agent {i}: {e:.3e}"
             for k in range(3):
-                assert abs(st[i, k] - terms[k]) <= RTOL * max(abs(terms[k]), 1e-2)
+                scale = max(abs(terms[k]), 1e-2)
+                if k == 0:
+                    scale = max(scale, pg_scale(net, HP, X[i], ro, i))
+                assert abs(st[i, k] - terms[k]) <= RTOL * scale
             gc = og.copy()
             norm, scale = orc.clip_grad_norm(gc, HP["max_grad_norm"])
             assert abs(st[i, 3] - norm) <= RTOL * norm and abs(st[i, 4] - scale) <= RTOL * scale

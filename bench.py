@@ -27,24 +27,36 @@ PEAK_MFMA_TFLOPS = {"f32": 157.3, "bf16": 2500.0}     # dense matrix-instruction
 PEAK_HBM_GBS = 8000.0
 
 # event-timed phase -> kernel name in the rocprofv3 summaries under profiles/
+# phases whose kernels reach fp32 accuracy with bf16 matrix instructions on exact bf16 pieces of the
+# operands: pieces multiplied per algorithmic product
+SPLIT_PRODUCTS = {"conv1_fwd": 3, "conv1_wgrad": 3,
+                  "conv2_fwd": 6, "conv3_fwd": 6, "fc_fwd": 6, "fc_dgrad": 6, "conv3_dgrad": 6}
+
+
 def kernel_of_phase(dtype: str) -> dict:
     """Event-timed phase -> kernel name as the rocprofv3 summaries under profiles/ print it.  The last
     template argument is the MFMA mode: 0 = fp32, 1 = bf16 operands, 2 = byte operand exact in bf16 and
-    the fp32 operand as three bf16 pieces (the first convolution in an fp32 run)."""
-    m, m1 = ("0", "2") if dtype == "f32" else ("1", "1")
-    return {
-        "conv1_fwd": f"igemm_kernel<Conv1Fwd, {m1}>",
-        "conv2_fwd": f"igemm_kernel<ConvFwd<32, 20, 20, 64, 9, 9, 4, 2>, {m}>",
-        "conv3_fwd": f"igemm_kernel<ConvFwd<64, 9, 9, 64, 7, 7, 3, 1>, {m}>",
-        "fc_fwd": f"igemm_kernel<FcFwdT<96>, {m}>", "fc_wgrad": f"igemm_kernel<FcWgrad, {m}>",
-        "fc_dgrad": f"igemm_kernel<FcDgrad, {m}>",
-        "conv3_wgrad": f"igemm_kernel<ConvWgrad<64, 9, 9, 64, 7, 7, 3, 1, 64>, {m}>",
-        "conv3_dgrad": f"igemm_kernel<Conv3Dgrad, {m}>",
-        "conv2_wgrad": f"igemm_kernel<ConvWgrad<32, 20, 20, 64, 9, 9, 4, 2, 128>, {m}>",
-        "conv2_dgrad": f"igemm_kernel<Conv2Dgrad, {m}>", "conv1_wgrad": f"igemm_kernel<Conv1Wgrad, {m1}>",
-        "grad_norm": "grad_norm_kernel", "clip_rmsprop": "rmsprop_kernel", "gossip_mix": "mix_kernel",
-        "gossip_publish": "copy_kernel", "clip_rmsprop_mix": "rmsprop_mix_kernel<64>",
+    the fp32 operand as three bf16 pieces (the first convolution in an fp32 run), 3 = both operands as
+    three bf16 pieces, six piece products."""
+    def mode(phase):
+        if dtype != "f32":
+            return "1"
+        return {3: "2", 6: "3"}.get(SPLIT_PRODUCTS.get(phase, 0), "0")
+    names = {
+        "conv1_fwd": "Conv1Fwd", "conv2_fwd": "ConvFwd<32, 20, 20, 64, 9, 9, 4, 2>",
+        "conv3_fwd": "ConvFwd<64, 9, 9, 64, 7, 7, 3, 1>", "fc_fwd": "FcFwdT<96>", "fc_wgrad": "FcWgrad",
+        "fc_dgrad": "FcDgrad", "conv3_wgrad": "ConvWgrad<64, 9, 9, 64, 7, 7, 3, 1, 64>",
+        "conv3_dgrad": "Conv3Dgrad", "conv2_wgrad": "ConvWgrad<32, 20, 20, 64, 9, 9, 4, 2, 128>",
+        "conv2_dgrad": "Conv2Dgrad", "conv1_wgrad": "Conv1Wgrad",
     }
+    out = {ph: f"igemm_kernel<{nm}, {mode(ph)}>" for ph, nm in names.items()}
+    out.update({
+        "grad_norm": "grad_norm_kernel", "clip_rmsprop": "rmsprop_kernel", "gossip_mix": "mix_kernel",
+        # one in-peer per agent and no delays (the only workload with a committed traffic summary): the
+        # cycle-walking pass; with delays or several in-peers the same phase runs rmsprop_mix_kernel<..>
+        "gossip_publish": "copy_kernel", "clip_rmsprop_mix": "rmsprop_mix_cycle_kernel",
+    })
+    return out
 
 
 def measured_traffic(phase: str, config: int, dtype: str):
@@ -71,17 +83,18 @@ def measured_traffic(phase: str, config: int, dtype: str):
 
 
 def kernel_work(N: int, M: int, F: int, d: int, tau: int, dtype: str) -> dict:
-    """Algorithmic work of one launch of each kernel: ('mfma', flop), ('mfma3', flop) or ('hbm', bytes).
-    'mfma3': the first convolution in an fp32 run.  Its byte operand is exact in bf16 and its fp32
-    operand is cut into three bf16 pieces, so it executes three bf16 matrix instructions per
-    algorithmic one and is priced against the bf16 matrix peak with 3 x the algorithmic flops."""
+    """Algorithmic work of one launch of each kernel: ('mfma', flop), ('split', flop, n) or ('hbm', bytes).
+    'split': in an fp32 run these kernels cut their operands into exact bf16 pieces and execute n bf16
+    piece products per algorithmic product (3 where one operand is a byte image, which bf16 holds
+    exactly; 6 otherwise).  They are priced against the bf16 matrix peak with n x the algorithmic flops."""
     w = {}
     for layer, macs in MACS.items():
-        kind = "mfma3" if (layer == "conv1" and dtype == "f32") else "mfma"
-        w[f"{layer}_fwd"] = (kind, 2.0 * macs * F * N)
-        w[f"{layer}_wgrad"] = (kind, 2.0 * macs * M * N)
-        if layer != "conv1":                     # the input needs no gradient
-            w[f"{layer}_dgrad"] = ("mfma", 2.0 * macs * M * N)
+        for kind, frames in (("fwd", F), ("wgrad", M), ("dgrad", M)):
+            if layer == "conv1" and kind == "dgrad":         # the input needs no gradient
+                continue
+            ph = f"{layer}_{kind}"
+            flop = 2.0 * macs * frames * N
+            w[ph] = ("split", flop, SPLIT_PRODUCTS[ph]) if (dtype == "f32" and ph in SPLIT_PRODUCTS) else ("mfma", flop)
     # the gradient norm is assembled from partial sums the weight-gradient kernels emit: no pass over g
     w["clip_rmsprop"] = ("hbm", 20.0 * d * N)    # read g, x, v; write x, v
     w["gossip_mix"] = ("hbm", 12.0 * d * N)      # read x_i, x_j; write x_i
@@ -179,23 +192,25 @@ def main() -> int:
     for k, ms in acc.items():
         ent = {"ms": round(ms, 5)}
         if k in work:
-            kind, amount = work[k]
+            kind, amount = work[k][0], work[k][1]
             if kind == "mfma":
                 ent.update(bound="mfma", achieved=round(amount / (ms * 1e-3) / 1e12, 2), unit="TFLOP/s",
                            frac=round(amount / (ms * 1e-3) / 1e12 / peak_mfma, 4))
-            elif kind == "mfma3":
-                ent.update(bound="mfma", dtype="bf16 x3 (fp32-exact)", algorithmic_tflops=round(amount / (ms * 1e-3) / 1e12, 2),
-                           achieved=round(3 * amount / (ms * 1e-3) / 1e12, 2), unit="TFLOP/s",
-                           frac=round(3 * amount / (ms * 1e-3) / 1e12 / PEAK_MFMA_TFLOPS["bf16"], 4))
+            elif kind == "split":
+                n = work[k][2]
+                ent.update(bound="mfma", dtype=f"bf16 pieces, {n} products (fp32-exact)",
+                           algorithmic_tflops=round(amount / (ms * 1e-3) / 1e12, 2),
+                           achieved=round(n * amount / (ms * 1e-3) / 1e12, 2), unit="TFLOP/s",
+                           frac=round(n * amount / (ms * 1e-3) / 1e12 / PEAK_MFMA_TFLOPS["bf16"], 4))
             else:
                 ent.update(bound="hbm", achieved=round(amount / (ms * 1e-3) / 1e9, 1), unit="GB/s",
                            frac=round(amount / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4))
         kernels[k] = ent
     dominant = max((k for k in acc if k in work), key=lambda k: acc[k])
-    kind, amount = work[dominant]
+    kind, amount = work[dominant][0], work[dominant][1]
     dur = acc[dominant] * 1e-3
-    if kind in ("mfma", "mfma3"):
-        mult, pk = (3.0, PEAK_MFMA_TFLOPS["bf16"]) if kind == "mfma3" else (1.0, peak_mfma)
+    if kind in ("mfma", "split"):
+        mult, pk = (float(work[dominant][2]), PEAK_MFMA_TFLOPS["bf16"]) if kind == "split" else (1.0, peak_mfma)
         roofline = dict(kernel=dominant, bound="mfma", achieved=mult * amount / dur / 1e12, peak=pk,
                         unit="TFLOP/s", frac=mult * amount / dur / 1e12 / pk,
                         traffic=measured_traffic(dominant, args.config, args.dtype), avg_launch_ms=acc[dominant])
@@ -205,8 +220,9 @@ def main() -> int:
                         traffic=measured_traffic(dominant, args.config, args.dtype), avg_launch_ms=acc[dominant])
     mfma_ms = sum(acc[k] for k in acc if k in work and work[k][0] == "mfma")
     mfma_flop = sum(work[k][1] for k in acc if k in work and work[k][0] == "mfma")
-    m3_ms = sum(acc[k] for k in acc if k in work and work[k][0] == "mfma3")
-    m3_flop = sum(work[k][1] for k in acc if k in work and work[k][0] == "mfma3")
+    m3_ms = sum(acc[k] for k in acc if k in work and work[k][0] == "split")
+    m3_flop = sum(work[k][1] for k in acc if k in work and work[k][0] == "split")
+    m3_exec = sum(work[k][1] * work[k][2] for k in acc if k in work and work[k][0] == "split")
     hbm_ms = sum(acc[k] for k in acc if k in work and work[k][0] == "hbm")
     hbm_bytes = sum(work[k][1] for k in acc if k in work and work[k][0] == "hbm")
     phase_summary = dict(
@@ -216,8 +232,12 @@ def main() -> int:
                               frac_hbm=round(hbm_bytes / (hbm_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)),
         other_ms=round(sum(acc.values()) - mfma_ms - m3_ms - hbm_ms, 4))
     if m3_ms > 0:
-        # the first convolution: algorithmic (fp32-equivalent) rate, and all conv/fc kernels together
-        phase_summary["conv1_bf16x3"] = dict(ms=round(m3_ms, 4), algorithmic_tflops=round(m3_flop / (m3_ms * 1e-3) / 1e12, 2))
+        # kernels on bf16 pieces: algorithmic (fp32-equivalent) rate and the rate of the bf16 matrix work they
+        # execute; then all conv/fc kernels together
+        phase_summary["conv_fc_bf16_pieces"] = dict(
+            ms=round(m3_ms, 4), algorithmic_tflops=round(m3_flop / (m3_ms * 1e-3) / 1e12, 2),
+            executed_bf16_tflops=round(m3_exec / (m3_ms * 1e-3) / 1e12, 2),
+            frac_of_bf16_mfma_peak=round(m3_exec / (m3_ms * 1e-3) / 1e12 / PEAK_MFMA_TFLOPS["bf16"], 4))
         all_tf = (mfma_flop + m3_flop) / ((mfma_ms + m3_ms) * 1e-3) / 1e12
         phase_summary["conv_fc_all"] = dict(ms=round(mfma_ms + m3_ms, 4), algorithmic_tflops=round(all_tf, 2),
                                             frac_of_fp32_mfma_peak=round(all_tf / PEAK_MFMA_TFLOPS["f32"], 4))

@@ -23,6 +23,9 @@ struct gala_ctx {
     int topo_kind = 0, tau = 0, n_phases = 1, max_in = 1;
     std::vector<int32_t> h_peer, h_delay;
     std::vector<float> h_weight;
+    // one in-peer per agent, no delay, peers a permutation in every phase: its cycles, agent by agent
+    bool cycles_ok = false;
+    std::vector<int32_t> h_cyc_order, h_cyc_start, n_cycles;
     Buffers b{};
     int cur = 0;                 // which of b.x[] holds the current parameters
     float *canon = nullptr;      // [N][d] staging for get/set through host pointers
@@ -130,6 +133,28 @@ static int build_topology(gala_ctx *c, const gala_topology *t)
                     c->tau > 0 ? (int32_t)(splitmix64(t->delay_seed + edge) % (uint64_t)(c->tau + 1)) : 0;
             }
         }
+    // cycle decomposition of the peer permutation (used by the fused optimizer + mix pass)
+    c->cycles_ok = K == 1 && c->tau == 0;
+    c->h_cyc_order.assign((size_t)P * N, 0);
+    c->h_cyc_start.assign((size_t)P * (N + 1), 0);
+    c->n_cycles.assign(P, 0);
+    for (int ph = 0; ph < P && c->cycles_ok; ++ph) {
+        const int32_t *pr = &c->h_peer[(size_t)ph * N];
+        std::vector<char> hit(N, 0), seen(N, 0);
+        for (int i = 0; i < N; ++i) {
+            if (pr[i] < 0 || hit[pr[i]]) { c->cycles_ok = false; break; }
+            hit[pr[i]] = 1;
+        }
+        if (!c->cycles_ok) break;
+        int pos = 0, nc = 0;
+        for (int i = 0; i < N; ++i) {
+            if (seen[i]) continue;
+            c->h_cyc_start[(size_t)ph * (N + 1) + nc++] = pos;
+            for (int a = i; !seen[a]; a = pr[a]) { seen[a] = 1; c->h_cyc_order[(size_t)ph * N + pos++] = a; }
+        }
+        c->h_cyc_start[(size_t)ph * (N + 1) + nc] = pos;
+        c->n_cycles[ph] = nc;
+    }
     return GALA_OK;
 }
 
@@ -202,11 +227,14 @@ extern "C" int gala_create(gala_ctx **out, int n_agents, const gala_topology *to
     ALLOC(b.cons_part, N * ((dp + CONS_COLS - 1) / CONS_COLS) + 2, true);
     ALLOC(b.peer, c->h_peer.size(), false); ALLOC(b.delay, c->h_delay.size(), false);
     ALLOC(b.weight, c->h_weight.size(), false);
+    ALLOC(b.cyc_order, c->h_cyc_order.size(), false); ALLOC(b.cyc_start, c->h_cyc_start.size(), false);
     ALLOC(c->canon, N * c->L.d, false);
 #undef ALLOC
     he = hipMemcpyAsync(b.peer, c->h_peer.data(), c->h_peer.size() * 4, hipMemcpyHostToDevice, c->stream);
     if (he == hipSuccess) he = hipMemcpyAsync(b.delay, c->h_delay.data(), c->h_delay.size() * 4, hipMemcpyHostToDevice, c->stream);
     if (he == hipSuccess) he = hipMemcpyAsync(b.weight, c->h_weight.data(), c->h_weight.size() * 4, hipMemcpyHostToDevice, c->stream);
+    if (he == hipSuccess) he = hipMemcpyAsync(b.cyc_order, c->h_cyc_order.data(), c->h_cyc_order.size() * 4, hipMemcpyHostToDevice, c->stream);
+    if (he == hipSuccess) he = hipMemcpyAsync(b.cyc_start, c->h_cyc_start.data(), c->h_cyc_start.size() * 4, hipMemcpyHostToDevice, c->stream);
     if (he == hipSuccess) he = hipStreamSynchronize(c->stream);
     if (he != hipSuccess) { fail(c, GALA_EHIP, "table upload: %s", hipGetErrorString(he)); return bail(GALA_EHIP); }
     if (!getenv("GALA_SINGLE_STREAM")) {
@@ -368,13 +396,23 @@ extern "C" int gala_round(gala_ctx *c, const uint8_t *obs_u8, const int32_t *act
     if (!c) return GALA_EINVAL;
     int rc = check_round(c, round);
     if (rc != GALA_OK) return rc;
-    if (!fused_mix_available(c->N)) {
+    if (!c->cycles_ok && !fused_mix_available(c->N)) {
         rc = gala_learner_step(c, obs_u8, actions, rewards, dones, bootstrap_obs);
         return rc != GALA_OK ? rc : gala_gossip(c, round);
     }
     rc = enqueue_gradients(c, obs_u8, actions, rewards, dones, bootstrap_obs);
     if (rc != GALA_OK) return rc;
     const int phase = (int)(round % c->n_phases);
+    if (c->cycles_ok) {
+        HIP_OK(c, launch_rmsprop_mix_cycles(c->N, c->L, c->hp, c->b.x[c->cur], c->b.v, c->b.g,
+                                            c->b.cyc_order + (size_t)phase * c->N,
+                                            c->b.cyc_start + (size_t)phase * (c->N + 1), c->n_cycles[phase],
+                                            c->b.weight + (size_t)phase * c->N * 2, c->b.stats, c->stream));
+        c->timer.mark("clip_rmsprop_mix");
+        c->shared_gradient = false;
+        c->last_round = round;
+        return GALA_OK;
+    }
     HIP_OK(c, launch_rmsprop_mix(c->N, c->L, c->hp, c->b.x[c->cur], c->b.v, c->b.g, c->b.hist, c->tau, (long)round,
                                  phase, c->max_in, c->b.peer, c->b.delay, c->b.weight, c->b.stats, c->stream));
     c->timer.mark("clip_rmsprop_mix");

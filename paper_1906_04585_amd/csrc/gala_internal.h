@@ -89,6 +89,7 @@ struct Buffers {
     float *cons_part;                 // [N][CONS_CHUNKS] + 2 results
     float *row_ss;                    // [N] scratch of the norm reductions
     int32_t *peer, *delay;            // [phases][N][max_in]
+    int32_t *cyc_order, *cyc_start;   // [phases][N], [phases][N + 1]: the peer permutation's cycles (if it is one)
     float *weight;                    // [phases][N][max_in+1]
 };
 
@@ -158,6 +159,9 @@ int grad_mean_blocks(const Layout &L);
 hipError_t launch_grad_mean(int N, const Layout &L, const HParams &hp, const float *g, float *gbar, float *part,
                             float *stats, hipStream_t s);
 bool fused_mix_available(int N);
+hipError_t launch_rmsprop_mix_cycles(int N, const Layout &L, const HParams &hp, float *x, float *v, const float *g,
+                                     const int32_t *order, const int32_t *cstart, int n_cycles, const float *weight,
+                                     const float *stats, hipStream_t s);
 hipError_t launch_rmsprop_mix(int N, const Layout &L, const HParams &hp, float *x, float *v, const float *g,
                               float *hist, int tau, long round, int phase, int max_in, const int32_t *peer,
                               const int32_t *delay, const float *weight, const float *stats, hipStream_t s);

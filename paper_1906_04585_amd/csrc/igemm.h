@@ -1,5 +1,6 @@
-// Agent-grouped implicit-GEMM on the gfx950 matrix cores (fp32 MFMA in 32x32x2 or 16x16x4
-// blocks; optionally bf16 operands with fp32 accumulation).
+// Agent-grouped implicit-GEMM on the gfx950 matrix cores: fp32 MFMA in 32x32x2 or 16x16x4
+// blocks, bf16 operands with fp32 accumulation, or fp32 accuracy from bf16 MFMAs on exact bf16
+// pieces of the operands (see the MODE list above the kernel).
 //
 // One launch computes, for every agent, C[m][n] = sum_k A[m][k] * B[k][n] where A and
 // B are *views* described by a problem functor P (im2col of an activation tensor, a
@@ -109,6 +110,14 @@ typedef __bf16 gala_bf16x2 __attribute__((ext_vector_type(2)));
 typedef float gala_f32x2 __attribute__((ext_vector_type(2)));
 typedef short gala_s16x4 __attribute__((ext_vector_type(4)));
 
+typedef __bf16 gala_bf16x8 __attribute__((ext_vector_type(8)));
+static __device__ __forceinline__ gala_bf16x8 gala_cat(gala_s16x4 lo, gala_s16x4 hi)
+{
+    typedef short s16x8 __attribute__((ext_vector_type(8)));
+    const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(gala_bf16x8, v);
+}
+
 // two floats -> two bf16 (round to nearest even) packed in 32 bits
 static __device__ __forceinline__ unsigned gala_pack_bf16(float lo, float hi)
 {
@@ -117,16 +126,22 @@ static __device__ __forceinline__ unsigned gala_pack_bf16(float lo, float hi)
     return *reinterpret_cast<unsigned *>(&b);
 }
 
-// fp32 value -> three bf16 values whose sum is the value to 24 significant bits (each piece is
-// the round-to-nearest bf16 of what the previous pieces left over; the leftovers are exact).
-static __device__ __forceinline__ void gala_split3_bf16(float v, unsigned short &hi, unsigned short &mid,
-                                                        unsigned short &lo)
+// Four fp32 values -> NP bf16 pieces each, as packed pairs (values 0,1 in lo[], 2,3 in hi[]):
+// piece q is the round-to-nearest bf16 of what pieces 0..q-1 left over; the leftovers are exact,
+// and three pieces add up to the value to 24 significant bits.
+template <int NP>
+static __device__ __forceinline__ void gala_pieces4(const float (&r)[4], unsigned (&lo)[NP], unsigned (&hi)[NP])
 {
-    const unsigned h = gala_pack_bf16(v, 0.f) & 0xffffu;
-    const float r1 = v - __uint_as_float(h << 16);
-    const unsigned m = gala_pack_bf16(r1, 0.f) & 0xffffu;
-    const float r2 = r1 - __uint_as_float(m << 16);
-    hi = (unsigned short)h; mid = (unsigned short)m; lo = (unsigned short)(gala_pack_bf16(r2, 0.f) & 0xffffu);
+    float a0 = r[0], a1 = r[1], a2 = r[2], a3 = r[3];
+#pragma unroll
+    for (int q = 0; q < NP; ++q) {
+        lo[q] = gala_pack_bf16(a0, a1);
+        hi[q] = gala_pack_bf16(a2, a3);
+        if (q + 1 < NP) {
+            a0 -= __uint_as_float(lo[q] << 16); a1 -= __uint_as_float(lo[q] & 0xffff0000u);
+            a2 -= __uint_as_float(hi[q] << 16); a3 -= __uint_as_float(hi[q] & 0xffff0000u);
+        }
+    }
 }
 
 // MODE 0: fp32 MFMA as described above.
@@ -138,11 +153,17 @@ static __device__ __forceinline__ void gala_split3_bf16(float v, unsigned short 
 //   rounding error, B is staged as three bf16 pieces that add up to the fp32 value, and each
 //   block takes three bf16 MFMAs per 16 k.  Every product is exact in fp32 and the accumulation
 //   is fp32, so the result is as accurate as the fp32 MFMA path at a fraction of its matrix time.
+// MODE 3: both operands are staged as three bf16 pieces.  With a = a0 + a1 + a2 and b = b0 + b1 + b2
+//   the six products a_p b_q with p + q <= 2 carry the product to 2^-24 of |a||b| (the three
+//   left out are below fp32 rounding); each bf16 product is exact in fp32 and the accumulation is
+//   fp32, smallest pieces first.  Six bf16 MFMAs per 16 k take 3/8 of the matrix time of the four
+//   fp32 MFMAs they replace.
 template <class P, int MODE>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void igemm_kernel(P p, int n_agents)
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MODE == 3 ? 2 : 4))) void igemm_kernel(P p, int n_agents)
 {
     constexpr bool BF16 = MODE != 0;
-    constexpr int NB = MODE == 2 ? 3 : 1;       // bf16 pieces of the B operand
+    constexpr int NA = MODE == 3 ? 3 : 1;                       // bf16 pieces of the A operand
+    constexpr int NB = (MODE == 2 || MODE == 3) ? 3 : 1;        // bf16 pieces of the B operand
     static_assert(MODE != 2 || P::A_EXACT_BF16, "three-piece mode needs an A operand that bf16 holds exactly");
     constexpr int BM = P::BM, BN = P::BN, BK = P::BK;
     // LDS tiles are k-major with a row padding of 4 floats: the transposing stores (four
@@ -161,18 +182,21 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void i
     constexpr int OFFB = 2 * BK * SA;
     constexpr int SC = BN + 4;                  // row stride of the output slab
     constexpr int SLAB = P::WM * MB;            // rows per epilogue pass: one block-row per wavefront row
-    constexpr int LDS_LOOP = 2 * BK * (SA + SB), LDS_OUT = SLAB * SC;
+    constexpr int BKP = BK + 4;                 // bf16 tiles: row length in shorts
+    constexpr int LDS_F32 = 2 * BK * (SA + SB), LDS_BF16 = BF16 ? (2 * (NA * BM + NB * BN) * BKP + 1) / 2 : 0;
+    constexpr int LDS_LOOP = LDS_F32 > LDS_BF16 ? LDS_F32 : LDS_BF16, LDS_OUT = SLAB * SC;
     constexpr int LDS_FLOATS = LDS_LOOP > LDS_OUT ? LDS_LOOP : LDS_OUT;
     __shared__ __attribute__((aligned(16))) float smem[LDS_FLOATS];
     auto As = [&](int buf, int k, int c) -> float & { return smem[(buf * BK + k) * SA + c]; };
     auto Bs = [&](int buf, int k, int c) -> float & { return smem[OFFB + (buf * BK + k) * SB + c]; };
     // bf16 tiles: [buf][row][BK + 4] shorts (the padding keeps 8-byte alignment and spreads banks)
     static_assert(!BF16 || (P::MFMA16 && BK % 16 == 0), "bf16 path: 16x16x16 blocks");
-    constexpr int BKP = BK + 4;
-    constexpr int OFFBH = 2 * BM * BKP;
-    static_assert(!BF16 || (2 * (BM + NB * BN) * BKP * 2 <= LDS_FLOATS * 4), "bf16 tiles fit the allocation");
+    constexpr int OFFBH = 2 * NA * BM * BKP;
+    static_assert(!BF16 || (2 * (NA * BM + NB * BN) * BKP * 2 <= LDS_FLOATS * 4), "bf16 tiles fit the allocation");
     unsigned short *hs = reinterpret_cast<unsigned short *>(smem);
-    auto Ah = [&](int buf, int m, int k) -> unsigned short & { return hs[(buf * BM + m) * BKP + k]; };
+    auto Ah = [&](int buf, int piece, int m, int k) -> unsigned short & {
+        return hs[((buf * NA + piece) * BM + m) * BKP + k];
+    };
     auto Bh = [&](int buf, int piece, int n, int k) -> unsigned short & {
         return hs[OFFBH + ((buf * NB + piece) * BN + n) * BKP + k];
     };
@@ -224,11 +248,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void i
     // that k for all of its groups, so whatever the functor derives from k (a position walked
     // through frame, row, column) is computed once per thread and tile, not once per group.
     constexpr int TPK = 256 / BK;                   // threads per k-row in that arrangement
-    auto map_mc = [&](auto qc, int i, int &kl, int &q) {
+    // bf16 tiles are [row][k]: there the four rows of a group are written as single 16-bit
+    // values, and lanes that differ in the quad (rows four apart) would collide on a few LDS
+    // banks.  Operands without a running sum therefore let k run fastest over the lanes, so that
+    // sixteen lanes write one row's sixteen consecutive k.
+    auto map_mc = [&](auto qc, int i, int &kl, int &q, bool k_fastest = false) {
         constexpr int Q = decltype(qc)::value;      // quads per k-row
-        if (Q % TPK == 0) { kl = tid / TPK; q = tid % TPK + TPK * i; }
+        if (k_fastest) { const int g = tid + i * 256; kl = g % BK; q = g / BK; }
+        else if (Q % TPK == 0) { kl = tid / TPK; q = tid % TPK + TPK * i; }
         else { const int g = tid + i * 256; kl = g / Q; q = g % Q; }
     };
+    constexpr bool KFAST_A = BF16 && !P::SUM_A, KFAST_B = BF16 && !P::SUM_B;
     typedef std::integral_constant<int, BM / 4> QA;
     typedef std::integral_constant<int, BN / 4> QB;
     // bf16 tiles are [row][k]: an m-contiguous A operand would scatter single bf16 values.  Where
@@ -239,7 +269,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void i
     constexpr int KT_A = KCONS_A ? 256 / (BM / 4) : 1;          // threads that share a quad of rows
     auto map_a = [&](int i, int &kl, int &q) {
         if (KCONS_A) { kl = (tid % KT_A) * PA + i; q = tid / KT_A; }
-        else map_mc(QA{}, i, kl, q);
+        else map_mc(QA{}, i, kl, q, KFAST_A);
     };
 
 #pragma unroll
@@ -257,7 +287,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void i
         okb[i] = true;
         if (GB % 256 == 0 || g < GB) {
             if (P::B_KC) p.prep_b(cb[i], (g % (BK / 4)) * 4, n0 + g / (BK / 4));
-            else { int kl, q; map_mc(QB{}, i, kl, q); p.prep_b(cb[i], kl, n0 + q * 4); }
+            else { int kl, q; map_mc(QB{}, i, kl, q, KFAST_B); p.prep_b(cb[i], kl, n0 + q * 4); }
         }
     }
 
@@ -291,11 +321,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void i
             int kl, q; map_a(0, kl, q);
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                if (PA == 4)
-                    *reinterpret_cast<uint2 *>(&Ah(buf, q * 4 + j, kl)) =
-                        make_uint2(gala_pack_bf16(rr[0][j], rr[1][j]), gala_pack_bf16(rr[2 % PA][j], rr[3 % PA][j]));
-                else
-                    *reinterpret_cast<unsigned *>(&Ah(buf, q * 4 + j, kl)) = gala_pack_bf16(rr[0][j], rr[1][j]);
+                const float along_k[4] = {rr[0][j], rr[1][j], PA == 4 ? rr[2 % PA][j] : 0.f, PA == 4 ? rr[3 % PA][j] : 0.f};
+                unsigned lo[NA], hi[NA];
+                gala_pieces4<NA>(along_k, lo, hi);
+#pragma unroll
+                for (int pc = 0; pc < NA; ++pc) {
+                    if (PA == 4) *reinterpret_cast<uint2 *>(&Ah(buf, pc, q * 4 + j, kl)) = make_uint2(lo[pc], hi[pc]);
+                    else *reinterpret_cast<unsigned *>(&Ah(buf, pc, q * 4 + j, kl)) = lo[pc];
+                }
             }
         }
 #pragma unroll
@@ -310,15 +343,22 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void i
                 }
                 if (BF16 && P::A_KC) {
                     const int row = g / (BK / 4), kq = g % (BK / 4);
-                    *reinterpret_cast<uint2 *>(&Ah(buf, row, kq * 4)) =
-                        make_uint2(gala_pack_bf16(r[0], r[1]), gala_pack_bf16(r[2], r[3]));
+                    unsigned lo[NA], hi[NA];
+                    gala_pieces4<NA>(r, lo, hi);
+#pragma unroll
+                    for (int pc = 0; pc < NA; ++pc)
+                        *reinterpret_cast<uint2 *>(&Ah(buf, pc, row, kq * 4)) = make_uint2(lo[pc], hi[pc]);
                 } else if (BF16) {
                     int k, mq; map_a(i, k, mq);
-                    const unsigned p01 = gala_pack_bf16(r[0], r[1]), p23 = gala_pack_bf16(r[2], r[3]);
-                    Ah(buf, mq * 4 + 0, k) = (unsigned short)(p01 & 0xffffu);
-                    Ah(buf, mq * 4 + 1, k) = (unsigned short)(p01 >> 16);
-                    Ah(buf, mq * 4 + 2, k) = (unsigned short)(p23 & 0xffffu);
-                    Ah(buf, mq * 4 + 3, k) = (unsigned short)(p23 >> 16);
+                    unsigned lo[NA], hi[NA];
+                    gala_pieces4<NA>(r, lo, hi);
+#pragma unroll
+                    for (int pc = 0; pc < NA; ++pc) {
+                        Ah(buf, pc, mq * 4 + 0, k) = (unsigned short)(lo[pc] & 0xffffu);
+                        Ah(buf, pc, mq * 4 + 1, k) = (unsigned short)(lo[pc] >> 16);
+                        Ah(buf, pc, mq * 4 + 2, k) = (unsigned short)(hi[pc] & 0xffffu);
+                        Ah(buf, pc, mq * 4 + 3, k) = (unsigned short)(hi[pc] >> 16);
+                    }
                 } else if (P::A_KC) {
                     const int row = g / (BK / 4), kq = g % (BK / 4);
 #pragma unroll
@@ -343,40 +383,30 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void i
 #pragma unroll
                     for (int j = 0; j < 4; ++j) r[j] = okb[i] ? r[j] : 0.f;
                 }
-                if (MODE == 2) {
-                    unsigned short pc[3][4];
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) gala_split3_bf16(r[j], pc[0][j], pc[1][j], pc[2][j]);
-                    if (P::B_KC) {
-                        const int col = g / (BK / 4), kq = g % (BK / 4);
-#pragma unroll
-                        for (int q = 0; q < 3; ++q)
-                            *reinterpret_cast<uint2 *>(&Bh(buf, q, col, kq * 4)) =
-                                make_uint2(pc[q][0] | ((unsigned)pc[q][1] << 16), pc[q][2] | ((unsigned)pc[q][3] << 16));
-                    } else {
-                        int k, nq; map_mc(QB{}, i, k, nq);
-#pragma unroll
-                        for (int q = 0; q < 3; ++q)
-#pragma unroll
-                            for (int j = 0; j < 4; ++j) Bh(buf, q, nq * 4 + j, k) = pc[q][j];
-                    }
-                } else if (BF16 && P::B_KC) {
+                if (BF16 && P::B_KC) {
                     const int col = g / (BK / 4), kq = g % (BK / 4);
-                    *reinterpret_cast<uint2 *>(&Bh(buf, 0, col, kq * 4)) =
-                        make_uint2(gala_pack_bf16(r[0], r[1]), gala_pack_bf16(r[2], r[3]));
+                    unsigned lo[NB], hi[NB];
+                    gala_pieces4<NB>(r, lo, hi);
+#pragma unroll
+                    for (int pc = 0; pc < NB; ++pc)
+                        *reinterpret_cast<uint2 *>(&Bh(buf, pc, col, kq * 4)) = make_uint2(lo[pc], hi[pc]);
                 } else if (BF16) {
-                    int k, nq; map_mc(QB{}, i, k, nq);
-                    const unsigned p01 = gala_pack_bf16(r[0], r[1]), p23 = gala_pack_bf16(r[2], r[3]);
-                    Bh(buf, 0, nq * 4 + 0, k) = (unsigned short)(p01 & 0xffffu);
-                    Bh(buf, 0, nq * 4 + 1, k) = (unsigned short)(p01 >> 16);
-                    Bh(buf, 0, nq * 4 + 2, k) = (unsigned short)(p23 & 0xffffu);
-                    Bh(buf, 0, nq * 4 + 3, k) = (unsigned short)(p23 >> 16);
+                    int k, nq; map_mc(QB{}, i, k, nq, KFAST_B);
+                    unsigned lo[NB], hi[NB];
+                    gala_pieces4<NB>(r, lo, hi);
+#pragma unroll
+                    for (int pc = 0; pc < NB; ++pc) {
+                        Bh(buf, pc, nq * 4 + 0, k) = (unsigned short)(lo[pc] & 0xffffu);
+                        Bh(buf, pc, nq * 4 + 1, k) = (unsigned short)(lo[pc] >> 16);
+                        Bh(buf, pc, nq * 4 + 2, k) = (unsigned short)(hi[pc] & 0xffffu);
+                        Bh(buf, pc, nq * 4 + 3, k) = (unsigned short)(hi[pc] >> 16);
+                    }
                 } else if (P::B_KC) {
                     const int col = g / (BK / 4), kq = g % (BK / 4);
 #pragma unroll
                     for (int j = 0; j < 4; ++j) Bs(buf, kq * 4 + j, col) = r[j];
                 } else {
-                    int k, nq; map_mc(QB{}, i, k, nq);
+                    int k, nq; map_mc(QB{}, i, k, nq, KFAST_B);
                     *reinterpret_cast<float4 *>(&Bs(buf, k, nq * 4)) = make_float4(r[0], r[1], r[2], r[3]);
                 }
                 if (!P::B_KC && P::SUM_B && do_sum_b) {
@@ -414,23 +444,52 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void i
         if constexpr (BF16) {
 #pragma unroll
             for (int kk = 0; kk < BK; kk += 16) {
-                gala_s16x4 a[BI], b[NB][BJ];
+                gala_s16x4 a[NA][BI], b[NB][BJ];
 #pragma unroll
-                for (int i = 0; i < BI; ++i)
-                    a[i] = *reinterpret_cast<const gala_s16x4 *>(&Ah(buf, wm0 + i * MB + lr, kk + lk * 4));
+                for (int pc = 0; pc < NA; ++pc)
+#pragma unroll
+                    for (int i = 0; i < BI; ++i)
+                        a[pc][i] = *reinterpret_cast<const gala_s16x4 *>(&Ah(buf, pc, wm0 + i * MB + lr, kk + lk * 4));
 #pragma unroll
                 for (int q = 0; q < NB; ++q)
 #pragma unroll
                     for (int j = 0; j < BJ; ++j)
                         b[q][j] = *reinterpret_cast<const gala_s16x4 *>(&Bh(buf, q, wn0 + j * MB + lr, kk + lk * 4));
-                // smallest pieces first
+                // Products of pieces a_pc b_q with pc + q <= NB - 1, the small ones first.  The
+                // 16x16x32 instruction takes eight k per lane: fed with the same four k of two
+                // different pieces it adds two such products at once.
+                if constexpr (MODE == 3) {
+                    gala_bf16x8 a01[BI], a02[BI], b21[BJ], b10[BJ], b00[BJ];
 #pragma unroll
-                for (int q = NB - 1; q >= 0; --q)
+                    for (int i = 0; i < BI; ++i) { a01[i] = gala_cat(a[0][i], a[1][i]); a02[i] = gala_cat(a[0][i], a[2][i]); }
+#pragma unroll
+                    for (int j = 0; j < BJ; ++j) {
+                        b21[j] = gala_cat(b[2][j], b[1][j]); b10[j] = gala_cat(b[1][j], b[0][j]); b00[j] = gala_cat(b[0][j], b[0][j]);
+                    }
 #pragma unroll
                     for (int i = 0; i < BI; ++i)
 #pragma unroll
-                        for (int j = 0; j < BJ; ++j)
-                            acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a[i], b[q][j], acc[i][j], 0, 0, 0);
+                        for (int j = 0; j < BJ; ++j)       // a0 b2 + a1 b1
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a01[i], b21[j], acc[i][j], 0, 0, 0);
+#pragma unroll
+                    for (int i = 0; i < BI; ++i)
+#pragma unroll
+                        for (int j = 0; j < BJ; ++j)       // a0 b1 + a2 b0
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a02[i], b10[j], acc[i][j], 0, 0, 0);
+#pragma unroll
+                    for (int i = 0; i < BI; ++i)
+#pragma unroll
+                        for (int j = 0; j < BJ; ++j)       // a0 b0 + a1 b0
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a01[i], b00[j], acc[i][j], 0, 0, 0);
+                } else {
+#pragma unroll
+                    for (int q = NB - 1; q >= 0; --q)
+#pragma unroll
+                        for (int i = 0; i < BI; ++i)
+#pragma unroll
+                            for (int j = 0; j < BJ; ++j)
+                                acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a[0][i], b[q][j], acc[i][j], 0, 0, 0);
+                }
             }
         } else {
 #pragma unroll
@@ -553,6 +612,8 @@ static inline hipError_t igemm_launch(const P &p, int n_agents, hipStream_t stre
     if (bf16) hipLaunchKernelGGL((igemm_kernel<P, 1>), dim3(grid), dim3(256), 0, stream, p, n_agents);
     else if constexpr (P::A_EXACT_BF16 && P::MFMA16)
         hipLaunchKernelGGL((igemm_kernel<P, 2>), dim3(grid), dim3(256), 0, stream, p, n_agents);
+    else if constexpr (P::SPLIT3 && P::MFMA16)
+        hipLaunchKernelGGL((igemm_kernel<P, 3>), dim3(grid), dim3(256), 0, stream, p, n_agents);
     else hipLaunchKernelGGL((igemm_kernel<P, 0>), dim3(grid), dim3(256), 0, stream, p, n_agents);
     return hipGetLastError();
 }

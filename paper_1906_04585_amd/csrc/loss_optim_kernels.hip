@@ -188,6 +188,21 @@ __global__ __launch_bounds__(NORM_THREADS) void grad_norm_kernel(const float *__
 }
 
 // ---- clip + RMSprop (Table 2; momentum 0) ---------------------------------------------------------------
+// The gradient and the second-moment estimate are touched once per round, hundreds of MB apart
+// in time: their loads and stores carry the non-temporal hint so that they stream past the
+// caches instead of evicting the parameters and activations that are reused.
+typedef float stream_vec4 __attribute__((ext_vector_type(4)));
+static __device__ __forceinline__ float4 stream_load4(const float *base, long idx4)
+{
+    const stream_vec4 t = __builtin_nontemporal_load(reinterpret_cast<const stream_vec4 *>(base) + idx4);
+    return make_float4(t.x, t.y, t.z, t.w);
+}
+static __device__ __forceinline__ void stream_store4(float *base, long idx4, float4 val)
+{
+    stream_vec4 t; t.x = val.x; t.y = val.y; t.z = val.z; t.w = val.w;
+    __builtin_nontemporal_store(t, reinterpret_cast<stream_vec4 *>(base) + idx4);
+}
+
 //   g <- c g;  v <- a v + (1 - a) g^2;  x <- x - lr g / (sqrt(v) + eps)
 static __device__ __forceinline__ void rmsprop4(float4 &xx, float4 &vv, float4 gg, float c, float lr, float alpha,
                                                 float om, float eps)
@@ -208,13 +223,14 @@ __global__ __launch_bounds__(256) void rmsprop_kernel(float *x, float *v, const 
     const float c = stats[agent * 5 + 4];
     const long n4 = d_pad / 4;
     float4 *x4 = reinterpret_cast<float4 *>(x + agent * d_pad);
-    float4 *v4 = reinterpret_cast<float4 *>(v + agent * d_pad);
-    const float4 *g4 = reinterpret_cast<const float4 *>(g + agent * g_stride);
+    float *va = v + agent * d_pad;
+    const float *ga = g + agent * g_stride;
     const float om = 1.f - alpha;
     for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < n4; i += (long)gridDim.x * 256) {
-        float4 vv = v4[i], xx = x4[i];
-        rmsprop4(xx, vv, g4[i], c, lr, alpha, om, eps);
-        v4[i] = vv; x4[i] = xx;
+        float4 vv = stream_load4(va, i), xx = x4[i];
+        // a gradient shared by all agents is read once per agent: kept cacheable
+        rmsprop4(xx, vv, g_stride ? stream_load4(ga, i) : reinterpret_cast<const float4 *>(ga)[i], c, lr, alpha, om, eps);
+        stream_store4(va, i, vv); x4[i] = xx;
     }
 }
 
@@ -390,9 +406,9 @@ __global__ __launch_bounds__(256) void rmsprop_mix_kernel(float *x, float *v, co
     float4 *slot = tau > 0 ? reinterpret_cast<float4 *>(hist + (round % (tau + 1)) * (long)N * d_pad) : nullptr;
     for (int i = q; i < N; i += GROUPS) {
         const long at = (long)i * n4 + e;
-        float4 vv = reinterpret_cast<float4 *>(v)[at], xx = reinterpret_cast<float4 *>(x)[at];
-        rmsprop4(xx, vv, reinterpret_cast<const float4 *>(g)[at], stats[i * 5 + 4], lr, alpha, om, eps);
-        reinterpret_cast<float4 *>(v)[at] = vv;
+        float4 vv = stream_load4(v, at), xx = reinterpret_cast<float4 *>(x)[at];
+        rmsprop4(xx, vv, stream_load4(g, at), stats[i * 5 + 4], lr, alpha, om, eps);
+        stream_store4(v, at, vv);
         u[i * COLS4 + col] = xx;
         if (slot) slot[at] = xx;
     }
@@ -418,6 +434,63 @@ __global__ __launch_bounds__(256) void rmsprop_mix_kernel(float *x, float *v, co
             }
         reinterpret_cast<float4 *>(x)[(long)i * n4 + e] = a;
     }
+}
+
+// The same pass without LDS for topologies in which every agent has exactly one in-peer, no
+// delay, and the peers form a permutation (directed ring, 1-peer exponential graph): the
+// permutation splits the agents into cycles a_0 <- a_1 <- ... <- a_0 (a_t receives from a_{t+1}).
+// A thread owns one float4 column of one cycle and walks it once, keeping the previous agent's
+// post-update value in registers, so that every value is read and written exactly once and no
+// workgroup ever waits: x_new(a_t) = w_self u(a_t) + w_peer u(a_{t+1}), same order of operations
+// as rmsprop_kernel + mix_kernel.  order[] lists the agents cycle by cycle, cstart[] the cycles'
+// first entries (n_cycles + 1 values), both for the phase of this round.
+__global__ __launch_bounds__(256) void rmsprop_mix_cycle_kernel(float *x, float *v, const float *__restrict__ g,
+                                                                long d_pad, const int32_t *__restrict__ order,
+                                                                const int32_t *__restrict__ cstart,
+                                                                const float *__restrict__ weight,
+                                                                const float *__restrict__ stats, float lr, float alpha,
+                                                                float eps)
+{
+    const long n4 = d_pad / 4;
+    const long e = (long)blockIdx.x * 256 + threadIdx.x;
+    if (e >= n4) return;
+    const int b0 = cstart[blockIdx.y], b1 = cstart[blockIdx.y + 1];
+    const float om = 1.f - alpha;
+    auto update = [&](int agent) -> float4 {
+        const long at = (long)agent * n4 + e;
+        float4 vv = stream_load4(v, at), xx = reinterpret_cast<float4 *>(x)[at];
+        rmsprop4(xx, vv, stream_load4(g, at), stats[agent * 5 + 4], lr, alpha, om, eps);
+        stream_store4(v, at, vv);
+        return xx;
+    };
+    auto mix_store = [&](int agent, float4 own, float4 msg) {
+        const float ws = weight[agent * 2], wp = weight[agent * 2 + 1];
+        float4 a = own;
+        a.x *= ws; a.y *= ws; a.z *= ws; a.w *= ws;
+        a.x += wp * msg.x; a.y += wp * msg.y; a.z += wp * msg.z; a.w += wp * msg.w;
+        reinterpret_cast<float4 *>(x)[(long)agent * n4 + e] = a;
+    };
+    int prev_agent = order[b0];
+    const float4 first = update(prev_agent);
+    float4 prev = first;
+    for (int t = b0 + 1; t < b1; ++t) {
+        const int agent = order[t];
+        const float4 cur = update(agent);
+        mix_store(prev_agent, prev, cur);
+        prev = cur; prev_agent = agent;
+    }
+    mix_store(prev_agent, prev, first);
+}
+
+hipError_t launch_rmsprop_mix_cycles(int N, const Layout &L, const HParams &hp, float *x, float *v, const float *g,
+                                     const int32_t *order, const int32_t *cstart, int n_cycles, const float *weight,
+                                     const float *stats, hipStream_t s)
+{
+    const int blocks = (int)((L.d_pad / 4 + 255) / 256);
+    hipLaunchKernelGGL(rmsprop_mix_cycle_kernel, dim3(blocks, n_cycles), dim3(256), 0, s, x, v, g, L.d_pad, order, cstart,
+                       weight, stats, hp.lr, hp.rms_alpha, hp.rms_eps);
+    (void)N;
+    return hipGetLastError();
 }
 
 // widest column block whose LDS tile stays within FUSED_LDS_BYTES; 0 = too many agents

@@ -61,6 +61,7 @@ struct ProblemBase {
     static constexpr bool SUM_A = false, SUM_B = false, HAS_AUX = false, A_ZERO = false, B_ZERO = false;
     static constexpr bool SUMSQ = false;
     static constexpr bool A_EXACT_BF16 = false;   // true: every A value is an integer 0..255 (a byte image)
+    static constexpr bool SPLIT3 = false;         // true: fp32 accuracy from three bf16 pieces of both operands
     static constexpr int TABLE = 0;
     static constexpr bool BLOCK_FETCH_A = false;
     __device__ void fill_table(int *, int) {}
@@ -140,6 +141,7 @@ template <int CI, int HI, int WI, int CO, int HO, int WO, int KS, int ST>
 struct ConvFwd : ProblemBase {
     static constexpr int BM = 128, BN = 64, BK = 16, WM = 2, WN = 2;
     static constexpr bool A_KC = true, B_KC = false;
+    static constexpr bool SPLIT3 = true;
     static_assert((KS * CI) % BK == 0, "a k-tile stays inside one kernel row");
     const float *in, *x;
     float *out;
@@ -187,6 +189,7 @@ template <int BM_>
 struct FcFwdT : ProblemBase {
     static constexpr int BM = BM_, BN = 128, BK = 16, WM = 1, WN = 4;
     static constexpr bool A_KC = true, B_KC = true;
+    static constexpr bool SPLIT3 = true;
     const float *a3, *x;
     float *ws;
     long d_pad, w_off;
@@ -219,6 +222,7 @@ struct FcDgrad : ProblemBase {
     static constexpr int BM = 80, BN = 128, BK = 16, WM = 1, WN = 4;     // 5 x 16 rows: no padding at M = 80, 160
     static constexpr bool A_KC = true, B_KC = false;
     static constexpr bool HAS_AUX = true;
+    static constexpr bool SPLIT3 = true;
     const float *dzh, *x, *a3;
     float *dz3;
     long d_pad, w_off;
@@ -320,6 +324,7 @@ struct Conv3Dgrad : ProblemBase {
     static constexpr int BM = GALA_MFMA16 ? 160 : 128, BN = 64, BK = 16, WM = 2, WN = 2;
     static constexpr bool A_KC = true, B_KC = true;
     static constexpr bool HAS_AUX = true;
+    static constexpr bool SPLIT3 = true;
     static constexpr int TILES_PER_TAP = C3 / BK;
     typedef TapCtx CtxA;
     const float *dz3, *x, *a2;      // dz3 points at the data; ZERO_PAGE zeros precede the allocation's data

@@ -167,6 +167,8 @@ def test_config2_lockstep_rounds():
         gpu.gossip(r)
         om.gossip(r)
         compare_params(gpu, om, net, f"cfg2 gossip {r}")
+        if r % 10 == 9:
+            print(f"cfg2: {r + 1} rounds agree", flush=True)      # a long run shows that it is alive
 
 
 def test_config3_delayed_gossip_lockstep():
@@ -189,6 +191,8 @@ def test_config3_delayed_gossip_lockstep():
         om.gossip(r)
         compare_params(gpu, om, net, f"cfg3 gossip {r}")
         seen |= set(gpu.get_peer_table(r)[1][:, 0].tolist())
+        if r % 10 == 9:
+            print(f"cfg3: {r + 1} rounds agree", flush=True)
     assert seen == {0, 1, 2}
 
 
@@ -367,3 +371,34 @@ def test_conv1_split_precision_is_fp32_level():
         worst_g = max(worst_g, rel_err(g[i, sl["conv1.w"]], om.grads[i, sl["conv1.w"]]))
     print(f"conv1 activation err {worst_a:.2e}, conv1.w gradient err {worst_g:.2e}")
     assert worst_a <= 1e-5 and worst_g <= 1e-5
+
+
+def test_six_product_split_precision_is_fp32_level():
+    """The second and third convolutions and the hidden layer (forward), and the data gradients of
+    the hidden layer and the third convolution, multiply three bf16 pieces of both operands (six
+    piece products).  Their activations and the gradients that flow through them must agree with
+    the fp64 oracle as closely as single-precision accumulation allows (1e-5 of the largest
+    entry), two orders below what one bf16 rounding of an operand (4e-3) would leave."""
+    cfg, net, gpu, om, X0 = _make(2)
+    N, T, B = cfg["n_agents"], cfg["T"], cfg["B"]
+    ro = gs.rollout(net, N, T, B, gs.round_seed(2, 78))
+    step_both(gpu, om, ro)
+    offs = orc.act_offsets(net)
+    sl = gs.segment_slices(net)
+    g = gpu.get_grads()
+    worst = {}
+    for layer, key in ((2, "conv2"), (3, "conv3"), (4, "fc")):
+        a = gpu.get_activations(layer)
+        a = a.reshape(N, T * B + B, -1) if layer == 4 else a.transpose(0, 1, 4, 2, 3).reshape(N, T * B + B, -1)
+        off, shape = offs[key]
+        n = int(np.prod(shape))
+        for i in range(N):
+            obs = ro["obs"][i].reshape((T * B,) + ro["obs"].shape[3:])
+            _, _, acts = orc.forward_acts(net, X0[i].astype(np.float64), obs)
+            worst[key] = max(worst.get(key, 0.0), rel_err(a[i, :T * B], acts[:, off:off + n]))
+    # weight gradients downstream of the split data-gradient kernels (fc dgrad feeds conv3.w, conv3 dgrad feeds conv2.w)
+    for name in ("conv3.w", "conv2.w", "conv1.w"):
+        for i in range(N):
+            worst[name] = max(worst.get(name, 0.0), rel_err(g[i, sl[name]], om.grads[i, sl[name]]))
+    print("six-product split errors:", {k: f"{v:.2e}" for k, v in worst.items()})
+    assert max(worst.values()) <= 1e-5

@@ -35,8 +35,13 @@ def grad_scale(ref_agent, sl, name) -> float:
     return float(own)
 
 
+# The hidden layer's fp32 activations agree with exact arithmetic to about 1e-6 of their largest
+# value; measured against the tolerance of 1e-4 that is this fraction of a sum's term magnitude.
+TERM_FRACTION = 1e-2
+
+
 def loss_conditioning(net, hp, x, ro: dict, i: int):
-    """(pg_scale, kappa) of agent i from an oracle forward pass.
+    """(pg_scale, kappa, rho_v) of agent i from an oracle forward pass.
 
     pg_scale = mean |log pi(a_m | s_m) * A_m|: the magnitude the policy term is made of.  The term
     itself, mean(-log pi * A), is a sum of signed products that can cancel to a small fraction of
@@ -47,19 +52,30 @@ def loss_conditioning(net, hp, x, ro: dict, i: int):
     error times kappa, and every gradient is linear in A (policy term) or in G - V (value term).
     At initialisation kappa is about 1; after many updates on random rewards the values grow
     into the hundreds while advantages stay of order one, and the gradients cannot agree with
-    the oracle better than kappa times the usual error.  Gradient tolerances are scaled by it."""
+    the oracle better than kappa times the usual error.  Gradient tolerances are scaled by it.
+
+    rho_v = max_j sum_f |A_f| h_fj / max_j |sum_f A_f h_fj|: how much the value head's weight
+    gradient, a sum over frames of advantages of both signs times the hidden activations, cancels.
+    Once the value regression has converged on an agent's data this gradient sits near a
+    stationary point and is hundreds to thousands of times smaller than its terms, while its
+    absolute error stays that of the terms (about 1e-6 of them).  The value head's two tensors
+    are therefore measured against max(own size, TERM_FRACTION * term magnitude)."""
     from oracle import gala_oracle as orc
     T, B = ro["actions"].shape[1:3]
     M = T * B
     frames = np.concatenate([ro["obs"][i].reshape((M,) + ro["obs"].shape[3:]), ro["boot_obs"][i]], axis=0)
-    logits, values = orc.forward(net, np.asarray(x, dtype=np.float64), frames)
+    logits, values, acts = orc.forward_acts(net, np.asarray(x, dtype=np.float64), frames)
+    off, shape = orc.act_offsets(net)["fc"]
+    h = acts[:M, off:off + shape[0]]
     G, adv = orc.nstep_returns(ro["rewards"][i], ro["dones"][i], values[M:], values[:M].reshape(T, B), hp["gamma"])
     z = logits[:M]
     logp = z - z.max(1, keepdims=True)
     logp = logp - np.log(np.exp(logp).sum(1, keepdims=True))
     la = logp[np.arange(M), ro["actions"][i].reshape(M)]
     kappa = max(1.0, float(np.abs(G).max() / max(np.abs(adv).max(), 1e-30)))
-    return float(np.abs(la * adv.reshape(M)).mean()), kappa
+    a = adv.reshape(M, 1)
+    rho_v = float((np.abs(a) * h).sum(0).max() / max(np.abs((a * h).sum(0)).max(), 1e-300))
+    return float(np.abs(la * adv.reshape(M)).mean()), kappa, rho_v
 
 
 def pg_scale(net, hp, x, ro: dict, i: int) -> float:
@@ -69,9 +85,12 @@ def pg_scale(net, hp, x, ro: dict, i: int) -> float:
 # Last resort for a gradient tensor that misses the criterion in an ill-conditioned state (sums
 # over samples of advantages of both signs times large activations): how far does the *exact*
 # gradient move when the parameters are perturbed by one unit of single-precision round-off?  The
-# fp32 computation rounds at every one of its stages, so its result is the exact gradient of
-# inputs perturbed at least that much; PERTURB_FACTOR such movements are granted on top of the
-# tolerance.  In well-conditioned states the movement is ~1e-7 of the tensor and changes nothing.
+# fp32 computation rounds at every one of its stages: its activations agree with exact arithmetic
+# to about 1e-6 of a layer's largest value (eight units of round-off, what sums over thousands of
+# terms through four layers leave), several times what a one-unit perturbation of the parameters
+# produces, and the backward pass adds as much again.  PERTURB_FACTOR such movements are granted
+# on top of the tolerance.  In well-conditioned states the movement is ~1e-7 of the tensor and
+# changes nothing.
 PERTURB_FACTOR = 16.0
 
 
@@ -157,12 +176,14 @@ def compare_learner_step(gpu, orc_model, net, tag="", rtol=RTOL, ro=None, X_befo
     sl = gs.segment_slices(net)
     g = gpu.get_grads()
     worst = {}
-    cond = [loss_conditioning(net, orc_model.hp, X_before[i], ro, i) if ro is not None else (0.0, 1.0)
+    cond = [loss_conditioning(net, orc_model.hp, X_before[i], ro, i) if ro is not None else (0.0, 1.0, 1.0)
             for i in range(gpu.N)]
     for i in range(gpu.N):
         resp = None
         for name, s in sl.items():
             scale = grad_scale(orc_model.grads[i], sl, name)
+            if name.startswith("v."):
+                scale *= max(1.0, TERM_FRACTION * cond[i][2])
             e = rel_err(g[i, s], orc_model.grads[i, s], scale)
             if e > rtol * cond[i][1] and ro is not None:
                 resp = perturbation_response(net, orc_model.hp, X_before[i], ro, i) if resp is None else resp

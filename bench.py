@@ -29,8 +29,8 @@ PEAK_HBM_GBS = 8000.0
 # event-timed phase -> kernel name in the rocprofv3 summaries under profiles/
 # phases whose kernels reach fp32 accuracy with bf16 matrix instructions on exact bf16 pieces of the
 # operands: pieces multiplied per algorithmic product
-SPLIT_PRODUCTS = {"conv1_fwd": 3, "conv1_wgrad": 3,
-                  "conv2_fwd": 6, "conv3_fwd": 6, "fc_fwd": 6, "fc_dgrad": 6, "conv3_dgrad": 6}
+SPLIT_PRODUCTS = {"conv1_fwd": 3, "conv1_wgrad": 3, "conv2_fwd": 6, "conv3_fwd": 6, "fc_fwd": 6,
+                  "fc_dgrad": 6, "fc_wgrad": 6, "conv3_dgrad": 6, "conv2_wgrad": 6}
 
 
 def kernel_of_phase(dtype: str) -> dict:
@@ -313,6 +313,10 @@ def main() -> int:
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": args.dtype,
+        "arithmetic": ("fp32 parameters, activations and accumulators; products on fp32 matrix instructions or, "
+                       "equally accurate, on bf16 matrix instructions over exact bf16 pieces of the fp32 operands "
+                       "(see kernels[*].dtype)") if args.dtype == "f32" else
+                      "fp32 parameters, activations and accumulators; operands rounded to bf16 for the matrix instructions",
         "data": "synthetic",
         "config": {"workload": f"N={N} agents, 1-peer {cfg['topology']} graph, Nature-CNN, {A} actions, "
                                f"rollout {T}x{B} per agent ({N * M} frames/round), "

@@ -190,15 +190,21 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MODE == 3 ?
     auto As = [&](int buf, int k, int c) -> float & { return smem[(buf * BK + k) * SA + c]; };
     auto Bs = [&](int buf, int k, int c) -> float & { return smem[OFFB + (buf * BK + k) * SB + c]; };
     // bf16 tiles: [buf][row][BK + 4] shorts (the padding keeps 8-byte alignment and spreads banks)
-    static_assert(!BF16 || (P::MFMA16 && BK % 16 == 0), "bf16 path: 16x16x16 blocks");
+    static_assert(!BF16 || (P::MFMA16 && BK == 16), "bf16 path: 16x16 blocks, four k-quads per tile row");
     constexpr int OFFBH = 2 * NA * BM * BKP;
     static_assert(!BF16 || (2 * (NA * BM + NB * BN) * BKP * 2 <= LDS_FLOATS * 4), "bf16 tiles fit the allocation");
     unsigned short *hs = reinterpret_cast<unsigned short *>(smem);
+    // Row-contiguous operands arrive as four rows at one k and are written as single 16-bit
+    // values by lanes whose rows lie four apart: with a row of ten dwords only four LDS banks
+    // would take a wavefront's store.  The four k-quads of a row are therefore exchanged by the
+    // row's bits 4..5, which spreads sixteen such rows over all banks and leaves the MFMA operand
+    // read (one aligned k-quad per lane, sixteen consecutive rows) as it was.
+    auto swz = [](int row, int k) { return k ^ (((row >> 4) & 3) << 2); };
     auto Ah = [&](int buf, int piece, int m, int k) -> unsigned short & {
-        return hs[((buf * NA + piece) * BM + m) * BKP + k];
+        return hs[((buf * NA + piece) * BM + m) * BKP + swz(m, k)];
     };
     auto Bh = [&](int buf, int piece, int n, int k) -> unsigned short & {
-        return hs[OFFBH + ((buf * NB + piece) * BN + n) * BKP + k];
+        return hs[OFFBH + ((buf * NB + piece) * BN + n) * BKP + swz(n, k)];
     };
 
     const int bid = blockIdx.x;
@@ -248,17 +254,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MODE == 3 ?
     // that k for all of its groups, so whatever the functor derives from k (a position walked
     // through frame, row, column) is computed once per thread and tile, not once per group.
     constexpr int TPK = 256 / BK;                   // threads per k-row in that arrangement
-    // bf16 tiles are [row][k]: there the four rows of a group are written as single 16-bit
-    // values, and lanes that differ in the quad (rows four apart) would collide on a few LDS
-    // banks.  Operands without a running sum therefore let k run fastest over the lanes, so that
-    // sixteen lanes write one row's sixteen consecutive k.
-    auto map_mc = [&](auto qc, int i, int &kl, int &q, bool k_fastest = false) {
+    auto map_mc = [&](auto qc, int i, int &kl, int &q) {
         constexpr int Q = decltype(qc)::value;      // quads per k-row
-        if (k_fastest) { const int g = tid + i * 256; kl = g % BK; q = g / BK; }
-        else if (Q % TPK == 0) { kl = tid / TPK; q = tid % TPK + TPK * i; }
+        if (Q % TPK == 0) { kl = tid / TPK; q = tid % TPK + TPK * i; }
         else { const int g = tid + i * 256; kl = g / Q; q = g % Q; }
     };
-    constexpr bool KFAST_A = BF16 && !P::SUM_A, KFAST_B = BF16 && !P::SUM_B;
     typedef std::integral_constant<int, BM / 4> QA;
     typedef std::integral_constant<int, BN / 4> QB;
     // bf16 tiles are [row][k]: an m-contiguous A operand would scatter single bf16 values.  Where
@@ -269,7 +269,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MODE == 3 ?
     constexpr int KT_A = KCONS_A ? 256 / (BM / 4) : 1;          // threads that share a quad of rows
     auto map_a = [&](int i, int &kl, int &q) {
         if (KCONS_A) { kl = (tid % KT_A) * PA + i; q = tid / KT_A; }
-        else map_mc(QA{}, i, kl, q, KFAST_A);
+        else map_mc(QA{}, i, kl, q);
     };
 
 #pragma unroll
@@ -287,7 +287,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MODE == 3 ?
         okb[i] = true;
         if (GB % 256 == 0 || g < GB) {
             if (P::B_KC) p.prep_b(cb[i], (g % (BK / 4)) * 4, n0 + g / (BK / 4));
-            else { int kl, q; map_mc(QB{}, i, kl, q, KFAST_B); p.prep_b(cb[i], kl, n0 + q * 4); }
+            else { int kl, q; map_mc(QB{}, i, kl, q); p.prep_b(cb[i], kl, n0 + q * 4); }
         }
     }
 
@@ -391,7 +391,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MODE == 3 ?
                     for (int pc = 0; pc < NB; ++pc)
                         *reinterpret_cast<uint2 *>(&Bh(buf, pc, col, kq * 4)) = make_uint2(lo[pc], hi[pc]);
                 } else if (BF16) {
-                    int k, nq; map_mc(QB{}, i, k, nq, KFAST_B);
+                    int k, nq; map_mc(QB{}, i, k, nq);
                     unsigned lo[NB], hi[NB];
                     gala_pieces4<NB>(r, lo, hi);
 #pragma unroll
@@ -406,7 +406,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MODE == 3 ?
 #pragma unroll
                     for (int j = 0; j < 4; ++j) Bs(buf, kq * 4 + j, col) = r[j];
                 } else {
-                    int k, nq; map_mc(QB{}, i, k, nq, KFAST_B);
+                    int k, nq; map_mc(QB{}, i, k, nq);
                     *reinterpret_cast<float4 *>(&Bs(buf, k, nq * 4)) = make_float4(r[0], r[1], r[2], r[3]);
                 }
                 if (!P::B_KC && P::SUM_B && do_sum_b) {

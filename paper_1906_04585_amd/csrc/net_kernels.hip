@@ -259,6 +259,7 @@ struct FcWgrad : ProblemBase {
     static constexpr int BM = 128, BN = 128, BK = 16, WM = 2, WN = 2;
     static constexpr bool A_KC = false, B_KC = false;
     static constexpr bool SUM_A = true, A_ZERO = true, B_ZERO = true;
+    static constexpr bool SPLIT3 = true;
     static constexpr bool SUMSQ = true;      // this tensor is 95 % of the parameters: its share of ||g||^2
     static constexpr int TILES = (FC / BM) * ((FLAT + BN - 1) / BN);
     static_assert(TILES == FC_WGRAD_TILES && TILES <= NORM_PARTS, "one gradient-norm partial per tile");
@@ -485,6 +486,7 @@ struct WalkCtx { unsigned moff; int p; unsigned foff; int k; };
 // live in zero-paged buffers: groups past the end of the split's k-range read zeros.
 template <int CI, int HI, int WI, int CO, int HO, int WO, int KS, int ST, int BM_>
 struct ConvWgrad : ProblemBase {
+    static constexpr bool SPLIT3 = BM_ >= 128;     // the 64 x 64 tile of the third convolution is faster on fp32 MFMAs
     static constexpr int BM = BM_, BN = 64, BK = 16, WM = 2, WN = 2;
     static constexpr bool A_KC = false, B_KC = false;
     static constexpr bool SUM_B = true;

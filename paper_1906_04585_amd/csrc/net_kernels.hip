@@ -407,14 +407,17 @@ struct Conv3Dgrad : ProblemBase {
 };
 
 // ---- conv2: gradient to a1 (stride 2) ----------------------------------------------------------
-// Input positions split into four parity classes (iy%2, ix%2), carried in the "split"
-// index; within a class the transposed convolution is a stride-1 2x2 correlation:
-// m = (f, y', x') with iy = 2y'+py, n = c, k = (a, b, o) with kh = py + 2a, oy = y' - a.
+// Input positions fall into four parity classes (iy%2, ix%2); within a class the transposed
+// convolution is a stride-1 2x2 correlation over the same window of dz2, only the kernel taps
+// differ.  The four classes therefore form the columns of one GEMM that reads the window once:
+// m = (f, y', x') with iy = 2y'+py, n = (class, c), k = (a, b, o) with kh = py + 2a, oy = y' - a.
 struct Conv2Dgrad : ProblemBase {
-    static constexpr int BM = 256, BN = 32, BK = 16, WM = 4, WN = 1;
+    static constexpr int BM = 128, BN = 128, BK = 16, WM = 2, WN = 2;
     static constexpr bool A_KC = true, B_KC = true;
     static constexpr bool HAS_AUX = true;
+    static constexpr bool SPLIT3 = true;
     static constexpr int HY = H1 / 2, WX = W1 / 2, PC = HY * WX;   // 10, 10, 100
+    static_assert(BN == 4 * C1, "four classes of C1 channels");
     typedef TapCtx CtxA;
     const float *dz2, *x, *a1;
     float *dz1;
@@ -422,9 +425,9 @@ struct Conv2Dgrad : ProblemBase {
     int M, F;
     const float *zp_, *w_, *act_;
     float *out_;
-    int rows_, py_, px_;
+    int rows_;
     unsigned abase_;
-    __device__ void bind(int agent, int cls)
+    __device__ void bind(int agent, int)
     {
         zp_ = dz2 - ZERO_PAGE;
         abase_ = ZPB + (unsigned)agent * (unsigned)(M * A2SZ) * 4u;
@@ -432,7 +435,6 @@ struct Conv2Dgrad : ProblemBase {
         act_ = a1 + (long)agent * F * A1SZ;
         out_ = dz1 + (long)agent * M * A1SZ;
         rows_ = M * PC;
-        py_ = cls >> 1; px_ = cls & 1;
         k0 = 0; k1 = 4 * C2;
     }
     __device__ void prep_a(CtxA &c, int m, int kl) const
@@ -453,17 +455,21 @@ struct Conv2Dgrad : ProblemBase {
         const int tap = (o0 - ((t >> 1) * W2 + (t & 1)) * C2) * 4;
         return ldg4b(zp_, ((c.mask >> t) & 1u) ? c.off + (unsigned)tap : 0u);
     }
-    __device__ void prep_b(CtxB &c, int kl, int n) const { c.off = (unsigned)((n * C2 + kl) * 4); }
+    __device__ void prep_b(CtxB &c, int kl, int n) const
+    {
+        const int cls = n / C1, ch = n % C1;                                       // kernel tap (py, px) of the class
+        c.off = (unsigned)(((((cls >> 1) * K2 + (cls & 1)) * C1 + ch) * C2 + kl) * 4);
+    }
     __device__ float4 fetch_b(CtxB &c, int kt0, bool &) const
     {
         const int t = kt0 / C2, o0 = kt0 % C2;
-        const int kh = py_ + 2 * (t >> 1), kw = px_ + 2 * (t & 1);
-        return ldg4b(w_ + (kh * K2 + kw) * (C1 * C2) + o0, c.off);
+        return ldg4b(w_ + (2 * (t >> 1) * K2 + 2 * (t & 1)) * (C1 * C2) + o0, c.off);
     }
     __device__ unsigned out_index(int m, int n) const
     {
         const int f = m / PC, p = m % PC, yy = p / WX, xx = p % WX;
-        return (unsigned)(((f * H1 + 2 * yy + py_) * W1 + 2 * xx + px_) * C1 + n);
+        const int cls = n / C1, ch = n % C1;
+        return (unsigned)(((f * H1 + 2 * yy + (cls >> 1)) * W1 + 2 * xx + (cls & 1)) * C1 + ch);
     }
     __device__ bool tile_full(int m0, int) const { return m0 + BM <= rows_; }
     template <bool CHECK> __device__ float4 aux4(int m, int n) const
@@ -951,7 +957,7 @@ hipError_t launch_backward(const NetArgs &a, hipStream_t s, PhaseTimer *pt, cons
         Conv2Dgrad p{};
         p.dz2 = a.b.dz2; p.x = a.x; p.a1 = a.b.a1; p.dz1 = a.b.dz1; p.d_pad = L.d_pad; p.w_off = L.w2;
         p.M = a.M; p.F = a.F;
-        p.tiles_m = cdiv((long)a.M * Conv2Dgrad::PC, Conv2Dgrad::BM); p.tiles_n = 1; p.splits = 4;
+        p.tiles_m = cdiv((long)a.M * Conv2Dgrad::PC, Conv2Dgrad::BM); p.tiles_n = 1; p.splits = 1;
         GALA_TRY(igemm_launch(p, a.N, s, a.bf16));
         pt->mark("conv2_dgrad");
     }

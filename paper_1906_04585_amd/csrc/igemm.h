@@ -481,14 +481,29 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MODE == 3 ?
 #pragma unroll
                         for (int j = 0; j < BJ; ++j)       // a0 b0 + a1 b0
                             acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a01[i], b00[j], acc[i][j], 0, 0, 0);
+                } else if constexpr (MODE == 2) {
+                    // a (b0 + b1 + b2): the two small products in one 16x16x32 instruction, then a b0
+                    gala_bf16x8 aa[BI], b21[BJ];
+#pragma unroll
+                    for (int i = 0; i < BI; ++i) aa[i] = gala_cat(a[0][i], a[0][i]);
+#pragma unroll
+                    for (int j = 0; j < BJ; ++j) b21[j] = gala_cat(b[2][j], b[1][j]);
+#pragma unroll
+                    for (int i = 0; i < BI; ++i)
+#pragma unroll
+                        for (int j = 0; j < BJ; ++j)
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aa[i], b21[j], acc[i][j], 0, 0, 0);
+#pragma unroll
+                    for (int i = 0; i < BI; ++i)
+#pragma unroll
+                        for (int j = 0; j < BJ; ++j)
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a[0][i], b[0][j], acc[i][j], 0, 0, 0);
                 } else {
 #pragma unroll
-                    for (int q = NB - 1; q >= 0; --q)
+                    for (int i = 0; i < BI; ++i)
 #pragma unroll
-                        for (int i = 0; i < BI; ++i)
-#pragma unroll
-                            for (int j = 0; j < BJ; ++j)
-                                acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a[0][i], b[q][j], acc[i][j], 0, 0, 0);
+                        for (int j = 0; j < BJ; ++j)
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a[0][i], b[0][j], acc[i][j], 0, 0, 0);
                 }
             }
         } else {

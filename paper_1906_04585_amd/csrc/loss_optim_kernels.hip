@@ -204,14 +204,19 @@ static __device__ __forceinline__ void stream_store4(float *base, long idx4, flo
 }
 
 //   g <- c g;  v <- a v + (1 - a) g^2;  x <- x - lr g / (sqrt(v) + eps)
+static __device__ __forceinline__ void rmsprop1(float &x, float &v, float g, float c, float lr, float alpha, float om,
+                                                float eps)
+{
+    // explicit roundings: the separate and the fused optimizer passes must agree to the last bit
+    g = __fmul_rn(g, c);
+    v = __fmaf_rn(alpha, v, __fmul_rn(__fmul_rn(om, g), g));
+    x = __fsub_rn(x, __fdiv_rn(__fmul_rn(lr, g), __fadd_rn(sqrtf(v), eps)));
+}
 static __device__ __forceinline__ void rmsprop4(float4 &xx, float4 &vv, float4 gg, float c, float lr, float alpha,
                                                 float om, float eps)
 {
-    gg.x *= c; gg.y *= c; gg.z *= c; gg.w *= c;
-    vv.x = alpha * vv.x + om * gg.x * gg.x; vv.y = alpha * vv.y + om * gg.y * gg.y;
-    vv.z = alpha * vv.z + om * gg.z * gg.z; vv.w = alpha * vv.w + om * gg.w * gg.w;
-    xx.x -= lr * gg.x / (sqrtf(vv.x) + eps); xx.y -= lr * gg.y / (sqrtf(vv.y) + eps);
-    xx.z -= lr * gg.z / (sqrtf(vv.z) + eps); xx.w -= lr * gg.w / (sqrtf(vv.w) + eps);
+    rmsprop1(xx.x, vv.x, gg.x, c, lr, alpha, om, eps); rmsprop1(xx.y, vv.y, gg.y, c, lr, alpha, om, eps);
+    rmsprop1(xx.z, vv.z, gg.z, c, lr, alpha, om, eps); rmsprop1(xx.w, vv.w, gg.w, c, lr, alpha, om, eps);
 }
 
 // g_stride = d_pad: every agent applies its own gradient; 0: all agents apply the same one.
@@ -330,6 +335,18 @@ hipError_t launch_publish(int N, const Layout &L, const float *x, float *hist_sl
 // keeps its own parameters (Algorithm 1: average only when every in-peer's message is there).
 constexpr int MIX_MAX_IN = 8;
 
+// The mixing arithmetic, written with explicit roundings so that every kernel that mixes (the
+// separate pass and the two fused optimizer passes) rounds in the same places whatever the
+// compiler would otherwise contract: a <- w_self a, then a <- fma(w_j, m_j, a) peer by peer.
+static __device__ __forceinline__ void mix_scale(float4 &a, float w)
+{
+    a.x = __fmul_rn(a.x, w); a.y = __fmul_rn(a.y, w); a.z = __fmul_rn(a.z, w); a.w = __fmul_rn(a.w, w);
+}
+static __device__ __forceinline__ void mix_add(float4 &a, float w, float4 m)
+{
+    a.x = __fmaf_rn(w, m.x, a.x); a.y = __fmaf_rn(w, m.y, a.y); a.z = __fmaf_rn(w, m.z, a.z); a.w = __fmaf_rn(w, m.w, a.w);
+}
+
 __global__ __launch_bounds__(256) void mix_kernel(const float *__restrict__ x_in, float *x_out,
                                                   const float *__restrict__ hist, int N, long d_pad, int tau,
                                                   long round, int phase, int max_in,
@@ -359,11 +376,8 @@ __global__ __launch_bounds__(256) void mix_kernel(const float *__restrict__ x_in
     const long n4 = d_pad / 4;
     for (long e = (long)blockIdx.x * 256 + threadIdx.x; e < n4; e += (long)gridDim.x * 256) {
         float4 a = xi[e];
-        a.x *= w_self; a.y *= w_self; a.z *= w_self; a.w *= w_self;
-        for (int s = 0; s < n_in; ++s) {
-            const float4 m = reinterpret_cast<const float4 *>(src[s])[e];
-            a.x += w[s] * m.x; a.y += w[s] * m.y; a.z += w[s] * m.z; a.w += w[s] * m.w;
-        }
+        mix_scale(a, w_self);
+        for (int s = 0; s < n_in; ++s) mix_add(a, w[s], reinterpret_cast<const float4 *>(src[s])[e]);
         xo[e] = a;
     }
 }
@@ -420,7 +434,7 @@ __global__ __launch_bounds__(256) void rmsprop_mix_kernel(float *x, float *v, co
             if (peer[tab + s] >= 0 && round - delay[tab + s] < 0) complete = false;
         float4 a = u[i * COLS4 + col];
         const float w_self = complete ? weight[((long)phase * N + i) * (max_in + 1)] : 1.f;
-        a.x *= w_self; a.y *= w_self; a.z *= w_self; a.w *= w_self;
+        mix_scale(a, w_self);
         if (complete)
             for (int s = 0; s < max_in; ++s) {
                 const int j = peer[tab + s];
@@ -430,7 +444,7 @@ __global__ __launch_bounds__(256) void rmsprop_mix_kernel(float *x, float *v, co
                 const float4 m = dl == 0 ? u[j * COLS4 + col]
                                          : reinterpret_cast<const float4 *>(
                                                hist + ((round - dl) % (tau + 1)) * (long)N * d_pad)[(long)j * n4 + e];
-                a.x += w * m.x; a.y += w * m.y; a.z += w * m.z; a.w += w * m.w;
+                mix_add(a, w, m);
             }
         reinterpret_cast<float4 *>(x)[(long)i * n4 + e] = a;
     }
@@ -466,8 +480,8 @@ __global__ __launch_bounds__(256) void rmsprop_mix_cycle_kernel(float *x, float 
     auto mix_store = [&](int agent, float4 own, float4 msg) {
         const float ws = weight[agent * 2], wp = weight[agent * 2 + 1];
         float4 a = own;
-        a.x *= ws; a.y *= ws; a.z *= ws; a.w *= ws;
-        a.x += wp * msg.x; a.y += wp * msg.y; a.z += wp * msg.z; a.w += wp * msg.w;
+        mix_scale(a, ws);
+        mix_add(a, wp, msg);
         reinterpret_cast<float4 *>(x)[(long)agent * n4 + e] = a;
     };
     int prev_agent = order[b0];

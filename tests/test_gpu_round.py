@@ -37,14 +37,41 @@ def _explicit_two_peer_tables(N, phases):
     return peers, weights
 
 
+def _explicit_one_peer_tables(N, phases, permutation):
+    """One in-peer per agent and phase with unequal weights.  permutation: every agent is the
+    in-peer of exactly one agent (a random permutation: cycles of different lengths);
+    otherwise two agents listen to the same peer and one agent to nobody."""
+    rng = np.random.default_rng(5 + N)
+    peers = np.zeros((phases, N, 1), dtype=np.int32)
+    weights = np.zeros((phases, N, 2), dtype=np.float32)
+    for p in range(phases):
+        perm = rng.permutation(N)
+        peers[p, :, 0] = perm
+        w_self = rng.uniform(0.2, 0.8, size=N).astype(np.float32)
+        weights[p, :, 0] = w_self
+        weights[p, :, 1] = np.float32(1.0) - w_self
+    if not permutation:
+        peers[0, 0, 0] = peers[0, 1, 0]
+        peers[1, 2, 0] = -1
+        weights[1, 2] = [1.0, 0.0]
+    return peers, weights
+
+
 @pytest.mark.parametrize("N,topology,tau", [(4, "exp", 0), (8, "exp", 2), (3, "ring", 1), (5, "explicit", 0),
-                                            (6, "explicit", 2)])
+                                            (6, "explicit", 2), (5, "ring", 0), (16, "exp", 0), (1, "ring", 0),
+                                            (9, "one_peer_permutation", 0), (9, "one_peer_shared", 0),
+                                            (6, "one_peer_permutation", 1)])
 def test_round_equals_learner_step_then_gossip(N, topology, tau):
     """Same arithmetic in the same order: the fused call must give the parameters and the
-    RMSprop state of the two-call sequence to the last bit, round after round."""
+    RMSprop state of the two-call sequence to the last bit, round after round.  One-peer
+    topologies without delays whose peers form a permutation take the cycle-walking kernel
+    (ring, exponential graph, explicit permutations); the others the general fused kernel."""
     kw = {}
     if topology == "explicit":
         kw["peers"], kw["weights"] = _explicit_two_peer_tables(N, 3)
+    elif topology.startswith("one_peer"):
+        kw["peers"], kw["weights"] = _explicit_one_peer_tables(N, 2, topology.endswith("permutation"))
+        topology = "explicit"
     net, fused, split, X0 = _pair(N, 6, 2, 3, topology, tau, **kw)
     for r in range(5):
         dev = upload(gs.rollout(net, N, 2, 3, 900 + r))

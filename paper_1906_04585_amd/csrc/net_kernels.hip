@@ -811,7 +811,7 @@ __global__ __launch_bounds__(256) void heads_wgrad_kernel(const float *__restric
 
 static inline int cdiv(long a, long b) { return (int)((a + b - 1) / b); }
 
-constexpr int FC_KCHUNK = 448;          // 3136 = 7 * 448
+constexpr int FC_KCHUNK = 784;          // 3136 = 4 * 784
 constexpr int FC_KCHUNK_SMALL = 224;    // few frames: twice the splits, so that enough workgroups stream the weights
 constexpr int FC_SMALL_FRAMES = 32;
 constexpr int FPS_CONV1 = 2, FPS_CONV2 = 8, FPS_CONV3 = 16;   // frames per split of the weight gradients

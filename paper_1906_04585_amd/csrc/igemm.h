@@ -65,6 +65,10 @@
 //                                           quad of rows (bf16 tiles, m-contiguous A): one call
 //                                           fetch_a_block(ctx of the first group, k0, raw[PA], ok[PA])
 //                                           loads all of the thread's groups, group i at local k + i
+//   static constexpr bool A_EXACT_BF16      optional: every A value is exactly representable in bf16 (a byte
+//                                           image); an fp32 run then takes mode 2
+//   static constexpr bool SPLIT3            optional: an fp32 run takes mode 3 (both operands as three bf16
+//                                           pieces) instead of fp32 MFMAs; set where that is measured faster
 //   static constexpr bool SUMSQ             optional: the workgroup also delivers the sum of
 //                                           squares of what it stored, through
 //                                           template <bool CHECK> float sumsq4(m, n, v) (the share of
@@ -150,14 +154,18 @@ static __device__ __forceinline__ void gala_pieces4(const float (&r)[4], unsigne
 //   consecutive k as 8 bytes, and each 16x16 block takes one v_mfma_f32_16x16x16_bf16 per 16 k.
 // MODE 2: for problems whose A operand is exactly representable in bf16 (P::A_EXACT_BF16: byte
 //   images, integers 0..255 have eight significant bits).  A is staged as in MODE 1 without any
-//   rounding error, B is staged as three bf16 pieces that add up to the fp32 value, and each
-//   block takes three bf16 MFMAs per 16 k.  Every product is exact in fp32 and the accumulation
-//   is fp32, so the result is as accurate as the fp32 MFMA path at a fraction of its matrix time.
-// MODE 3: both operands are staged as three bf16 pieces.  With a = a0 + a1 + a2 and b = b0 + b1 + b2
-//   the six products a_p b_q with p + q <= 2 carry the product to 2^-24 of |a||b| (the three
-//   left out are below fp32 rounding); each bf16 product is exact in fp32 and the accumulation is
-//   fp32, smallest pieces first.  Six bf16 MFMAs per 16 k take 3/8 of the matrix time of the four
-//   fp32 MFMAs they replace.
+//   rounding error, B is staged as three bf16 pieces b0 + b1 + b2 that add up to the fp32 value.
+//   Every product is exact in fp32 and the accumulation is fp32, so the result is as accurate as
+//   the fp32 MFMA path at a fraction of its matrix time.  Per block and 16 k: one 16x16x32
+//   instruction that takes the same four k of b2 and b1 (eight k per lane: two piece products
+//   at once), then one 16x16x16 instruction for a b0.
+// MODE 3: both operands are staged as three bf16 pieces (each the round-to-nearest bf16 of what
+//   the previous ones left over; the leftovers are exact).  With a = a0 + a1 + a2 and
+//   b = b0 + b1 + b2 the six products a_p b_q with p + q <= 2 carry the product to 2^-26 of
+//   |a||b| (the three left out are below fp32 rounding); each bf16 product is exact in fp32 and
+//   the accumulation is fp32, small pieces first.  Three 16x16x32 instructions per block and
+//   16 k, each adding two piece products, take 3/8 of the matrix time of the four fp32 MFMAs
+//   they replace.
 template <class P, int MODE>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MODE == 3 ? 2 : 4))) void igemm_kernel(P p, int n_agents)
 {

@@ -213,7 +213,7 @@ extern "C" int gala_create(gala_ctx **out, int n_agents, const gala_topology *to
     ALLOC_ZP(b.a3, N * F * A3SZ); ALLOC_ZP(b.h, N * F * FC);
     ALLOC(b.logits, N * M * A, true); ALLOC(b.values, N * F, true);
     ALLOC(b.ret, N * M, true); ALLOC(b.adv, N * M, true);
-    ALLOC(b.dlogits, N * M * A, false); ALLOC(b.dvalues, N * M, false);
+    ALLOC(b.dlogits, N * M * A, false); ALLOC(b.dvalues, N * M, false); ALLOC(b.loss_part, N * M * 3, false);
     ALLOC_ZP(b.dzh, N * M * FC); ALLOC_ZP(b.dz3, N * M * A3SZ);
     ALLOC_ZP(b.dz2, N * M * A2SZ); ALLOC_ZP(b.dz1, N * M * A1SZ);
 #undef ALLOC_ZP
@@ -324,7 +324,7 @@ static int enqueue_gradients(gala_ctx *c, const uint8_t *obs_u8, const int32_t *
     pt->begin();
     HIP_OK(c, launch_forward(a, c->stream, pt));
     HIP_OK(c, launch_loss(a, c->hp, actions, rewards, dones, c->stream));
-    pt->mark("returns_loss");
+    pt->mark("loss_heads_dgrad");
     HIP_OK(c, launch_backward(a, c->stream, pt, &c->side));
     if (own_norm) {
         HIP_OK(c, launch_grad_norm(c->N, c->L, c->hp, c->b.g, c->b.norm_part, c->b.stats, c->stream));

@@ -79,6 +79,7 @@ struct Buffers {
     float *logits, *values;           // [N][M][A], [N][F]
     float *ret, *adv;                 // [N][M]
     float *dlogits, *dvalues;         // [N][M][A], [N][M]
+    float *loss_part;                 // [N][M][3]: per-sample policy term, squared value error, entropy
     float *dzh, *dz3, *dz2, *dz1;     // [N][M][..] pre-activation gradients
     float *ws;                        // split-K partial sums
     float *norm_part;                 // [N][NORM_PARTS]
@@ -138,8 +139,11 @@ struct NetArgs {
 };
 
 hipError_t launch_forward(const NetArgs &a, hipStream_t s, PhaseTimer *pt);
+// returns, advantages, loss terms per sample, head output gradients and the hidden layer's dzh
 hipError_t launch_loss(const NetArgs &a, const HParams &hp, const int32_t *actions, const float *rewards,
                        const uint8_t *dones, hipStream_t s);
+// the three loss terms of every agent from the per-sample terms (any stream ordered after launch_loss)
+hipError_t launch_loss_stats(const NetArgs &a, hipStream_t s);
 hipError_t launch_sample(int N, int Bn, int A, const float *logits, const float *values, uint64_t seed, long step,
                          int32_t *actions, float *values_out, float *logp_out, hipStream_t s);
 // Second stream (default priority) and the events that order it against the context's stream.

@@ -69,6 +69,8 @@
 //                                           image); an fp32 run then takes mode 2
 //   static constexpr bool SPLIT3            optional: an fp32 run takes mode 3 (both operands as three bf16
 //                                           pieces) instead of fp32 MFMAs; set where that is measured faster
+//   static constexpr int  PREFETCH          k-tiles of global loads in flight ahead of the MFMAs: 1, or 2 with a
+//                                           second set of load registers
 //   static constexpr bool SUMSQ             optional: the workgroup also delivers the sum of
 //                                           squares of what it stored, through
 //                                           template <bool CHECK> float sumsq4(m, n, v) (the share of
@@ -240,11 +242,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MODE == 3 ?
 
     constexpr int GA = BM * BK / 4, GB = BN * BK / 4;       // groups of four per tile
     constexpr int PA = (GA + 255) / 256, PB = (GB + 255) / 256;
-    typename P::ARaw ra[PA];
-    typename P::BRaw rb[PB];
+    // Global loads run PF k-tiles ahead of the MFMAs, one register set per tile in flight.
+    constexpr int PF = P::PREFETCH;
+    static_assert(PF == 1 || PF == 2, "one or two k-tiles of loads in flight");
+    typename P::ARaw ra[PF][PA];
+    typename P::BRaw rb[PF][PB];
     typename P::CtxA ca[PA];
     typename P::CtxB cb[PB];
-    bool oka[PA], okb[PB];
+    bool oka[PF][PA], okb[PF][PB];
     static_assert(!P::SUM_A || (!P::A_KC && 256 % (BM / 4) == 0), "SUM_A needs m-contiguous groups");
     static_assert(!P::SUM_B || (!P::B_KC && 256 % (BN / 4) == 0), "SUM_B needs n-contiguous groups");
     static_assert(!P::SUM_A || (BM / 4) % (256 / BK) == 0 || PA == 1, "SUM_A: one pass unless k is shared");
@@ -283,7 +288,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MODE == 3 ?
 #pragma unroll
     for (int i = 0; i < PA; ++i) {
         const int g = tid + i * 256;
-        oka[i] = true;
+#pragma unroll
+        for (int st = 0; st < PF; ++st) oka[st][i] = true;
         if (GA % 256 == 0 || g < GA) {
             if (P::A_KC) p.prep_a(ca[i], m0 + g / (BK / 4), (g % (BK / 4)) * 4);
             else { int kl, q; map_a(i, kl, q); p.prep_a(ca[i], m0 + q * 4, kl); }
@@ -292,38 +298,41 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MODE == 3 ?
 #pragma unroll
     for (int i = 0; i < PB; ++i) {
         const int g = tid + i * 256;
-        okb[i] = true;
+#pragma unroll
+        for (int st = 0; st < PF; ++st) okb[st][i] = true;
         if (GB % 256 == 0 || g < GB) {
             if (P::B_KC) p.prep_b(cb[i], (g % (BK / 4)) * 4, n0 + g / (BK / 4));
             else { int kl, q; map_mc(QB{}, i, kl, q); p.prep_b(cb[i], kl, n0 + q * 4); }
         }
     }
 
-    auto fetch = [&](int k0) {
-        if constexpr (KCONS_A && P::BLOCK_FETCH_A) p.fetch_a_block(ca[0], k0, ra, oka);
+    auto fetch = [&](auto setc, int k0) {
+        constexpr int st = decltype(setc)::value;
+        if constexpr (KCONS_A && P::BLOCK_FETCH_A) p.fetch_a_block(ca[0], k0, ra[st], oka[st]);
         else {
 #pragma unroll
             for (int i = 0; i < PA; ++i) {
                 const int g = tid + i * 256;
-                if (GA % 256 == 0 || g < GA) ra[i] = p.fetch_a(ca[i], k0, oka[i]);
+                if (GA % 256 == 0 || g < GA) ra[st][i] = p.fetch_a(ca[i], k0, oka[st][i]);
             }
         }
 #pragma unroll
         for (int i = 0; i < PB; ++i) {
             const int g = tid + i * 256;
-            if (GB % 256 == 0 || g < GB) rb[i] = p.fetch_b(cb[i], k0, okb[i]);
+            if (GB % 256 == 0 || g < GB) rb[st][i] = p.fetch_b(cb[i], k0, okb[st][i]);
         }
     };
-    auto stage = [&](auto bufc) {
+    auto stage = [&](auto bufc, auto setc) {
         constexpr int buf = decltype(bufc)::value;
+        constexpr int st = decltype(setc)::value;
         if constexpr (KCONS_A) {
             float rr[PA][4];
 #pragma unroll
             for (int i = 0; i < PA; ++i) {
-                p.decode_a(rr[i], ra[i], oka[i]);
+                p.decode_a(rr[i], ra[st][i], oka[st][i]);
                 if (P::A_ZERO) {
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) rr[i][j] = oka[i] ? rr[i][j] : 0.f;
+                    for (int j = 0; j < 4; ++j) rr[i][j] = oka[st][i] ? rr[i][j] : 0.f;
                 }
             }
             int kl, q; map_a(0, kl, q);
@@ -344,10 +353,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MODE == 3 ?
             const int g = tid + i * 256;
             if (!KCONS_A && (GA % 256 == 0 || g < GA)) {
                 float r[4];
-                p.decode_a(r, ra[i], oka[i]);
+                p.decode_a(r, ra[st][i], oka[st][i]);
                 if (P::A_ZERO) {
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) r[j] = oka[i] ? r[j] : 0.f;
+                    for (int j = 0; j < 4; ++j) r[j] = oka[st][i] ? r[j] : 0.f;
                 }
                 if (BF16 && P::A_KC) {
                     const int row = g / (BK / 4), kq = g % (BK / 4);
@@ -386,10 +395,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MODE == 3 ?
             const int g = tid + i * 256;
             if (GB % 256 == 0 || g < GB) {
                 float r[4];
-                p.decode_b(r, rb[i], okb[i]);
+                p.decode_b(r, rb[st][i], okb[st][i]);
                 if (P::B_ZERO) {
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) r[j] = okb[i] ? r[j] : 0.f;
+                    for (int j = 0; j < 4; ++j) r[j] = okb[st][i] ? r[j] : 0.f;
                 }
                 if (BF16 && P::B_KC) {
                     const int col = g / (BK / 4), kq = g % (BK / 4);
@@ -436,8 +445,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MODE == 3 ?
     const int lr = lane % MB, lk = lane / MB;
     const int nkt = p.n_ktiles(BK);
     if (nkt > 0) {
-        fetch(p.ktile_k0(0, BK));
-        stage(std::integral_constant<int, 0>{});
+        fetch(std::integral_constant<int, 0>{}, p.ktile_k0(0, BK));
+        if (PF == 2 && nkt > 1) fetch(std::integral_constant<int, PF - 1>{}, p.ktile_k0(1, BK));
+        stage(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
     }
     __syncthreads();
     // One k-tile: request the next tile, run this tile's MFMAs out of buffer `buf`, stage the
@@ -445,7 +455,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MODE == 3 ?
     // unrolled by two) so that every LDS address is a per-lane base plus an immediate.
     auto tile_step = [&](auto bufc, int kt) {
         constexpr int buf = decltype(bufc)::value;
-        if (kt + 1 < nkt) fetch(p.ktile_k0(kt + 1, BK));
+        // tile kt sits in LDS buffer kt % 2 and came through register set kt % PF
+        if (kt + PF < nkt) fetch(std::integral_constant<int, PF == 2 ? buf : 0>{}, p.ktile_k0(kt + PF, BK));
         // keep the global loads of the next tile ahead of this tile's MFMAs: without the fence
         // the scheduler sinks them next to their first use and their latency is exposed
         __builtin_amdgcn_sched_barrier(0);
@@ -528,7 +539,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MODE == 3 ?
                     for (int j = 0; j < BJ; ++j) acc[i][j] = Blk::mma(a[i], b[j], acc[i][j]);
             }
         }
-        if (kt + 1 < nkt) stage(std::integral_constant<int, buf ^ 1>{});
+        if (kt + 1 < nkt) stage(std::integral_constant<int, buf ^ 1>{}, std::integral_constant<int, PF == 2 ? buf ^ 1 : 0>{});
         __syncthreads();
     };
     for (int kt = 0; kt < nkt; kt += 2) {

@@ -22,46 +22,47 @@ static __device__ __forceinline__ float block_sum_256(float v, float *red)
     return (red[0] + red[1]) + (red[2] + red[3]);
 }
 
-// ---- Algorithm 1, "compute returns and advantages" + loss of Eq. (1) and Eq. (4) -------------
-// One workgroup per agent.
+// ---- Algorithm 1, "compute returns and advantages" + loss of Eq. (1) and Eq. (4), and the gradient
+// that the two heads send back into the hidden layer -------------------------------------------------
 //   G_t = r_t + gamma (1 - done_t) G_{t+1},  G_T = V(state after the last action);  A_t = G_t - V_t
 //   loss = mean(-log pi(a_t|s_t) A_t) + c_v mean((G_t - V_t)^2) - eta mean(H_t),  G and A constants
 //   dloss/dz_k = [A (pi_k - 1[k = a]) + eta pi_k (log pi_k + H)] / M,   dloss/dV = -2 c_v (G - V) / M
-// (pi_a - 1 is formed as -sum_{k != a} pi_k)
+//   (pi_a - 1 is formed as -sum_{k != a} pi_k)
+//   dzh[f][j] = (sum_a W_pi[a][j] dlogits[f][a] + w_v[j] dvalue[f]) * (h[f][j] > 0)
+// One workgroup per (LOSS_FRAMES samples, agent), one wavefront per sample and one lane per action
+// for the loss part: every wavefront walks its simulator's rollout back from the last step to its
+// own (at most T steps) instead of waiting for a pass over the whole rollout.  The per-sample loss
+// terms go to loss_part[agent][sample][3] and are summed by loss_stats_kernel in sample order.
+// Then a thread owns one hidden column j, reads each head weight once and applies it to all
+// LOSS_FRAMES samples, whose output gradients sit in LDS.
 constexpr int MAX_ACTIONS = 64;
-constexpr int LOSS_THREADS = 1024;
+constexpr int LOSS_FRAMES = 8;
+constexpr int LOSS_THREADS = 64 * LOSS_FRAMES;
+static_assert(LOSS_THREADS == FC, "one thread per hidden column");
 
-__global__ __launch_bounds__(LOSS_THREADS) void loss_kernel(int T, int Bn, int A, float gamma, float vf_coef,
-                                                            float ent_coef, const float *__restrict__ logits,
-                                                            const float *__restrict__ values,
-                                                            const int32_t *__restrict__ actions,
-                                                            const float *__restrict__ rewards,
-                                                            const uint8_t *__restrict__ dones, float *ret, float *adv,
-                                                            float *dlogits, float *dvalues, float *stats)
+__global__ __launch_bounds__(LOSS_THREADS) void loss_heads_kernel(
+    int T, int Bn, float gamma, float vf_coef, float ent_coef, Layout L, const float *__restrict__ logits,
+    const float *__restrict__ values, const int32_t *__restrict__ actions, const float *__restrict__ rewards,
+    const uint8_t *__restrict__ dones, const float *__restrict__ h, const float *__restrict__ x, float *ret,
+    float *adv, float *dlogits, float *dvalues, float *loss_part, float *dzh)
 {
-    constexpr int NW = LOSS_THREADS / 64;
-    __shared__ float red[3][NW];
-    const int agent = blockIdx.x;
+    __shared__ float dl[LOSS_FRAMES][MAX_ACTIONS + 1];   // [sample][action], value gradient in slot A
+    const int A = L.n_actions;
+    const int agent = blockIdx.y, f0 = blockIdx.x * LOSS_FRAMES;
     const int M = T * Bn, F = M + Bn;
     const float *V = values + (long)agent * F;
-    float *G = ret + (long)agent * M, *Ad = adv + (long)agent * M;
-    // one thread per environment walks its rollout backwards
-    for (int b = threadIdx.x; b < Bn; b += blockDim.x) {
-        float next = V[M + b];
-        for (int t = T - 1; t >= 0; --t) {
-            const long i = (long)agent * M + t * Bn + b;
-            const float keep = dones[i] ? 0.f : 1.f;
-            next = rewards[i] + gamma * keep * next;
-            G[t * Bn + b] = next;
-            Ad[t * Bn + b] = next - V[t * Bn + b];
-        }
-    }
-    __syncthreads();
-    // one wavefront per sample, one lane per action
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int m = f0 + wave;
     const float inv_m = 1.0f / (float)M;
-    float pg = 0.f, td = 0.f, ent = 0.f;       // accumulated identically in every lane
-    for (int m = wave; m < M; m += NW) {
+    if (m < M) {
+        const int b = m % Bn, t = m / Bn;
+        float G = V[M + b];
+        for (int tt = T - 1; tt >= t; --tt) {
+            const long i = (long)agent * M + tt * Bn + b;
+            const float keep = dones[i] ? 0.f : 1.f;
+            G = rewards[i] + gamma * keep * G;
+        }
+        const float Vm = V[m], Am = G - Vm;
         const bool on = lane < A;
         const float z = on ? logits[((long)agent * M + m) * A + lane] : -INFINITY;
         float zmax = z;
@@ -78,30 +79,65 @@ __global__ __launch_bounds__(LOSS_THREADS) void loss_kernel(int T, int Bn, int A
         const float lp_act = __shfl(lp, act, 64);
         // pi_a - 1 for the taken action as minus the sum of the other probabilities (no cancellation)
         const float not_act = wave_sum((on && lane != act) ? p : 0.f);
-        const float Am = Ad[m], Gm = G[m], Vm = V[m];
-        pg += -lp_act * Am;
-        td += (Gm - Vm) * (Gm - Vm);
-        ent += H;
-        if (on)
-            dlogits[((long)agent * M + m) * A + lane] =
-                (Am * (lane == act ? -not_act : p) + ent_coef * p * (lp + H)) * inv_m;
-        if (lane == 0) dvalues[(long)agent * M + m] = -2.f * vf_coef * (Gm - Vm) * inv_m;
+        if (on) {
+            const float d = (Am * (lane == act ? -not_act : p) + ent_coef * p * (lp + H)) * inv_m;
+            dlogits[((long)agent * M + m) * A + lane] = d;
+            dl[wave][lane] = d;
+        }
+        if (lane == 0) {
+            const float dv = -2.f * vf_coef * (G - Vm) * inv_m;
+            dvalues[(long)agent * M + m] = dv;
+            dl[wave][A] = dv;
+            ret[(long)agent * M + m] = G;
+            adv[(long)agent * M + m] = Am;
+            float *lp3 = loss_part + ((long)agent * M + m) * 3;
+            lp3[0] = -lp_act * Am; lp3[1] = (G - Vm) * (G - Vm); lp3[2] = H;
+        }
+    } else if (lane <= A) {
+        dl[wave][lane] = 0.f;
     }
-    if (lane == 0) { red[0][wave] = pg; red[1][wave] = td; red[2][wave] = ent; }
     __syncthreads();
-    if (threadIdx.x < 3) {
-        float t = 0.f;
-        for (int w = 0; w < NW; ++w) t += red[threadIdx.x][w];
-        stats[agent * 5 + threadIdx.x] = t * inv_m;
+    const float *xa = x + agent * L.d_pad;
+    const int j = threadIdx.x;
+    float acc[LOSS_FRAMES];
+    const float wv = xa[L.vw + j];
+#pragma unroll
+    for (int fi = 0; fi < LOSS_FRAMES; ++fi) acc[fi] = wv * dl[fi][A];
+    for (int a = 0; a < A; ++a) {
+        const float w = xa[L.piw + (long)a * FC + j];
+#pragma unroll
+        for (int fi = 0; fi < LOSS_FRAMES; ++fi) acc[fi] += w * dl[fi][a];
     }
+#pragma unroll
+    for (int fi = 0; fi < LOSS_FRAMES; ++fi) {
+        const int f = f0 + fi;
+        if (f < M) dzh[((long)agent * M + f) * FC + j] = h[((long)agent * F + f) * FC + j] > 0.f ? acc[fi] : 0.f;
+    }
+}
+
+// stats[agent][0..2] = means over the agent's samples of the policy term, the squared value error and
+// the entropy: one wavefront per agent and term, samples taken in order (lane l: l, l + 64, ...).
+__global__ __launch_bounds__(192) void loss_stats_kernel(int M, const float *__restrict__ loss_part, float *stats)
+{
+    const int agent = blockIdx.x, term = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    float t = 0.f;
+    for (int m = lane; m < M; m += 64) t += loss_part[((long)agent * M + m) * 3 + term];
+    t = wave_sum(t);
+    if (lane == 0) stats[agent * 5 + term] = t * (1.0f / (float)M);
 }
 
 hipError_t launch_loss(const NetArgs &a, const HParams &hp, const int32_t *actions, const float *rewards,
                        const uint8_t *dones, hipStream_t s)
 {
-    hipLaunchKernelGGL(loss_kernel, dim3(a.N), dim3(LOSS_THREADS), 0, s, hp.T, hp.B, a.L.n_actions, hp.gamma, hp.vf_coef,
-                       hp.ent_coef, a.b.logits, a.b.values, actions, rewards, dones, a.b.ret, a.b.adv,
-                       a.b.dlogits, a.b.dvalues, a.b.stats);
+    hipLaunchKernelGGL(loss_heads_kernel, dim3((a.M + LOSS_FRAMES - 1) / LOSS_FRAMES, a.N), dim3(LOSS_THREADS), 0, s,
+                       hp.T, hp.B, hp.gamma, hp.vf_coef, hp.ent_coef, a.L, a.b.logits, a.b.values, actions, rewards,
+                       dones, a.b.h, a.x, a.b.ret, a.b.adv, a.b.dlogits, a.b.dvalues, a.b.loss_part, a.b.dzh);
+    return hipGetLastError();
+}
+
+hipError_t launch_loss_stats(const NetArgs &a, hipStream_t s)
+{
+    hipLaunchKernelGGL(loss_stats_kernel, dim3(a.N), dim3(192), 0, s, a.M, a.b.loss_part, a.b.stats);
     return hipGetLastError();
 }
 

@@ -61,6 +61,7 @@ struct ProblemBase {
     static constexpr bool SUM_A = false, SUM_B = false, HAS_AUX = false, A_ZERO = false, B_ZERO = false;
     static constexpr bool SUMSQ = false;
     static constexpr bool A_EXACT_BF16 = false;   // true: every A value is an integer 0..255 (a byte image)
+    static constexpr int PREFETCH = 1;            // k-tiles of global loads in flight (1 or 2)
     static constexpr bool SPLIT3 = false;         // true: fp32 accuracy from three bf16 pieces of both operands
     static constexpr int TABLE = 0;
     static constexpr bool BLOCK_FETCH_A = false;
@@ -90,6 +91,7 @@ struct Conv1Fwd : ProblemBase {
     static constexpr int BM = 256, BN = 32, BK = 16, WM = 4, WN = 1;
     static constexpr bool A_KC = true, B_KC = false;
     static constexpr bool A_EXACT_BF16 = true;
+    static constexpr int PREFETCH = 2;            // little work per k-tile (byte loads, K = 256): 3 % faster; slower elsewhere
     typedef uint32_t ARaw;
     struct CtxA { const uint8_t *ptr; };
     const uint8_t *obs, *boot;
@@ -730,46 +732,6 @@ __global__ __launch_bounds__(128) void fc_reduce_heads_kernel(const float *__res
     }
 }
 
-constexpr int HEAD_FRAMES = 8;
-
-// dzh[f][j] = (sum_a W_pi[a][j] dlogits[f][a] + w_v[j] dvalue[f]) * (h[f][j] > 0)
-// One workgroup per (HEAD_FRAMES frames, agent): a thread owns two columns j, reads each head
-// weight once and applies it to all eight frames, whose output gradients sit in LDS.
-__global__ __launch_bounds__(256) void heads_dgrad_kernel(const float *__restrict__ h, const float *__restrict__ x,
-                                                          Layout L, int M, int F, const float *__restrict__ dlogits,
-                                                          const float *__restrict__ dvalues, float *dzh)
-{
-    __shared__ float dl[HEAD_FRAMES][65];                 // [frame][action], value gradient in the last used slot
-    const int f0 = blockIdx.x * HEAD_FRAMES, agent = blockIdx.y, t = threadIdx.x;
-    const float *xa = x + agent * L.d_pad;
-    const int A = L.n_actions;
-    for (int e = t; e < HEAD_FRAMES * (A + 1); e += 256) {
-        const int fi = e / (A + 1), a = e % (A + 1), f = f0 + fi;
-        float v = 0.f;
-        if (f < M) v = a < A ? dlogits[((long)agent * M + f) * A + a] : dvalues[(long)agent * M + f];
-        dl[fi][a] = v;
-    }
-    __syncthreads();
-#pragma unroll
-    for (int jj = 0; jj < FC / 256; ++jj) {
-        const int j = t + jj * 256;
-        float acc[HEAD_FRAMES];
-        const float wv = xa[L.vw + j];
-#pragma unroll
-        for (int fi = 0; fi < HEAD_FRAMES; ++fi) acc[fi] = wv * dl[fi][A];
-        for (int a = 0; a < A; ++a) {
-            const float w = xa[L.piw + (long)a * FC + j];
-#pragma unroll
-            for (int fi = 0; fi < HEAD_FRAMES; ++fi) acc[fi] += w * dl[fi][a];
-        }
-#pragma unroll
-        for (int fi = 0; fi < HEAD_FRAMES; ++fi) {
-            const int f = f0 + fi;
-            if (f < M) dzh[((long)agent * M + f) * FC + j] = h[((long)agent * F + f) * FC + j] > 0.f ? acc[fi] : 0.f;
-        }
-    }
-}
-
 // Head parameter gradients: row a < A of W_pi (and b_pi[a]); row A = value head.  One thread
 // per (row, column j); frames are summed in four interleaved chains, combined in a fixed order.
 __global__ __launch_bounds__(256) void heads_wgrad_kernel(const float *__restrict__ h, Layout L, int M, int F,
@@ -898,11 +860,10 @@ hipError_t launch_backward(const NetArgs &a, hipStream_t s, PhaseTimer *pt, cons
         GALA_TRY(hipEventRecord(e, s));
         return hipStreamWaitEvent(w, e, 0);
     };
-    hipLaunchKernelGGL(heads_dgrad_kernel, dim3(cdiv(a.M, HEAD_FRAMES), a.N), dim3(256), 0, s, a.b.h, a.x, L, a.M,
-                       a.F, a.b.dlogits, a.b.dvalues, a.b.dzh);
-    GALA_TRY(hipGetLastError());
-    pt->mark("heads_dgrad");
+    // dzh came with the loss; the loss terms' means are off the data-gradient chain
     GALA_TRY(publish());
+    GALA_TRY(launch_loss_stats(a, w));
+    pt->mark("loss_stats");
     hipLaunchKernelGGL(heads_wgrad_kernel, dim3(L.n_actions + 1, a.N, FC / 256), dim3(256), 0, w, a.b.h, L, a.M, a.F,
                        a.b.dlogits, a.b.dvalues, a.b.g);
     GALA_TRY(hipGetLastError());

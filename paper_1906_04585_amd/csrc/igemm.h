@@ -163,8 +163,9 @@ static __device__ __forceinline__ void gala_pieces4(const float (&r)[4], unsigne
 //   at once), then one 16x16x16 instruction for a b0.
 // MODE 3: both operands are staged as three bf16 pieces (each the round-to-nearest bf16 of what
 //   the previous ones left over; the leftovers are exact).  With a = a0 + a1 + a2 and
-//   b = b0 + b1 + b2 the six products a_p b_q with p + q <= 2 carry the product to 2^-26 of
-//   |a||b| (the three left out are below fp32 rounding); each bf16 product is exact in fp32 and
+//   b = b0 + b1 + b2 the six products a_p b_q with p + q <= 2 carry the product to 2^-24 of
+//   |a||b| (what the three left out add up to at most: half a unit of fp32 round-off of the
+//   product); each bf16 product is exact in fp32 and
 //   the accumulation is fp32, small pieces first.  Three 16x16x32 instructions per block and
 //   16 k, each adding two piece products, take 3/8 of the matrix time of the four fp32 MFMAs
 //   they replace.

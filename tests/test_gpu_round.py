@@ -156,15 +156,45 @@ def test_round_rejects_what_gossip_rejects():
     gpu.round(dev["obs"], dev["actions"], dev["rewards"], dev["dones"], dev["boot_obs"], 0)
 
 
-@pytest.mark.parametrize("N", [72, 130])
-def test_round_many_agents_narrower_column_blocks(N):
-    """Above 64 agents the fused kernel's column block narrows (32, then 16 float4 columns)
-    so that its LDS tile still fits; the result stays that of the two-call sequence."""
-    net, fused, split, X0 = _pair(N, 6, 1, 2, "ring", 0, seed=5)
-    for r in range(2):
+@pytest.mark.parametrize("N,tau", [(72, 1), (130, 1), (72, 0), (130, 0)])
+def test_round_many_agents(N, tau):
+    """With delays the general fused kernel runs, and above 64 agents its column block narrows
+    (32, then 16 float4 columns) so that its LDS tile still fits; without delays the ring takes
+    the cycle-walking kernel (one cycle of N agents).  Either way the result stays that of the
+    two-call sequence."""
+    net, fused, split, X0 = _pair(N, 6, 1, 2, "ring", tau, seed=5)
+    for r in range(3):
         dev = upload(gs.rollout(net, N, 1, 2, 300 + r))
         fused.round(dev["obs"], dev["actions"], dev["rewards"], dev["dones"], dev["boot_obs"], r)
         split.learner_step(dev["obs"], dev["actions"], dev["rewards"], dev["dones"], dev["boot_obs"])
         split.gossip(r)
         np.testing.assert_array_equal(fused.get_opt_state(), split.get_opt_state())
         np.testing.assert_array_equal(fused.get_params(), split.get_params())
+
+
+def test_single_stream_and_event_timing_give_the_same_bits(monkeypatch):
+    """The weight gradients normally run on an internal second stream; GALA_SINGLE_STREAM=1 at
+    creation and the per-kernel event timing both put everything on one stream.  Same kernels,
+    same order of arithmetic: identical gradients, statistics, optimizer state and parameters."""
+    from paper_1906_04585_amd import Gala
+    N, A, T, B = 4, 6, 3, 4
+    net = gs.make_net(A)
+    X0 = gs.init_params(net, N, seed=33, bias_scale=0.05)
+    two = Gala(N, A, T, B, HP, "exp")
+    timed = Gala(N, A, T, B, HP, "exp")
+    timed.set_profiling(True)
+    monkeypatch.setenv("GALA_SINGLE_STREAM", "1")
+    one = Gala(N, A, T, B, HP, "exp")
+    monkeypatch.delenv("GALA_SINGLE_STREAM")
+    for g in (two, timed, one):
+        g.set_params(X0)
+    for r in range(3):
+        dev = upload(gs.rollout(net, N, T, B, 700 + r))
+        for g in (two, timed, one):
+            g.round(dev["obs"], dev["actions"], dev["rewards"], dev["dones"], dev["boot_obs"], r)
+        for other in (timed, one):
+            np.testing.assert_array_equal(other.get_grads(), two.get_grads())
+            np.testing.assert_array_equal(other.get_step_stats(), two.get_step_stats())
+            np.testing.assert_array_equal(other.get_opt_state(), two.get_opt_state())
+            np.testing.assert_array_equal(other.get_params(), two.get_params())
+    assert set(timed.get_phase_times()) >= {"conv1_fwd", "loss_heads_dgrad", "clip_rmsprop_mix"}

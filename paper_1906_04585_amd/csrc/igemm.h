@@ -69,6 +69,8 @@
 //                                           image); an fp32 run then takes mode 2
 //   static constexpr bool SPLIT3            optional: an fp32 run takes mode 3 (both operands as three bf16
 //                                           pieces) instead of fp32 MFMAs; set where that is measured faster
+//   static constexpr bool FENCE_STAGING     bf16 modes: keep the scheduler from moving staging code (and its wait for
+//                                           the global loads) in between the MFMAs of a tile; set where measured faster
 //   static constexpr int  PREFETCH          k-tiles of global loads in flight ahead of the MFMAs: 1, or 2 with a
 //                                           second set of load registers
 //   static constexpr bool SUMSQ             optional: the workgroup also delivers the sum of
@@ -545,6 +547,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MODE == 3 ?
                     for (int j = 0; j < BJ; ++j) acc[i][j] = Blk::mma(a[i], b[j], acc[i][j]);
             }
         }
+        // optionally all of this tile's MFMAs are issued before the wave waits for the next tile's global
+        // loads: otherwise the scheduler mixes the staging code (and its wait) in between them and the
+        // matrix instructions still to come sit behind a memory wait
+        if constexpr (BF16 && P::FENCE_STAGING) __builtin_amdgcn_sched_barrier(0);
         if (kt + 1 < nkt) stage(std::integral_constant<int, buf ^ 1>{}, std::integral_constant<int, PF == 2 ? buf ^ 1 : 0>{});
         __syncthreads();
     };

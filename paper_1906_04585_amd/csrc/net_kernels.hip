@@ -62,6 +62,7 @@ struct ProblemBase {
     static constexpr bool SUMSQ = false;
     static constexpr bool A_EXACT_BF16 = false;   // true: every A value is an integer 0..255 (a byte image)
     static constexpr int PREFETCH = 1;            // k-tiles of global loads in flight (1 or 2)
+    static constexpr bool FENCE_STAGING = false;  // bf16 modes: all MFMAs of a tile before the staging of the next
     static constexpr bool SPLIT3 = false;         // true: fp32 accuracy from three bf16 pieces of both operands
     static constexpr int TABLE = 0;
     static constexpr bool BLOCK_FETCH_A = false;
@@ -92,6 +93,7 @@ struct Conv1Fwd : ProblemBase {
     static constexpr bool A_KC = true, B_KC = false;
     static constexpr bool A_EXACT_BF16 = true;
     static constexpr int PREFETCH = 2;            // little work per k-tile (byte loads, K = 256): 3 % faster; slower elsewhere
+    static constexpr bool FENCE_STAGING = true;   // 4 % faster
     typedef uint32_t ARaw;
     struct CtxA { const uint8_t *ptr; };
     const uint8_t *obs, *boot;
@@ -418,6 +420,7 @@ struct Conv2Dgrad : ProblemBase {
     static constexpr bool A_KC = true, B_KC = true;
     static constexpr bool HAS_AUX = true;
     static constexpr bool SPLIT3 = true;
+    static constexpr bool FENCE_STAGING = true;   // 128 -> 113 us; neutral or slower for the other kernels
     static constexpr int HY = H1 / 2, WX = W1 / 2, PC = HY * WX;   // 10, 10, 100
     static_assert(BN == 4 * C1, "four classes of C1 channels");
     typedef TapCtx CtxA;

@@ -131,11 +131,13 @@ int gala_learner_step(gala_ctx *ctx, const uint8_t *obs_u8, const int32_t *actio
 int gala_gossip(gala_ctx *ctx, int64_t round);
 
 /* One whole round of Algorithm 1 (optimise, broadcast, average) in a single call: the same
- * result as gala_learner_step followed by gala_gossip(round), same arguments and rules, but
- * clipping, RMSprop and the mixing step run as one kernel in which a workgroup owns a block
- * of parameter columns of all agents, so parameters, gradients and optimizer state cross
- * HBM once (20 bytes per parameter instead of 32).  For more than 256 agents the call runs
- * the two separate steps. */
+ * result, bit for bit, as gala_learner_step followed by gala_gossip(round), same arguments
+ * and rules, but clipping, RMSprop and the mixing step run as one kernel, so parameters,
+ * gradients and optimizer state cross HBM once (20 bytes per parameter instead of 32).
+ * Topologies with one in-peer per agent and no delays whose peers form a permutation (ring,
+ * exponential graph, explicit permutations) are walked cycle by cycle, any number of agents;
+ * otherwise a workgroup owns a block of parameter columns of all agents and keeps their
+ * updated values in LDS, and for more than 256 agents the call runs the two separate steps. */
 int gala_round(gala_ctx *ctx, const uint8_t *obs_u8, const int32_t *actions, const float *rewards,
                const uint8_t *dones, const uint8_t *bootstrap_obs, int64_t round);
 

@@ -150,14 +150,15 @@ def main() -> int:
         pool.append({k: torch.from_numpy(v).cuda() for k, v in ro.items()})
     torch.cuda.synchronize()
 
-    def one_round(r):
+    def one_round(r, actions=None):
         d = pool[r % len(pool)]
+        acts = d["actions"] if actions is None else actions
         if args.mode == "fused":
-            gpu.round(d["obs"], d["actions"], d["rewards"], d["dones"], d["boot_obs"], r)
+            gpu.round(d["obs"], acts, d["rewards"], d["dones"], d["boot_obs"], r)
         elif args.mode == "a2c_allreduce":
-            gpu.a2c_allreduce_step(d["obs"], d["actions"], d["rewards"], d["dones"], d["boot_obs"])
+            gpu.a2c_allreduce_step(d["obs"], acts, d["rewards"], d["dones"], d["boot_obs"])
         else:
-            gpu.learner_step(d["obs"], d["actions"], d["rewards"], d["dones"], d["boot_obs"])
+            gpu.learner_step(d["obs"], acts, d["rewards"], d["dones"], d["boot_obs"])
             gpu.gossip(r)
 
     rnd = 0
@@ -257,10 +258,40 @@ def main() -> int:
             gpu.act(pool[s_ % len(pool)]["boot_obs"], 1, 10 + s_, act_out, val_out)
         torch.cuda.synchronize()
         act_s = (time.perf_counter() - t0) / n_act
+        # One iteration of Algorithm 1 as a loop: T acting steps whose drawn actions become the
+        # rollout's actions, then the learner step and the gossip round.  States, rewards and
+        # episode ends stay synthetic (there is no simulator), so this times the GPU side of an
+        # actor-learner iteration, not a training run.
+        acts_buf = pool[0]["actions"].clone()
+
+        def actor_learner_iteration(r, step0):
+            d = pool[r % len(pool)]
+            for t in range(T):
+                gpu.act(d["boot_obs"], 1, step0 + t, act_out, val_out)
+                acts_buf[:, t].copy_(act_out)
+            one_round(r, acts_buf)
+
+        step_ctr = 1000
+        for _ in range(5):
+            actor_learner_iteration(rnd, step_ctr)
+            rnd += 1
+            step_ctr += T
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        n_it = 100
+        for _ in range(n_it):
+            actor_learner_iteration(rnd, step_ctr)
+            rnd += 1
+            step_ctr += T
+        torch.cuda.synchronize()
+        it_s = (time.perf_counter() - t0) / n_it
         acting = dict(call="gala_act", us_per_call=round(act_s * 1e6, 1), frames_per_call=N * B,
                       frames_per_s=round(N * B / act_s, 1),
-                      round_with_acting_ms=round(ms_per_step + T * act_s * 1e3, 4),
-                      note=f"a full actor-learner round = {T} acting steps + 1 learner/gossip step")
+                      actor_learner_iteration_ms=round(it_s * 1e3, 4),
+                      actor_learner_frames_per_s=round(N * T * B / it_s, 1),
+                      note=f"an actor-learner iteration = {T} acting steps (policy forward + draw; the drawn actions "
+                           f"are the rollout's actions) + 1 learner/gossip step, measured as one loop; states, "
+                           f"rewards and episode ends synthetic")
 
         # diagnostics of Sec. 5 (gradient cosine matrix, update norm, consensus distance): event-timed per call
         gpu.set_profiling(True)

@@ -57,6 +57,7 @@ __global__ __launch_bounds__(LOSS_THREADS) void loss_heads_kernel(
     if (m < M) {
         const int b = m % Bn, t = m / Bn;
         float G = V[M + b];
+#pragma unroll 4
         for (int tt = T - 1; tt >= t; --tt) {
             const long i = (long)agent * M + tt * Bn + b;
             const float keep = dones[i] ? 0.f : 1.f;
@@ -103,10 +104,18 @@ __global__ __launch_bounds__(LOSS_THREADS) void loss_heads_kernel(
     const float wv = xa[L.vw + j];
 #pragma unroll
     for (int fi = 0; fi < LOSS_FRAMES; ++fi) acc[fi] = wv * dl[fi][A];
-    for (int a = 0; a < A; ++a) {
-        const float w = xa[L.piw + (long)a * FC + j];
+    // six policy rows are requested at a time (the last one again where fewer remain) and applied in
+    // order: one wait for memory per six actions instead of one per action
+    for (int a0 = 0; a0 < A; a0 += 6) {
+        float w[6];
 #pragma unroll
-        for (int fi = 0; fi < LOSS_FRAMES; ++fi) acc[fi] += w * dl[fi][a];
+        for (int u = 0; u < 6; ++u) w[u] = xa[L.piw + (long)min(a0 + u, A - 1) * FC + j];
+#pragma unroll
+        for (int u = 0; u < 6; ++u)
+            if (a0 + u < A) {
+#pragma unroll
+                for (int fi = 0; fi < LOSS_FRAMES; ++fi) acc[fi] += w[u] * dl[fi][a0 + u];
+            }
     }
 #pragma unroll
     for (int fi = 0; fi < LOSS_FRAMES; ++fi) {
@@ -206,6 +215,7 @@ __global__ __launch_bounds__(NORM_THREADS) void grad_norm_kernel(const float *__
     const int agent = blockIdx.x;
     const float4 *p = reinterpret_cast<const float4 *>(g + agent * d_pad);
     float acc = 0.f;
+#pragma unroll 4
     for (long i = tail_begin / 4 + threadIdx.x; i < d_pad / 4; i += NORM_THREADS) {
         const float4 v = p[i];
         acc += (v.x * v.x + v.y * v.y) + (v.z * v.z + v.w * v.w);

@@ -669,9 +669,14 @@ __global__ __launch_bounds__(256) void reduce_splits_kernel(const float *__restr
     if (i < len) {
         const float *p = part + (long)agent * S * len + i;
         float4 acc = *reinterpret_cast<const float4 *>(p);
-        for (int s = 1; s < S; ++s) {
-            const float4 t = *reinterpret_cast<const float4 *>(p + (long)s * len);
-            acc.x += t.x; acc.y += t.y; acc.z += t.z; acc.w += t.w;
+        // eight partials are requested at a time (the last one again where fewer remain) and added in order
+        for (int s0 = 1; s0 < S; s0 += 8) {
+            float4 t[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) t[u] = *reinterpret_cast<const float4 *>(p + (long)min(s0 + u, S - 1) * len);
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (s0 + u < S) { acc.x += t[u].x; acc.y += t[u].y; acc.z += t[u].z; acc.w += t[u].w; }
         }
         *reinterpret_cast<float4 *>(out + agent * out_stride + i) = acc;
         sq = (acc.x * acc.x + acc.y * acc.y) + (acc.z * acc.z + acc.w * acc.w);
@@ -707,9 +712,14 @@ __global__ __launch_bounds__(128) void fc_reduce_heads_kernel(const float *__res
     const long len = (long)F * FC;
     const float *p = part + (long)agent * S * len + (long)f * FC + t * 4;
     float4 acc = *reinterpret_cast<const float4 *>(p);
-    for (int s = 1; s < S; ++s) {
-        const float4 v = *reinterpret_cast<const float4 *>(p + (long)s * len);
-        acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+    // partials are requested four at a time (the last one again where there are fewer) and added in order
+    for (int s0 = 1; s0 < S; s0 += 4) {
+        float4 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v[u] = *reinterpret_cast<const float4 *>(p + (long)min(s0 + u, S - 1) * len);
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (s0 + u < S) { acc.x += v[u].x; acc.y += v[u].y; acc.z += v[u].z; acc.w += v[u].w; }
     }
     const float4 b = *reinterpret_cast<const float4 *>(xa + L.fcb + t * 4);
     acc.x = fmaxf(acc.x + b.x, 0.f); acc.y = fmaxf(acc.y + b.y, 0.f);
@@ -718,14 +728,26 @@ __global__ __launch_bounds__(128) void fc_reduce_heads_kernel(const float *__res
 
     const int A = L.n_actions;
     const int n_out = f < M ? A + 1 : 1;            // bootstrap states need the value only
-    for (int oi = 0; oi < n_out; ++oi) {
-        const bool is_v = (oi == n_out - 1);
-        const float *w = is_v ? xa + L.vw : xa + L.piw + (long)oi * FC;
-        const float4 wv = *reinterpret_cast<const float4 *>(w + t * 4);
-        float d = (wv.x * acc.x + wv.y * acc.y) + (wv.z * acc.z + wv.w * acc.w);
+    // HEAD_GROUP outputs at a time: their weight rows are requested together and their reductions
+    // interleave, so a workgroup waits for memory once per group rather than once per output
+    constexpr int HEAD_GROUP = 4;
+    for (int o0 = 0; o0 < n_out; o0 += HEAD_GROUP) {
+        float d[HEAD_GROUP];
 #pragma unroll
-        for (int off = 32; off > 0; off >>= 1) d += __shfl_xor(d, off, 64);
-        if ((t & 63) == 0) red[t >> 6][oi] = d;
+        for (int u = 0; u < HEAD_GROUP; ++u) {
+            const int oi = min(o0 + u, n_out - 1);
+            const float *w = (oi == n_out - 1) ? xa + L.vw : xa + L.piw + (long)oi * FC;
+            const float4 wv = *reinterpret_cast<const float4 *>(w + t * 4);
+            d[u] = (wv.x * acc.x + wv.y * acc.y) + (wv.z * acc.z + wv.w * acc.w);
+        }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1)
+#pragma unroll
+            for (int u = 0; u < HEAD_GROUP; ++u) d[u] += __shfl_xor(d[u], off, 64);
+        if ((t & 63) == 0)
+#pragma unroll
+            for (int u = 0; u < HEAD_GROUP; ++u)
+                if (o0 + u < n_out) red[t >> 6][o0 + u] = d[u];
     }
     __syncthreads();
     if (t < n_out) {

@@ -67,6 +67,12 @@
 //                                           loads all of the thread's groups, group i at local k + i
 //   static constexpr bool A_EXACT_BF16      optional: every A value is exactly representable in bf16 (a byte
 //                                           image); an fp32 run then takes mode 2
+//   static constexpr bool A_DIRECT          optional, bf16 modes with WN == 1 and a k-contiguous A: A does not go
+//                                           through LDS; every lane loads and splits the groups of its own
+//                                           MFMA operand position (prep_a is called with that row and k)
+//   static constexpr bool B_DIRECT          the same for a k-contiguous B with WM == 1
+//   static constexpr bool DIRECT_SINGLE_PIECE   whether mode 1 (one rounded piece per operand) takes the direct
+//                                           path as well: it pays where the operand's loads dominate
 //   static constexpr bool SPLIT3            optional: an fp32 run takes mode 3 (both operands as three bf16
 //                                           pieces) instead of fp32 MFMAs; set where that is measured faster
 //   static constexpr bool FENCE_STAGING     bf16 modes: keep the scheduler from moving staging code (and its wait for
@@ -206,23 +212,34 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MODE == 3 ?
     //    four apart): rows padded to BK + 4 shorts (ten dwords, sixteen rows on sixteen bank pairs) and
     //    the quads exchanged by the row's bits 4..5, which spreads the stores of rows four apart.
     constexpr int RA = BK + (P::A_KC ? 0 : 4), RB = BK + (P::B_KC ? 0 : 4);     // row lengths in shorts
-    constexpr int LDS_F32 = 2 * BK * (SA + SB), LDS_BF16 = BF16 ? (2 * (NA * BM * RA + NB * BN * RB) + 1) / 2 : 0;
-    constexpr int LDS_LOOP = LDS_F32 > LDS_BF16 ? LDS_F32 : LDS_BF16, LDS_OUT = SLAB * SC;
+    // A_DIRECT: with one column of wavefronts (WN == 1) no two wavefronts need the same A rows, and a
+    // k-contiguous A group (one row, four consecutive k) is exactly what an MFMA lane holds: every
+    // lane loads the groups of its own operand position, splits them into pieces in registers and
+    // feeds them to the MFMAs; only B goes through LDS.
+    constexpr bool A_DIRECT = BF16 && P::A_DIRECT && (MODE != 1 || P::DIRECT_SINGLE_PIECE);
+    static_assert(!A_DIRECT || (P::A_KC && P::WN == 1 && !P::SUM_A && P::MFMA16), "direct A operands: k-contiguous, one wavefront column");
+    constexpr int NA_LDS = A_DIRECT ? 0 : NA;                                    // pieces of A kept in LDS
+    // B_DIRECT: the same for B with one row of wavefronts (WM == 1)
+    constexpr bool B_DIRECT = BF16 && P::B_DIRECT && (MODE != 1 || P::DIRECT_SINGLE_PIECE);
+    static_assert(!B_DIRECT || (P::B_KC && P::WM == 1 && !P::SUM_B && P::MFMA16 && !A_DIRECT), "direct B operands: k-contiguous, one wavefront row");
+    constexpr int NB_LDS = B_DIRECT ? 0 : NB;
+    constexpr int LDS_F32 = 2 * BK * (SA + SB), LDS_BF16 = BF16 ? (2 * (NA_LDS * BM * RA + NB_LDS * BN * RB) + 1) / 2 : 0;
+    constexpr int LDS_LOOP = (A_DIRECT || B_DIRECT) ? LDS_BF16 : (LDS_F32 > LDS_BF16 ? LDS_F32 : LDS_BF16), LDS_OUT = SLAB * SC;
     constexpr int LDS_FLOATS = LDS_LOOP > LDS_OUT ? LDS_LOOP : LDS_OUT;
     __shared__ __attribute__((aligned(16))) float smem[LDS_FLOATS];
     auto As = [&](int buf, int k, int c) -> float & { return smem[(buf * BK + k) * SA + c]; };
     auto Bs = [&](int buf, int k, int c) -> float & { return smem[OFFB + (buf * BK + k) * SB + c]; };
     // bf16 tiles: [buf][row][BK + 4] shorts (the padding keeps 8-byte alignment and spreads banks)
     static_assert(!BF16 || (P::MFMA16 && BK == 16), "bf16 path: 16x16 blocks, four k-quads per tile row");
-    constexpr int OFFBH = 2 * NA * BM * RA;
-    static_assert(!BF16 || (2 * (NA * BM * RA + NB * BN * RB) * 2 <= LDS_FLOATS * 4), "bf16 tiles fit the allocation");
+    constexpr int OFFBH = 2 * NA_LDS * BM * RA;
+    static_assert(!BF16 || (2 * (NA_LDS * BM * RA + NB_LDS * BN * RB) * 2 <= LDS_FLOATS * 4), "bf16 tiles fit the allocation");
     unsigned short *hs = reinterpret_cast<unsigned short *>(smem);
     auto swz = [](bool kc, int row, int k) { return k ^ ((((kc ? row >> 2 : row >> 4)) & 3) << 2); };
     auto Ah = [&](int buf, int piece, int m, int k) -> unsigned short & {
         return hs[((buf * NA + piece) * BM + m) * RA + swz(P::A_KC, m, k)];
     };
     auto Bh = [&](int buf, int piece, int n, int k) -> unsigned short & {
-        return hs[OFFBH + ((buf * NB + piece) * BN + n) * RB + swz(P::B_KC, n, k)];
+        return hs[OFFBH + ((buf * NB_LDS + piece) * BN + n) * RB + swz(P::B_KC, n, k)];
     };
 
     const int bid = blockIdx.x;
@@ -258,6 +275,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MODE == 3 ?
     typename P::CtxA ca[PA];
     typename P::CtxB cb[PB];
     bool oka[PF][PA], okb[PF][PB];
+    static_assert(!A_DIRECT || PA == BI, "direct A operands: one group per MFMA block row of the wavefront");
+    gala_s16x4 areg[NA][A_DIRECT ? BI : 1];       // A_DIRECT: the pieces of the tile about to be multiplied
+    static_assert(!B_DIRECT || PB == BJ, "direct B operands: one group per MFMA block column of the wavefront");
+    gala_s16x4 breg[NB][B_DIRECT ? BJ : 1];
     static_assert(!P::SUM_A || (!P::A_KC && 256 % (BM / 4) == 0), "SUM_A needs m-contiguous groups");
     static_assert(!P::SUM_B || (!P::B_KC && 256 % (BN / 4) == 0), "SUM_B needs n-contiguous groups");
     static_assert(!P::SUM_A || (BM / 4) % (256 / BK) == 0 || PA == 1, "SUM_A: one pass unless k is shared");
@@ -299,7 +320,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MODE == 3 ?
 #pragma unroll
         for (int st = 0; st < PF; ++st) oka[st][i] = true;
         if (GA % 256 == 0 || g < GA) {
-            if (P::A_KC) p.prep_a(ca[i], m0 + g / (BK / 4), (g % (BK / 4)) * 4);
+            if constexpr (A_DIRECT) p.prep_a(ca[i], m0 + wm0 + i * MB + lane % MB, (lane / MB) * 4);
+            else if (P::A_KC) p.prep_a(ca[i], m0 + g / (BK / 4), (g % (BK / 4)) * 4);
             else { int kl, q; map_a(i, kl, q); p.prep_a(ca[i], m0 + q * 4, kl); }
         }
     }
@@ -309,7 +331,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MODE == 3 ?
 #pragma unroll
         for (int st = 0; st < PF; ++st) okb[st][i] = true;
         if (GB % 256 == 0 || g < GB) {
-            if (P::B_KC) p.prep_b(cb[i], (g % (BK / 4)) * 4, n0 + g / (BK / 4));
+            if constexpr (B_DIRECT) p.prep_b(cb[i], (lane / MB) * 4, n0 + wn0 + i * MB + lane % MB);
+            else if (P::B_KC) p.prep_b(cb[i], (g % (BK / 4)) * 4, n0 + g / (BK / 4));
             else { int kl, q; map_mc(QB{}, i, kl, q); p.prep_b(cb[i], kl, n0 + q * 4); }
         }
     }
@@ -366,7 +389,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MODE == 3 ?
 #pragma unroll
                     for (int j = 0; j < 4; ++j) r[j] = oka[st][i] ? r[j] : 0.f;
                 }
-                if (BF16 && P::A_KC) {
+                if constexpr (A_DIRECT) {
+                    unsigned lo[NA], hi[NA];
+                    gala_pieces4<NA>(r, lo, hi);
+#pragma unroll
+                    for (int pc = 0; pc < NA; ++pc) areg[pc][i] = __builtin_bit_cast(gala_s16x4, make_uint2(lo[pc], hi[pc]));
+                } else if (BF16 && P::A_KC) {
                     const int row = g / (BK / 4), kq = g % (BK / 4);
                     unsigned lo[NA], hi[NA];
                     gala_pieces4<NA>(r, lo, hi);
@@ -408,7 +436,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MODE == 3 ?
 #pragma unroll
                     for (int j = 0; j < 4; ++j) r[j] = okb[st][i] ? r[j] : 0.f;
                 }
-                if (BF16 && P::B_KC) {
+                if constexpr (B_DIRECT) {
+                    unsigned lo[NB], hi[NB];
+                    gala_pieces4<NB>(r, lo, hi);
+#pragma unroll
+                    for (int pc = 0; pc < NB; ++pc) breg[pc][i] = __builtin_bit_cast(gala_s16x4, make_uint2(lo[pc], hi[pc]));
+                } else if (BF16 && P::B_KC) {
                     const int col = g / (BK / 4), kq = g % (BK / 4);
                     unsigned lo[NB], hi[NB];
                     gala_pieces4<NB>(r, lo, hi);
@@ -475,13 +508,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MODE == 3 ?
 #pragma unroll
                 for (int pc = 0; pc < NA; ++pc)
 #pragma unroll
-                    for (int i = 0; i < BI; ++i)
-                        a[pc][i] = *reinterpret_cast<const gala_s16x4 *>(&Ah(buf, pc, wm0 + i * MB + lr, kk + lk * 4));
+                    for (int i = 0; i < BI; ++i) {
+                        if constexpr (A_DIRECT) a[pc][i] = areg[pc][i];
+                        else a[pc][i] = *reinterpret_cast<const gala_s16x4 *>(&Ah(buf, pc, wm0 + i * MB + lr, kk + lk * 4));
+                    }
 #pragma unroll
                 for (int q = 0; q < NB; ++q)
 #pragma unroll
-                    for (int j = 0; j < BJ; ++j)
-                        b[q][j] = *reinterpret_cast<const gala_s16x4 *>(&Bh(buf, q, wn0 + j * MB + lr, kk + lk * 4));
+                    for (int j = 0; j < BJ; ++j) {
+                        if constexpr (B_DIRECT) b[q][j] = breg[q][j];
+                        else b[q][j] = *reinterpret_cast<const gala_s16x4 *>(&Bh(buf, q, wn0 + j * MB + lr, kk + lk * 4));
+                    }
                 // Products of pieces a_pc b_q with pc + q <= NB - 1, the small ones first.  The
                 // 16x16x32 instruction takes eight k per lane: fed with the same four k of two
                 // different pieces it adds two such products at once.

@@ -64,6 +64,9 @@ struct ProblemBase {
     static constexpr int PREFETCH = 1;            // k-tiles of global loads in flight (1 or 2)
     static constexpr bool FENCE_STAGING = false;  // bf16 modes: all MFMAs of a tile before the staging of the next
     static constexpr bool SPLIT3 = false;         // true: fp32 accuracy from three bf16 pieces of both operands
+    static constexpr bool A_DIRECT = false;       // true: bf16 modes take A from global memory into the MFMA lanes
+    static constexpr bool B_DIRECT = false;       // the same for B
+    static constexpr bool DIRECT_SINGLE_PIECE = false;   // whether the bf16 variant (mode 1) does so too
     static constexpr int TABLE = 0;
     static constexpr bool BLOCK_FETCH_A = false;
     __device__ void fill_table(int *, int) {}
@@ -94,6 +97,8 @@ struct Conv1Fwd : ProblemBase {
     static constexpr bool A_EXACT_BF16 = true;
     static constexpr int PREFETCH = 2;            // little work per k-tile (byte loads, K = 256): 3 % faster; slower elsewhere
     static constexpr bool FENCE_STAGING = true;   // 4 % faster
+    static constexpr bool A_DIRECT = true;        // fp32: 121 -> 116 us; the bf16 variant: 104 -> 83 us
+    static constexpr bool DIRECT_SINGLE_PIECE = true;
     typedef uint32_t ARaw;
     struct CtxA { const uint8_t *ptr; };
     const uint8_t *obs, *boot;
@@ -143,9 +148,13 @@ struct Conv1Fwd : ProblemBase {
 // k never crosses a kernel row, so its offset is uniform.
 template <int CI, int HI, int WI, int CO, int HO, int WO, int KS, int ST>
 struct ConvFwd : ProblemBase {
-    static constexpr int BM = 128, BN = 64, BK = 16, WM = 2, WN = 2;
+    // One column of wavefronts (32 x 64 each): no two of them read the same input rows, so the input
+    // operand skips LDS in mode 3 (conv2 126 -> 120 us, conv3 93 -> 87 us; the bf16 variant is faster
+    // through LDS and keeps it).
+    static constexpr int BM = 128, BN = 64, BK = 16, WM = 4, WN = 1;
     static constexpr bool A_KC = true, B_KC = false;
     static constexpr bool SPLIT3 = true;
+    static constexpr bool A_DIRECT = true;
     static_assert((KS * CI) % BK == 0, "a k-tile stays inside one kernel row");
     const float *in, *x;
     float *out;
@@ -194,6 +203,7 @@ struct FcFwdT : ProblemBase {
     static constexpr int BM = BM_, BN = 128, BK = 16, WM = 1, WN = 4;
     static constexpr bool A_KC = true, B_KC = true;
     static constexpr bool SPLIT3 = true;
+    static constexpr bool B_DIRECT = true;        // each wavefront has its own 32 weight columns: 82 -> 77 us
     const float *a3, *x;
     float *ws;
     long d_pad, w_off;
@@ -318,7 +328,7 @@ struct TapCtx { unsigned off; unsigned mask; };
 
 // ---- conv3: gradient to a2 (stride 1: full correlation with the flipped kernel) -----------------
 // m = (iy, ix, f), n = c, k = (kh, kw, o); a tile of 16 consecutive k lies inside one tap.
-// Rows are ordered position-major so that a workgroup's rows share one or two input positions:
+// Rows are ordered position-major so that a workgroup's rows share two or three input positions:
 // the taps that fall outside the 7x7 output for all of them (40 % of all taps on average) are
 // left out of its k-loop; a tap that is outside for only some rows is read from the zero page
 // in front of dz3 for those rows.  (Sorting the positions by their tap sets would leave out
@@ -326,10 +336,11 @@ struct TapCtx { unsigned off; unsigned mask; };
 // Row -> (position, frame) divides by the runtime frame count with a multiply-high by
 // mdiv = 2^32 / M + 1, exact for rows below 2^32 / M (M = 1 needs no division).
 struct Conv3Dgrad : ProblemBase {
-    static constexpr int BM = GALA_MFMA16 ? 160 : 128, BN = 64, BK = 16, WM = 2, WN = 2;
+    static constexpr int BM = 128, BN = 64, BK = 16, WM = 4, WN = 1;
     static constexpr bool A_KC = true, B_KC = true;
     static constexpr bool HAS_AUX = true;
     static constexpr bool SPLIT3 = true;
+    static constexpr bool A_DIRECT = true;        // 117 -> 98 us (128-, 192-, 256- and 320-row tiles within 3 us)
     static constexpr int TILES_PER_TAP = C3 / BK;
     typedef TapCtx CtxA;
     const float *dz3, *x, *a2;      // dz3 points at the data; ZERO_PAGE zeros precede the allocation's data
@@ -416,6 +427,8 @@ struct Conv3Dgrad : ProblemBase {
 // differ.  The four classes therefore form the columns of one GEMM that reads the window once:
 // m = (f, y', x') with iy = 2y'+py, n = (class, c), k = (a, b, o) with kh = py + 2a, oy = y' - a.
 struct Conv2Dgrad : ProblemBase {
+    // (a 4 x 1 wavefront grid with the gradient operand taken straight from global memory reads as
+    // much LDS per MFMA as the 2 x 2 grid does and was slower: 130 vs 113 us)
     static constexpr int BM = 128, BN = 128, BK = 16, WM = 2, WN = 2;
     static constexpr bool A_KC = true, B_KC = true;
     static constexpr bool HAS_AUX = true;

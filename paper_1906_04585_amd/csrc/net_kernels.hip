@@ -633,18 +633,18 @@ struct Conv1Wgrad : ProblemBase {
         return v;
     }
     // Four groups at consecutive k = four consecutive output positions starting at a multiple of
-    // four: they never straddle a frame (P1 and the k-range bounds are multiples of four), so one
-    // walk and one 16-byte table read serve all of them.
+    // four: they never straddle a frame or an output row (P1, W1 and the k-range bounds are multiples
+    // of four), and with stride S1 = 4 bytes between positions their four 4-byte groups are sixteen
+    // consecutive bytes of one image row: one walk, one table read and one 16-byte load (4-byte
+    // aligned) serve all of them.
     __device__ void fetch_a_block(CtxA &c, int, uint32_t (&raw)[4], bool (&ok)[4]) const
     {
-        static_assert(P1 % 4 == 0 && BK % 4 == 0, "position quads");
+        static_assert(P1 % 4 == 0 && W1 % 4 == 0 && BK % 4 == 0 && S1 == 4, "position quads");
+        typedef uint32_t u32x4_a4 __attribute__((ext_vector_type(4), aligned(4)));
         const bool in = c.k < k1;
-        const int4 o = *reinterpret_cast<const int4 *>(tab_ + c.p);
-        const unsigned base = c.moff + c.foff;
-        raw[0] = ldg_u32b(o_, in ? base + (unsigned)o.x : 0u);
-        raw[1] = ldg_u32b(o_, in ? base + (unsigned)o.y : 0u);
-        raw[2] = ldg_u32b(o_, in ? base + (unsigned)o.z : 0u);
-        raw[3] = ldg_u32b(o_, in ? base + (unsigned)o.w : 0u);
+        const unsigned off = in ? c.moff + c.foff + (unsigned)tab_[c.p] : 0u;
+        const u32x4_a4 v = *reinterpret_cast<const u32x4_a4 *>(o_ + off);
+        raw[0] = v.x; raw[1] = v.y; raw[2] = v.z; raw[3] = v.w;
         ok[0] = ok[1] = ok[2] = ok[3] = in;
         c.k += BK; c.p += BK;
         if (c.p >= P1) { c.p -= P1; c.foff += (unsigned)FRAME; }

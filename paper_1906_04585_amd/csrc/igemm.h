@@ -8,6 +8,8 @@
 // P::store4.  The kernel never materialises A or B in HBM: 256 threads stage BM x BK and
 // BK x BN tiles through LDS (k-major, so a wavefront's MFMA operand read is one
 // ds_read_b32 per lane), double-buffered against the global loads of the next k-tile.
+// In the bf16 modes an operand that only one wavefront of the workgroup needs can skip LDS
+// (A_DIRECT / B_DIRECT below): its lanes load and split exactly the groups they multiply.
 // The result tile leaves through LDS as well, so that every global store (and every
 // epilogue operand load) is a float4 with consecutive lanes on consecutive addresses.
 //

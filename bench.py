@@ -329,6 +329,24 @@ def main() -> int:
         cpu_baseline = dict(value=n_s * n_r / cpu_t, unit="agent-steps/s", cores=threads, kind="oracle",
                             sample=f"{n_r} rounds (learner step + gossip) of {n_s} of the {N} agents, "
                                    f"{n_s * n_r * M} frames, fp64, {cpu_t:.2f} s wall on {threads} threads")
+        # the same oracle on one thread (one round of two agents), through the OpenMP runtime's own switch
+        try:
+            import ctypes
+            gomp = ctypes.CDLL("libgomp.so.1")
+            gomp.omp_set_num_threads(1)
+            n1 = min(N, 2)
+            om1 = orc.OracleGala(net, n1, T, B, gs.HPARAMS, "ring")
+            om1.set_params(X0[:n1])
+            ro1 = {k: v[:n1] for k, v in ros[0].items()}
+            t0 = time.perf_counter()
+            om1.learner_step(ro1["obs"], ro1["actions"], ro1["rewards"], ro1["dones"], ro1["boot_obs"])
+            om1.gossip(0)
+            t1 = time.perf_counter() - t0
+            gomp.omp_set_num_threads(threads)
+            cpu_baseline["single_thread"] = dict(value=n1 / t1, unit="agent-steps/s",
+                                                 sample=f"1 round of {n1} agents, {t1:.2f} s wall on 1 thread")
+        except OSError:
+            pass
 
     out = {
         "metric": "agent learner-steps/sec (one learner step + one gossip round per agent)"

@@ -72,6 +72,9 @@ typedef struct {
 #define GALA_TOPO_EXP       1   /* 1-peer exponential graph: at round r agent i mixes with
                                    (i + 2^(r mod log2 N)) mod N; N must be a power of two       */
 #define GALA_TOPO_EXPLICIT  2   /* caller-supplied peers and weights, n_phases tables cycled by round */
+#define GALA_TOPO_EXP_REVERSE 3 /* the exponential graph with every edge turned round: agent i mixes with
+                                   (i - 2^(r mod log2 N)) mod N.  Both directions give the doubly
+                                   stochastic P = (I + shift)/2 of Sec. 2; N a power of two          */
 
 /* Mixing weights follow Algorithm 1: 1/(1+|N_in|) for ring and exponential graphs.
  * max_delay = tau bounds message staleness; each edge (phase, receiver[, in-peer slot])
@@ -93,7 +96,15 @@ typedef struct {
 
 /* Create a context for n_agents agents.  hip_stream is a hipStream_t (NULL = the
  * default stream) on which all work is enqueued.  Parameters start at zero and the
- * RMSprop state at zero; call gala_set_params before the first learner step.
+ * RMSprop state at zero; call gala_set_params before the first learner step (a learner,
+ * round, comparator or acting step before it fails with GALA_ESTATE).
+ * Limits: 1 <= n_agents <= 4096, T*B <= 4096 and n_agents * (T*B + B) <= 83 886 frames per
+ * context (the kernels address an agent's activations with 32-bit byte offsets); beyond
+ * them the call fails with GALA_EINVAL.
+ * If the environment variable GALA_CHECK_ACTIONS is set when the context is created, every
+ * learner, round and comparator step first counts the actions outside [0, n_actions) with
+ * a small kernel, waits for the count and fails with GALA_EINVAL when it is not zero (a
+ * debugging aid: it synchronises the stream on every step).
  * The context also owns one internal stream of default priority on which the weight-gradient
  * kernels of a learner step run beside the data-gradient chain; it is forked from and joined
  * back into hip_stream inside every call, so callers only ever order against hip_stream.
@@ -119,6 +130,7 @@ int gala_get_opt_state(gala_ctx *ctx, float *dst, int dst_is_device);
  * entropy Eq. (4)).  All pointers dev:
  *   obs_u8        uint8 [N][T][B][4][84][84]  states s_t (scaled by 1/255 inside)
  *   actions       int32 [N][T][B]             in [0, n_actions); out-of-range is undefined
+ *                                             unless GALA_CHECK_ACTIONS is set (see gala_create)
  *   rewards       float [N][T][B]
  *   dones         uint8 [N][T][B]             1 = the transition at t ended the episode
  *   bootstrap_obs uint8 [N][B][4][84][84]     state reached after the last action */
@@ -197,6 +209,11 @@ int gala_update_norm(gala_ctx *ctx, float *row_norms_host, float *frob_host);
  * of round s (gala_update_norm) and beta in [0, 1] is the contraction factor of the mixing
  * matrices (cos(pi/N) for the directed ring with weights 1/2).  Host arithmetic only. */
 int gala_prop1_bound(double beta, const double *update_norms, int n, double *bound);
+/* Output gradients of the two heads as the loss kernel of the last learner step wrote them, host
+ * buffers (either may be NULL): dlogits [N][T*B][A] = dLoss/dlogits, dvalues [N][T*B] = dLoss/dV.
+ * With the entropy coefficient at zero a row of dlogits is A_m (pi - onehot(a_m)) / (T*B): the
+ * taken action is the one entry whose sign differs, which lets a test check the integer gather. */
+int gala_get_head_grads(gala_ctx *ctx, float *dlogits_host, float *dvalues_host);
 /* In-peer and delay tables the library will use at `round`, host int32 [N][max_in] each
  * (max_in = 1 for ring and exponential graphs). */
 int gala_get_peer_table(gala_ctx *ctx, int64_t round, int32_t *peer, int32_t *delay);

@@ -532,7 +532,9 @@ void orc_a2c_allreduce_step(const orc_net *n, const orc_hparams *hp, int N, doub
  * kind 0: directed ring v_1 -> v_2 -> ... -> v_n -> v_1 (Fig. 5): agent i
  *         receives from i-1.
  * kind 1: one-peer exponential graph: agent i mixes with (i + 2^k) mod N,
- *         k = round mod log2(N). */
+ *         k = round mod log2(N).
+ * kind 2: the same graph with every edge reversed: agent i mixes with
+ *         (i - 2^k) mod N (the transposed, equally doubly stochastic matrix). */
 int orc_in_peer(int kind, int N, long round, int i)
 {
     if (kind == 0) return (i + N - 1) % N;
@@ -540,7 +542,8 @@ int orc_in_peer(int kind, int N, long round, int i)
     while ((1 << (m + 1)) <= N) ++m;      /* log2 N for a power of two */
     if (m == 0) return i;
     const int k = (int)(round % m);
-    return (i + (1 << k)) % N;
+    const int hop = (1 << k) % N;
+    return kind == 1 ? (i + hop) % N : (i + N - hop) % N;
 }
 
 int orc_n_phases(int kind, int N)

@@ -242,7 +242,7 @@ def rmsprop(x: np.ndarray, v: np.ndarray, g: np.ndarray, lr, alpha, eps):
     lib().orc_rmsprop(_p(x), _p(v), _p(g), x.size, float(lr), float(alpha), float(eps))
 
 
-TOPOLOGY_KIND = {"ring": 0, "exp": 1}
+TOPOLOGY_KIND = {"ring": 0, "exp": 1, "exp_reverse": 2}
 
 
 def in_peer(kind: str, N: int, rnd: int, i: int) -> int:
@@ -363,7 +363,7 @@ class OracleGala:
                  max_delay: int = 0, delay_seed: int = 0):
         self.net, self.N, self.T, self.B, self.hp = net, n_agents, T, B, dict(hp)
         self.topology, self.max_delay, self.delay_seed = topology, max_delay, delay_seed
-        if topology == "exp" and n_agents & (n_agents - 1):
+        if topology in ("exp", "exp_reverse") and n_agents & (n_agents - 1):
             raise ValueError("the exponential graph needs a power-of-two number of agents")
         self.d = param_count(net)
         self.X = np.zeros((n_agents, self.d))

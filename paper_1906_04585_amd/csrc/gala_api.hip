@@ -30,6 +30,9 @@ struct gala_ctx {
     int cur = 0;                 // which of b.x[] holds the current parameters
     float *canon = nullptr;      // [N][d] staging for get/set through host pointers
     int64_t last_round = -1;
+    bool params_set = false;        // gala_set_params has been called: a learner step has something to learn from
+    bool check_actions = false;     // GALA_CHECK_ACTIONS was set at creation: validate the action buffer of every step
+    int32_t *bad_actions = nullptr; // device counter of the validation kernel
     bool shared_gradient = false;   // the last optimiser step applied the averaged gradient
     hipStream_t stream = nullptr;
     int device = 0;
@@ -67,6 +70,13 @@ static uint64_t splitmix64(uint64_t z)
     return z ^ (z >> 31);
 }
 
+// Bytes from the start of the largest activation buffer (zero page included) to its end.
+static unsigned long long max_buffer_bytes(int n_agents, int T, int B)
+{
+    const unsigned long long frames = (unsigned long long)n_agents * ((unsigned long long)T * B + B);
+    return frames * A1SZ * 4ull + ZERO_PAGE * 4ull;
+}
+
 template <class T>
 static int dev_alloc(gala_ctx *c, T **p, size_t count, bool zero)
 {
@@ -87,7 +97,7 @@ static int build_topology(gala_ctx *c, const gala_topology *t)
     if (t->max_delay < 0 || t->max_delay > 16) return fail(nullptr, GALA_EINVAL, "max_delay must be in [0, 16]");
     if (t->kind == GALA_TOPO_RING) {
         c->n_phases = 1; c->max_in = 1;
-    } else if (t->kind == GALA_TOPO_EXP) {
+    } else if (t->kind == GALA_TOPO_EXP || t->kind == GALA_TOPO_EXP_REVERSE) {
         if (N & (N - 1)) return fail(nullptr, GALA_EINVAL, "exponential graph needs a power-of-two agent count, got %d", N);
         int m = 0;
         while ((1 << (m + 1)) <= N) ++m;
@@ -123,7 +133,8 @@ static int build_topology(gala_ctx *c, const gala_topology *t)
                     return fail(nullptr, GALA_EINVAL, "mixing weights of agent %d, phase %d sum to %g, not 1", i, ph, sum);
             } else {
                 // |N_in| = 1: uniform weights 1/(1+|N_in|) = 1/2 (Algorithm 1, footnote)
-                pr[0] = t->kind == GALA_TOPO_RING ? (i + N - 1) % N : (i + (1 << ph)) % N;
+                pr[0] = t->kind == GALA_TOPO_RING ? (i + N - 1) % N
+                      : t->kind == GALA_TOPO_EXP ? (i + (1 << ph)) % N : (i + N - (1 << ph) % N) % N;
                 if (N == 1) pr[0] = 0;
                 w[0] = 0.5f; w[1] = 0.5f;
             }
@@ -169,6 +180,12 @@ extern "C" int gala_create(gala_ctx **out, int n_agents, const gala_topology *to
         return fail(nullptr, GALA_EINVAL, "only the 4x84x84 -> 32/64/64 -> 512 network is supported");
     if (net->n_actions < 1 || net->n_actions > 64) return fail(nullptr, GALA_EINVAL, "n_actions must be in [1, 64]");
     if (hp->T < 1 || hp->B < 1 || (long)hp->T * hp->B > 4096) return fail(nullptr, GALA_EINVAL, "need T, B >= 1 and T*B <= 4096");
+    // the convolution kernels address an agent's activations by 32-bit byte offsets from the start of
+    // the whole buffer; the largest buffer is the first layer's activations over all frames
+    if (max_buffer_bytes(n_agents, hp->T, hp->B) >= (1ull << 32))
+        return fail(nullptr, GALA_EINVAL, "n_agents * (T*B + B) = %lld frames exceed the 32-bit activation offsets "
+                    "(at most %lld frames in one context)", (long long)n_agents * ((long long)hp->T * hp->B + hp->B),
+                    (long long)(((1ull << 32) - ZERO_PAGE * 4) / ((unsigned long long)A1SZ * 4)));
     if (hp->compute_dtype != 0 && hp->compute_dtype != 1)
         return fail(nullptr, GALA_EINVAL, "compute_dtype %d not available (0 = fp32, 1 = bf16 MFMA)", hp->compute_dtype);
     if (!(hp->rms_eps > 0.f) || !(hp->rms_alpha >= 0.f && hp->rms_alpha < 1.f) || !(hp->max_grad_norm > 0.f))
@@ -224,12 +241,14 @@ extern "C" int gala_create(gala_ctx **out, int n_agents, const gala_topology *to
     ALLOC(b.upd_part, N * UPDATE_NORM_BLOCKS, true); ALLOC(b.upd_norm, N + 2, true); ALLOC(b.row_ss, N, true);
     ALLOC(b.gbar, dp, true); ALLOC(b.gbar_part, (size_t)grad_mean_blocks(c->L), true);
     ALLOC(b.stats, N * 5, true);
-    ALLOC(b.cons_part, N * ((dp + CONS_COLS - 1) / CONS_COLS) + 2, true);
+    ALLOC(b.cons_part, N * (size_t)consensus_parts(c->N, c->L) + 2, true);
     ALLOC(b.peer, c->h_peer.size(), false); ALLOC(b.delay, c->h_delay.size(), false);
     ALLOC(b.weight, c->h_weight.size(), false);
     ALLOC(b.cyc_order, c->h_cyc_order.size(), false); ALLOC(b.cyc_start, c->h_cyc_start.size(), false);
     ALLOC(c->canon, N * c->L.d, false);
+    ALLOC(c->bad_actions, 1, true);
 #undef ALLOC
+    c->check_actions = getenv("GALA_CHECK_ACTIONS") != nullptr;
     he = hipMemcpyAsync(b.peer, c->h_peer.data(), c->h_peer.size() * 4, hipMemcpyHostToDevice, c->stream);
     if (he == hipSuccess) he = hipMemcpyAsync(b.delay, c->h_delay.data(), c->h_delay.size() * 4, hipMemcpyHostToDevice, c->stream);
     if (he == hipSuccess) he = hipMemcpyAsync(b.weight, c->h_weight.data(), c->h_weight.size() * 4, hipMemcpyHostToDevice, c->stream);
@@ -291,7 +310,13 @@ static int import_arena(gala_ctx *c, float *arena, const float *src, int src_is_
     return GALA_OK;
 }
 
-extern "C" int gala_set_params(gala_ctx *c, const float *src, int dev) { return c ? import_arena(c, c->b.x[c->cur], src, dev) : GALA_EINVAL; }
+extern "C" int gala_set_params(gala_ctx *c, const float *src, int dev)
+{
+    if (!c) return GALA_EINVAL;
+    const int rc = import_arena(c, c->b.x[c->cur], src, dev);
+    if (rc == GALA_OK) c->params_set = true;
+    return rc;
+}
 extern "C" int gala_get_params(gala_ctx *c, float *dst, int dev) { return c ? export_arena(c, c->b.x[c->cur], dst, dev) : GALA_EINVAL; }
 extern "C" int gala_set_opt_state(gala_ctx *c, const float *src, int dev) { return c ? import_arena(c, c->b.v, src, dev) : GALA_EINVAL; }
 extern "C" int gala_get_opt_state(gala_ctx *c, float *dst, int dev) { return c ? export_arena(c, c->b.v, dst, dev) : GALA_EINVAL; }
@@ -316,6 +341,15 @@ static int enqueue_gradients(gala_ctx *c, const uint8_t *obs_u8, const int32_t *
     if (!obs_u8 || !actions || !rewards || !dones || !bootstrap_obs) return fail(c, GALA_EINVAL, "null input buffer");
     if ((reinterpret_cast<uintptr_t>(obs_u8) | reinterpret_cast<uintptr_t>(bootstrap_obs)) & 3)
         return fail(c, GALA_EINVAL, "observation buffers must be 4-byte aligned");
+    if (!c->params_set) return fail(c, GALA_ESTATE, "learner step before gala_set_params: the parameters are all zero");
+    if (c->check_actions) {
+        // opt-in (GALA_CHECK_ACTIONS): count the actions outside [0, A) and refuse the step; synchronises
+        int32_t bad = 0;
+        HIP_OK(c, launch_count_bad_actions(actions, (long)c->N * c->M, c->L.n_actions, c->bad_actions, c->stream));
+        HIP_OK(c, hipMemcpyAsync(&bad, c->bad_actions, 4, hipMemcpyDeviceToHost, c->stream));
+        HIP_OK(c, hipStreamSynchronize(c->stream));
+        if (bad) return fail(c, GALA_EINVAL, "%d action(s) outside [0, %d)", (int)bad, c->L.n_actions);
+    }
     NetArgs a{};
     a.N = c->N; a.M = c->M; a.F = c->F; a.Bn = c->hp.B; a.L = c->L;
     a.x = c->b.x[c->cur]; a.b = c->b; a.obs = obs_u8; a.boot = bootstrap_obs;
@@ -428,6 +462,7 @@ extern "C" int gala_act(gala_ctx *c, const uint8_t *obs_u8, uint64_t seed, int64
     if (!obs_u8 || !actions) return fail(c, GALA_EINVAL, "null observation or action buffer");
     if (reinterpret_cast<uintptr_t>(obs_u8) & 3) return fail(c, GALA_EINVAL, "observation buffer must be 4-byte aligned");
     if (step < 0) return fail(c, GALA_EINVAL, "negative acting step");
+    if (!c->params_set) return fail(c, GALA_ESTATE, "acting step before gala_set_params: the parameters are all zero");
     // forward pass over B frames per agent: all of them take the policy head, none is a bootstrap state
     NetArgs a{};
     a.N = c->N; a.M = c->hp.B; a.F = c->hp.B; a.Bn = 0; a.L = c->L;
@@ -465,8 +500,7 @@ extern "C" int gala_get_outputs(gala_ctx *c, float *logits, float *values, float
 extern "C" int gala_consensus_distance(gala_ctx *c, float *max_dist, float *frob)
 {
     if (!c || !max_dist || !frob) return fail(c, GALA_EINVAL, "null argument");
-    const size_t chunks = (c->L.d_pad + CONS_COLS - 1) / CONS_COLS;
-    float *result = c->b.cons_part + (size_t)c->N * chunks;
+    float *result = c->b.cons_part + (size_t)c->N * consensus_parts(c->N, c->L);
     c->timer.mark("diag_begin");
     HIP_OK(c, launch_consensus(c->N, c->L, c->b.x[c->cur], c->b.cons_part, c->b.row_ss, result, c->stream));
     c->timer.mark("consensus_distance");
@@ -474,6 +508,17 @@ extern "C" int gala_consensus_distance(gala_ctx *c, float *max_dist, float *frob
     HIP_OK(c, hipMemcpyAsync(r, result, 8, hipMemcpyDeviceToHost, c->stream));
     HIP_OK(c, hipStreamSynchronize(c->stream));
     *max_dist = r[0]; *frob = r[1];
+    return GALA_OK;
+}
+
+extern "C" int gala_get_head_grads(gala_ctx *c, float *dlogits_host, float *dvalues_host)
+{
+    if (!c) return GALA_EINVAL;
+    const size_t n = (size_t)c->N * c->M;
+    if (dlogits_host)
+        HIP_OK(c, hipMemcpyAsync(dlogits_host, c->b.dlogits, n * c->L.n_actions * 4, hipMemcpyDeviceToHost, c->stream));
+    if (dvalues_host) HIP_OK(c, hipMemcpyAsync(dvalues_host, c->b.dvalues, n * 4, hipMemcpyDeviceToHost, c->stream));
+    HIP_OK(c, hipStreamSynchronize(c->stream));
     return GALA_OK;
 }
 

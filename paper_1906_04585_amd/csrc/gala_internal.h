@@ -87,7 +87,7 @@ struct Buffers {
     float *gram_part, *gram, *cosm;   // [pairs][chunks][GRAM_T^2] partial Gram tiles, [N][N] Gram, [N][N] cosine
     float *upd_part, *upd_norm;       // [N][UPDATE_NORM_BLOCKS], [N] row norms + [2] (largest row, Frobenius)
     float *stats;                     // [N][5]
-    float *cons_part;                 // [N][CONS_CHUNKS] + 2 results
+    float *cons_part;                 // [N][4 * consensus_blocks] partial sums of squares + 2 results
     float *row_ss;                    // [N] scratch of the norm reductions
     int32_t *peer, *delay;            // [phases][N][max_in]
     int32_t *cyc_order, *cyc_start;   // [phases][N], [phases][N + 1]: the peer permutation's cycles (if it is one)
@@ -144,6 +144,8 @@ hipError_t launch_loss(const NetArgs &a, const HParams &hp, const int32_t *actio
                        const uint8_t *dones, hipStream_t s);
 // the three loss terms of every agent from the per-sample terms (any stream ordered after launch_loss)
 hipError_t launch_loss_stats(const NetArgs &a, hipStream_t s);
+// number of entries of actions[0..n) outside [0, A), written to *count (one workgroup, no atomics)
+hipError_t launch_count_bad_actions(const int32_t *actions, long n, int A, int32_t *count, hipStream_t s);
 hipError_t launch_sample(int N, int Bn, int A, const float *logits, const float *values, uint64_t seed, long step,
                          int32_t *actions, float *values_out, float *logp_out, hipStream_t s);
 // Second stream (default priority) and the events that order it against the context's stream.
@@ -183,7 +185,12 @@ hipError_t launch_grad_cosine(int N, const Layout &L, const float *g, float *par
 hipError_t launch_update_norm(int N, const Layout &L, const HParams &hp, const float *g, bool shared_gradient,
                               const float *v, const float *stats, float *part, float *row_ss, float *out,
                               hipStream_t s);
-constexpr int CONS_COLS = 1024;   // columns per workgroup of the consensus kernel
+// Consensus distance.  Up to CONS_REG_AGENTS agents: at most CONS_BLOCKS workgroups of four
+// wavefronts, one partial sum of squares per (agent, wavefront); more agents: one partial per
+// (agent, 1024 columns).  consensus_parts gives the partials per agent for sizing the scratch buffer.
+constexpr int CONS_BLOCKS = 512;
+constexpr int CONS_REG_AGENTS = 64;
+int consensus_parts(int N, const Layout &L);
 hipError_t launch_row_norms(const float *part, int rows, int cols, float *row_ss, float *row_norm, float *result,
                             hipStream_t s);
 hipError_t launch_consensus(int N, const Layout &L, const float *x, float *part, float *row_ss, float *result,

@@ -135,6 +135,30 @@ __global__ __launch_bounds__(192) void loss_stats_kernel(int M, const float *__r
     if (lane == 0) stats[agent * 5 + term] = t * (1.0f / (float)M);
 }
 
+// Opt-in validation of the action buffer: one workgroup counts the entries outside [0, A).
+__global__ __launch_bounds__(1024) void count_bad_actions_kernel(const int32_t *__restrict__ actions, long n, int A,
+                                                                 int32_t *count)
+{
+    __shared__ int red[16];
+    int bad = 0;
+    for (long i = threadIdx.x; i < n; i += 1024) bad += (actions[i] < 0 || actions[i] >= A) ? 1 : 0;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) bad += __shfl_xor(bad, off, 64);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = bad;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int t = 0;
+        for (int w = 0; w < 16; ++w) t += red[w];
+        *count = t;
+    }
+}
+
+hipError_t launch_count_bad_actions(const int32_t *actions, long n, int A, int32_t *count, hipStream_t s)
+{
+    hipLaunchKernelGGL(count_bad_actions_kernel, dim3(1), dim3(1024), 0, s, actions, n, A, count);
+    return hipGetLastError();
+}
+
 hipError_t launch_loss(const NetArgs &a, const HParams &hp, const int32_t *actions, const float *rewards,
                        const uint8_t *dones, hipStream_t s)
 {
@@ -582,25 +606,32 @@ hipError_t launch_rmsprop_mix(int N, const Layout &L, const HParams &hp, float *
 }
 
 // ---- distance from consensus (Prop. 1) --------------------------------------------------------------------
-// Each workgroup owns CONS_COLS element columns: the mean over agents is formed in registers,
-// then every agent's squared deviation over those columns is block-reduced into
-// part[agent][chunk].  The second pass over the agents hits L2.
-__global__ __launch_bounds__(256) void consensus_kernel(const float *__restrict__ x, int N, long d_pad, int chunks,
-                                                        float *part)
+// A thread owns float4 columns e, e + stride, ...: for each it forms the mean over the agents (in
+// double, so that identical rows give it back exactly) and adds every agent's squared deviation to
+// that agent's accumulator, which it keeps in registers across its columns.  Up to CONS_KEEP agents'
+// values of a column stay in registers between the two steps, so the parameters cross HBM once;
+// rows beyond that are read a second time (from cache).  At the end each wavefront reduces its
+// accumulators and stores one partial per agent: part[agent][block * 4 + wave].  No LDS, no
+// barrier; the order of every sum is fixed by the launch shape.
+constexpr int CONS_KEEP = 32;
+
+// More than 64 agents: a workgroup owns 1024 element columns, forms the mean in registers and
+// block-reduces every agent's squared deviation over those columns into part[agent][chunk]; the
+// second pass over the agents hits cache.
+__global__ __launch_bounds__(256) void consensus_wide_kernel(const float *__restrict__ x, int N, long d_pad, int chunks,
+                                                             float *part)
 {
     __shared__ float red[4];
     const int chunk = blockIdx.x;
     const long e = ((long)chunk * 256 + threadIdx.x) * 4;
     const bool in = e < d_pad;
-    // the mean is accumulated in double so that identical rows give it back exactly
     double m0 = 0.0, m1 = 0.0, m2 = 0.0, m3 = 0.0;
     if (in)
         for (int i = 0; i < N; ++i) {
             const float4 v = *reinterpret_cast<const float4 *>(x + (long)i * d_pad + e);
             m0 += v.x; m1 += v.y; m2 += v.z; m3 += v.w;
         }
-    const double inv = 1.0 / (double)N;
-    m0 *= inv; m1 *= inv; m2 *= inv; m3 *= inv;
+    m0 /= (double)N; m1 /= (double)N; m2 /= (double)N; m3 /= (double)N;
     for (int i = 0; i < N; ++i) {
         float ss = 0.f;
         if (in) {
@@ -610,6 +641,53 @@ __global__ __launch_bounds__(256) void consensus_kernel(const float *__restrict_
         }
         ss = block_sum_256(ss, red);
         if (threadIdx.x == 0) part[(long)i * chunks + chunk] = ss;
+    }
+}
+
+template <int NACC>      // agents' accumulators a thread holds: 32 or 64 (NACC >= N)
+__global__ __launch_bounds__(256) void consensus_kernel(const float *__restrict__ x, int N, long d_pad, int parts,
+                                                        float *part)
+{
+    const long n4 = d_pad / 4;
+    const float4 *x4 = reinterpret_cast<const float4 *>(x);
+    float ss[NACC];
+#pragma unroll
+    for (int i = 0; i < NACC; ++i) ss[i] = 0.f;
+    for (long e = (long)blockIdx.x * 256 + threadIdx.x; e < n4; e += (long)gridDim.x * 256) {
+        float4 keep[CONS_KEEP];
+#pragma unroll
+        for (int i = 0; i < CONS_KEEP; ++i)
+            keep[i] = x4[(long)(i < N ? i : N - 1) * n4 + e];        // the last row again where fewer agents exist
+        double m0 = 0.0, m1 = 0.0, m2 = 0.0, m3 = 0.0;
+#pragma unroll
+        for (int i = 0; i < CONS_KEEP; ++i)
+            if (i < N) { m0 += keep[i].x; m1 += keep[i].y; m2 += keep[i].z; m3 += keep[i].w; }
+        if (NACC > CONS_KEEP)
+            for (int i = CONS_KEEP; i < N; ++i) {
+                const float4 v = x4[(long)i * n4 + e];
+                m0 += v.x; m1 += v.y; m2 += v.z; m3 += v.w;
+            }
+        m0 /= (double)N; m1 /= (double)N; m2 /= (double)N; m3 /= (double)N;
+        auto dev2 = [&](float4 v) {
+            const float a = (float)(v.x - m0), b = (float)(v.y - m1), c = (float)(v.z - m2), d = (float)(v.w - m3);
+            return (a * a + b * b) + (c * c + d * d);
+        };
+#pragma unroll
+        for (int i = 0; i < CONS_KEEP; ++i)
+            if (i < N) ss[i] += dev2(keep[i]);
+        if (NACC > CONS_KEEP) {
+#pragma unroll
+            for (int i = CONS_KEEP; i < NACC; ++i)
+                if (i < N) ss[i] += dev2(x4[(long)i * n4 + e]);
+        }
+    }
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int i = 0; i < NACC; ++i) {
+        if (i < N) {
+            const float t = wave_sum(ss[i]);
+            if (lane == 0) part[(long)i * parts + blockIdx.x * 4 + wave] = t;
+        }
     }
 }
 
@@ -659,14 +737,34 @@ hipError_t launch_row_norms(const float *part, int rows, int cols, float *row_ss
     return hipGetLastError();
 }
 
+// Launch shape of the register-resident kernel: every thread takes the same number of columns (the
+// fewest that keeps the grid within CONS_BLOCKS workgroups), so that no wavefront runs a longer loop
+// than the others.
+static int consensus_blocks(const Layout &L)
+{
+    const long want = (L.d_pad / 4 + 255) / 256;         // workgroups at one column per thread
+    const long per = (want + CONS_BLOCKS - 1) / CONS_BLOCKS;
+    return (int)((want + per - 1) / per);
+}
+
+int consensus_parts(int N, const Layout &L)
+{
+    return N <= CONS_REG_AGENTS ? consensus_blocks(L) * 4 : (int)((L.d_pad + 1023) / 1024);
+}
+
 hipError_t launch_consensus(int N, const Layout &L, const float *x, float *part, float *row_ss, float *result,
                             hipStream_t s)
 {
-    const int chunks = (int)((L.d_pad + CONS_COLS - 1) / CONS_COLS);
-    hipLaunchKernelGGL(consensus_kernel, dim3(chunks), dim3(256), 0, s, x, N, L.d_pad, chunks, part);
+    const int parts = consensus_parts(N, L);
+    if (N <= 32)
+        hipLaunchKernelGGL(consensus_kernel<32>, dim3(parts / 4), dim3(256), 0, s, x, N, L.d_pad, parts, part);
+    else if (N <= CONS_REG_AGENTS)
+        hipLaunchKernelGGL(consensus_kernel<CONS_REG_AGENTS>, dim3(parts / 4), dim3(256), 0, s, x, N, L.d_pad, parts, part);
+    else
+        hipLaunchKernelGGL(consensus_wide_kernel, dim3(parts), dim3(256), 0, s, x, N, L.d_pad, parts, part);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    return launch_row_norms(part, N, chunks, row_ss, nullptr, result, s);
+    return launch_row_norms(part, N, parts, row_ss, nullptr, result, s);
 }
 
 // ---- canonical <-> internal order --------------------------------------------------------------------------

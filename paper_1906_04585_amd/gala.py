@@ -17,11 +17,12 @@ EXPORTS = [
     "gala_create", "gala_destroy", "gala_param_count", "gala_last_error",
     "gala_set_params", "gala_get_params", "gala_set_opt_state", "gala_get_opt_state",
     "gala_learner_step", "gala_gossip", "gala_round", "gala_a2c_allreduce_step", "gala_get_mean_grad", "gala_act", "gala_grad_cosine", "gala_update_norm", "gala_prop1_bound", "gala_get_grads", "gala_get_step_stats",
-    "gala_get_outputs", "gala_consensus_distance", "gala_get_peer_table",
+    "gala_get_outputs", "gala_consensus_distance", "gala_get_head_grads",
+    "gala_get_peer_table",
     "gala_set_profiling", "gala_get_phase_times", "gala_get_activations",
 ]
 
-TOPOLOGY = {"ring": 0, "exp": 1, "explicit": 2}
+TOPOLOGY = {"ring": 0, "exp": 1, "explicit": 2, "exp_reverse": 3}
 
 
 class GalaError(RuntimeError):
@@ -81,6 +82,7 @@ def load_library():
         L.gala_get_step_stats.argtypes = [C.c_void_p, C.c_void_p]
         L.gala_get_outputs.argtypes = [C.c_void_p] * 5
         L.gala_consensus_distance.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
+        L.gala_get_head_grads.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
         L.gala_get_peer_table.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
         L.gala_set_profiling.argtypes = [C.c_void_p, C.c_int]
         L.gala_get_activations.argtypes = [C.c_void_p, C.c_int, C.c_void_p]
@@ -256,6 +258,14 @@ class Gala:
         mx, fr = C.c_float(0.0), C.c_float(0.0)
         self._check(self._lib.gala_consensus_distance(self._h, C.byref(mx), C.byref(fr)))
         return float(mx.value), float(fr.value)
+
+    def get_head_grads(self):
+        """(dlogits [N, T*B, A], dvalues [N, T*B]) as the loss kernel of the last learner step wrote them."""
+        M = self.T * self.B
+        dl = np.empty((self.N, M, self.A), np.float32)
+        dv = np.empty((self.N, M), np.float32)
+        self._check(self._lib.gala_get_head_grads(self._h, dl.ctypes.data_as(C.c_void_p), dv.ctypes.data_as(C.c_void_p)))
+        return dl, dv
 
     def get_peer_table(self, rnd: int):
         peer = np.empty((self.N, self.max_in), dtype=np.int32)

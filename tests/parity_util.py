@@ -82,30 +82,6 @@ def pg_scale(net, hp, x, ro: dict, i: int) -> float:
     return loss_conditioning(net, hp, x, ro, i)[0]
 
 
-# Last resort for a gradient tensor that misses the criterion in an ill-conditioned state (sums
-# over samples of advantages of both signs times large activations): how far does the *exact*
-# gradient move when the parameters are perturbed by one unit of single-precision round-off?  The
-# fp32 computation rounds at every one of its stages: its activations agree with exact arithmetic
-# to about 1e-6 of a layer's largest value (eight units of round-off, what sums over thousands of
-# terms through four layers leave), several times what a one-unit perturbation of the parameters
-# produces, and the backward pass adds as much again.  PERTURB_FACTOR such movements are granted
-# on top of the tolerance.  In well-conditioned states the movement is ~1e-7 of the tensor and
-# changes nothing.
-PERTURB_FACTOR = 16.0
-
-
-def perturbation_response(net, hp, x, ro: dict, i: int) -> np.ndarray:
-    """|g(x (1 + u r)) - g(x)| per parameter, u = 2^-23, r uniform in (-1, 1), from the oracle."""
-    from oracle import gala_oracle as orc
-    T, B = ro["actions"].shape[1:3]
-    x = np.asarray(x, dtype=np.float64)
-    r = np.random.default_rng(12345 + i).uniform(-1.0, 1.0, size=x.shape)
-    args = (ro["obs"][i], ro["actions"][i], ro["rewards"][i], ro["dones"][i], ro["boot_obs"][i])
-    g0, _ = orc.agent_gradient(net, T, B, hp, x, *args)
-    g1, _ = orc.agent_gradient(net, T, B, hp, x * (1.0 + 2.0 ** -23 * r), *args)
-    return np.abs(g1 - g0)
-
-
 def upload(ro: dict):
     import torch
     return {k: torch.from_numpy(np.ascontiguousarray(v)).cuda() for k, v in ro.items()}
@@ -170,28 +146,42 @@ def step_both(gpu, orc_model, ro: dict, dev: dict | None = None):
     return marked
 
 
-def compare_learner_step(gpu, orc_model, net, tag="", rtol=RTOL, ro=None, X_before=None):
+def compare_learner_step(gpu, orc_model, net, tag="", rtol=RTOL, ro=None, X_before=None, max_cond=None, plain=False):
     """Gradients per tensor and agent, loss terms, norms, clip factors, parameters, RMSprop state.
-    With the rollout and the pre-step parameters the policy term is measured against pg_scale."""
+
+    With the rollout and the pre-step parameters the policy term is measured against pg_scale and the
+    conditioning factors kappa (all gradients) and max(1, TERM_FRACTION * rho_v) (value head) widen the
+    gradient tolerances; without them every tensor is held to the plain rtol.  Returns the worst
+    error per tensor (already divided by the factor applied) under the tensor's name, and the largest
+    factors applied under "kappa" and "rho_v_factor"; both are printed.  max_cond, when given, is an
+    upper bound both factors must respect: a round started from freshly initialised parameters passes
+    it as 2, so that such a round demonstrably passes at (about) the plain rtol.  plain=True computes
+    the factors (they are printed and returned) but applies none: every tensor is held to rtol itself
+    and only the policy term keeps its pg_scale."""
     sl = gs.segment_slices(net)
     g = gpu.get_grads()
     worst = {}
     cond = [loss_conditioning(net, orc_model.hp, X_before[i], ro, i) if ro is not None else (0.0, 1.0, 1.0)
             for i in range(gpu.N)]
+    kappa_max = max(c[1] for c in cond)
+    rho_factor_max = max(max(1.0, TERM_FRACTION * c[2]) for c in cond)
+    if plain:
+        print(f"{tag}: plain tolerance (conditioning factors kappa {kappa_max:.3f}, value head {rho_factor_max:.3f} "
+              f"computed, not applied)", flush=True)
+        cond = [(c[0], 1.0, 1.0) for c in cond]
+    else:
+        print(f"{tag}: " + ("plain tolerance, no conditioning factors" if ro is None else
+                            f"largest conditioning factors applied: kappa {kappa_max:.3f}, value head {rho_factor_max:.3f}"),
+              flush=True)
+    if max_cond is not None:
+        assert kappa_max <= max_cond and rho_factor_max <= max_cond, \
+            f"{tag}: conditioning factors kappa {kappa_max:.2f}, value head {rho_factor_max:.2f} exceed {max_cond}"
     for i in range(gpu.N):
-        resp = None
         for name, s in sl.items():
             scale = grad_scale(orc_model.grads[i], sl, name)
             if name.startswith("v."):
                 scale *= max(1.0, TERM_FRACTION * cond[i][2])
             e = rel_err(g[i, s], orc_model.grads[i, s], scale)
-            if e > rtol * cond[i][1] and ro is not None:
-                resp = perturbation_response(net, orc_model.hp, X_before[i], ro, i) if resp is None else resp
-                slack = PERTURB_FACTOR * float(resp[s].max())
-                assert np.abs(g[i, s] - orc_model.grads[i, s]).max() <= rtol * cond[i][1] * scale + slack, \
-                    f"{tag} grad {name} agent {i}: rel err {e:.3e} (kappa {cond[i][1]:.1f}, slack {slack / scale:.2e})"
-                print(f"{tag} grad {name} agent {i}: rel err {e:.3e} accepted with perturbation slack {slack / scale:.2e}")
-                continue
             worst[name] = max(worst.get(name, 0.0), e / cond[i][1])
             assert e <= rtol * cond[i][1], f"{tag} grad {name} agent {i}: rel err {e:.3e} (kappa {cond[i][1]:.1f})"
     st = gpu.get_step_stats()
@@ -213,6 +203,8 @@ def compare_learner_step(gpu, orc_model, net, tag="", rtol=RTOL, ro=None, X_befo
             # v holds squared gradients: twice the relative error, measured like the gradient
             ev = rel_err(v[i, s], orc_model.V[i, s], grad_scale(orc_model.V[i], sl, name))
             assert ev <= 2 * rtol * cond[i][1], f"{tag} rmsprop {name} agent {i}: rel err {ev:.3e}"
+    worst["kappa"] = kappa_max
+    worst["rho_v_factor"] = rho_factor_max
     return worst
 
 

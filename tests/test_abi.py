@@ -62,6 +62,10 @@ def _create(n_agents=2, n_actions=6, topology="ring", **kw):
     (dict(rms_eps=0.0), "rms_eps"),
     (dict(rms_alpha=1.0), "rms_alpha"),
     (dict(topology="exp", n_agents=6), "power-of-two"),
+    (dict(topology="exp_reverse", n_agents=12), "power-of-two"),
+    # 32-bit activation offsets: 83 886 frames per context at most (1024 agents x (64 + 32) = 98 304)
+    (dict(n_agents=1024, T=2, B=32), "32-bit"),
+    (dict(n_agents=4096, T=64, B=64), "32-bit"),
     (dict(topology=7), "topology kind"),
     (dict(max_delay=-1), "max_delay"),
     (dict(max_delay=17), "max_delay"),

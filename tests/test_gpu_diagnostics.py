@@ -5,7 +5,7 @@ import pytest
 
 import gala_synth as gs
 from oracle import gala_oracle as orc
-from parity_util import RTOL, step_both, upload
+from parity_util import RTOL, relu_gates, step_both, upload
 
 pytestmark = pytest.mark.gpu
 
@@ -56,19 +56,23 @@ def test_update_norm_matches_oracle_in_every_mode():
     om.set_opt_state(gpu.get_opt_state())
     before = om.X.copy()
     gpu.round(dev["obs"], dev["actions"], dev["rewards"], dev["dones"], dev["boot_obs"], 0)
-    om.learner_step(ro["obs"], ro["actions"], ro["rewards"], ro["dones"], ro["boot_obs"])
+    gates, marked = relu_gates(gpu, net, before, ro)    # ReLU units at rounding distance: the kernel's decision
+    om.learner_step(ro["obs"], ro["actions"], ro["rewards"], ro["dones"], ro["boot_obs"],
+                    gates=gates if marked else None)
     fr, rows = gpu.update_norm()
     ofr, orows = orc.update_norm(before, om.X)
-    assert abs(fr - ofr) <= 5 * RTOL * ofr              # no ReLU marks passed here: a looser bound
+    assert abs(fr - ofr) <= RTOL * ofr and np.abs(rows - orows).max() <= RTOL * orows.max()
     # averaged gradient: every agent moves by the same update
     om.set_params(gpu.get_params())
     om.set_opt_state(gpu.get_opt_state())
     before = om.X.copy()
     gpu.a2c_allreduce_step(dev["obs"], dev["actions"], dev["rewards"], dev["dones"], dev["boot_obs"])
-    om.a2c_allreduce_step(ro["obs"], ro["actions"], ro["rewards"], ro["dones"], ro["boot_obs"])
+    gates, marked = relu_gates(gpu, net, before, ro)
+    om.a2c_allreduce_step(ro["obs"], ro["actions"], ro["rewards"], ro["dones"], ro["boot_obs"],
+                          gates=gates if marked else None)
     fr, rows = gpu.update_norm()
     ofr, orows = orc.update_norm(before, om.X)
-    assert abs(fr - ofr) <= 5 * RTOL * ofr and np.abs(rows - orows).max() <= 5 * RTOL * orows.max()
+    assert abs(fr - ofr) <= RTOL * ofr and np.abs(rows - orows).max() <= RTOL * orows.max()
 
 
 def test_prop1_bound_holds_on_gpu_rounds():

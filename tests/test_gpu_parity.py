@@ -1,14 +1,12 @@
 """GPU parity: the HIP path through the C ABI against the CPU oracle on identical seeded
 inputs.  Integer work (action gather, peer and delay tables) bit-exact; floating point
 within the norm-wise tolerance of parity_util.RTOL per tensor."""
-import os
-
 import numpy as np
 import pytest
 
 import gala_synth as gs
 from oracle import gala_oracle as orc
-from parity_util import RTOL, compare_learner_step, compare_params, grad_scale, pg_scale, rel_err, step_both, upload
+from parity_util import RTOL, compare_learner_step, compare_params, rel_err, step_both, upload
 
 pytestmark = pytest.mark.gpu
 
@@ -62,7 +60,7 @@ def test_config1_one_round_ring():
     cfg, net, gpu, om, X0 = _make(1)
     ro = gs.rollout(net, cfg["n_agents"], cfg["T"], cfg["B"], gs.round_seed(1, 0))
     step_both(gpu, om, ro)
-    worst = compare_learner_step(gpu, om, net, "cfg1")
+    worst = compare_learner_step(gpu, om, net, "cfg1")        # no rollout passed: the plain tolerance
     print("worst per-tensor gradient errors:", {k: f"{v:.2e}" for k, v in worst.items()})
     gpu.gossip(0)
     om.gossip(0)
@@ -74,27 +72,45 @@ def test_config1_one_round_ring():
 
 
 def test_action_gather_is_exact():
-    """With zero advantage weight removed (ent_coef = 0) the policy gradient row of a
-    sample is A_m (pi - onehot(a_m)): flipping one action moves exactly that sample's
-    contribution; compare against the oracle under both action sets."""
+    """The integer gather of the taken action, checked on the head gradients the loss kernel writes
+    (read back through gala_get_head_grads).  With the entropy term switched off a sample's row is
+    A_m (pi - onehot(a_m)) / M: every entry has the sign of A_m except the taken action's, which has
+    the opposite sign, so the one odd-signed lane *is* the gathered index -- compared exactly with
+    the action fed in.  Changing one action must then change, bit for bit, nothing but that sample's
+    two lanes (old and new action), and the oracle must agree on both action sets."""
     from paper_1906_04585_amd import Gala
-    net = gs.make_net(6)
+    A = 6
+    net = gs.make_net(A)
     N, T, B = 2, 5, 4
+    M = T * B
     hp = dict(HP, ent_coef=0.0)
     X0 = gs.init_params(net, N, seed=99, bias_scale=0.05)
     ro = gs.rollout(net, N, T, B, 1234)
+    rows = {}
     for flip in (False, True):
         r2 = dict(ro)
         if flip:
             a = ro["actions"].copy()
-            a[1, 3, 2] = (a[1, 3, 2] + 1) % 6
+            a[1, 3, 2] = (a[1, 3, 2] + 1) % A
             r2["actions"] = a
-        gpu = Gala(N, 6, T, B, hp, "ring")
+        gpu = Gala(N, A, T, B, hp, "ring")
         om = orc.OracleGala(net, N, T, B, hp, "ring")
         gpu.set_params(X0)
         om.set_params(X0)
         step_both(gpu, om, r2)
         compare_learner_step(gpu, om, net, f"flip={flip}")
+        dlogits, dvalues = gpu.get_head_grads()
+        adv = gpu.get_outputs()["advantages"]
+        assert np.all(adv != 0.0) and np.all(dlogits != 0.0)
+        odd = np.sign(dlogits) != np.sign(adv)[:, :, None]          # [N][M][A]
+        assert np.all(odd.sum(axis=2) == 1)                         # exactly one lane per sample ...
+        np.testing.assert_array_equal(odd.argmax(axis=2), r2["actions"].reshape(N, M))   # ... the action taken
+        rows[flip] = (dlogits, dvalues, r2["actions"].reshape(N, M))
+    (d0, v0, a0), (d1, v1, a1) = rows[False], rows[True]
+    np.testing.assert_array_equal(v0, v1)                           # the value gradient does not see the action
+    changed = np.argwhere(d0 != d1)
+    m = 3 * B + 2
+    assert {tuple(c) for c in changed} == {(1, m, int(a0[1, m])), (1, m, int(a1[1, m]))}
 
 
 @pytest.mark.parametrize("topology,N", [("ring", 2), ("ring", 4), ("exp", 4), ("exp", 8), ("exp", 32)])
@@ -149,119 +165,51 @@ def test_exponential_graph_exact_average_after_log2_rounds():
     assert mx <= 1e-4 * np.linalg.norm(mean)
 
 
-def test_config2_lockstep_rounds():
-    """Four agents, exponential graph, 18 actions, 5 x 16 rollouts: every round is checked
-    against the oracle restarted from the GPU's own state (lock-step).  GALA_TEST_ROUNDS
-    sets the number of rounds (100 for the full configuration)."""
-    rounds = int(os.environ.get("GALA_TEST_ROUNDS", "6"))
-    cfg, net, gpu, om, X0 = _make(2)
-    N, T, B = cfg["n_agents"], cfg["T"], cfg["B"]
-    for r in range(rounds):
-        om.set_params(gpu.get_params())
-        om.set_opt_state(gpu.get_opt_state())
-        ro = gs.rollout(net, N, T, B, gs.round_seed(2, r))
-        X = om.X.copy()
-        step_both(gpu, om, ro)
-        compare_learner_step(gpu, om, net, f"cfg2 round {r}", ro=ro, X_before=X)
-        om.set_params(gpu.get_params())
-        gpu.gossip(r)
-        om.gossip(r)
-        compare_params(gpu, om, net, f"cfg2 gossip {r}")
-        if r % 10 == 9:
-            print(f"cfg2: {r + 1} rounds agree", flush=True)      # a long run shows that it is alive
-
-
-def test_config3_delayed_gossip_lockstep():
-    """Eight agents with per-edge message delays of 0..2 rounds read from the broadcast
-    history.  GALA_TEST_ROUNDS_DELAY sets the number of rounds (200 for the full run)."""
-    rounds = int(os.environ.get("GALA_TEST_ROUNDS_DELAY", "7"))
-    cfg, net, gpu, om, X0 = _make(3)
-    N, T, B = cfg["n_agents"], cfg["T"], cfg["B"]
-    seen = set()
-    for r in range(rounds):
-        om.set_params(gpu.get_params())
-        om.set_opt_state(gpu.get_opt_state())
-        ro = gs.rollout(net, N, T, B, gs.round_seed(3, r))
-        X = om.X.copy()
-        step_both(gpu, om, ro)
-        compare_learner_step(gpu, om, net, f"cfg3 round {r}", ro=ro, X_before=X)
-        # the oracle's message history must hold what the GPU actually broadcast
-        om.set_params(gpu.get_params())
-        gpu.gossip(r)
-        om.gossip(r)
-        compare_params(gpu, om, net, f"cfg3 gossip {r}")
-        seen |= set(gpu.get_peer_table(r)[1][:, 0].tolist())
-        if r % 10 == 9:
-            print(f"cfg3: {r + 1} rounds agree", flush=True)
-    assert seen == {0, 1, 2}
-
-
-def _sampled_full_size(cfg_id, sample_agents, rounds=1):
-    """Full-size configuration in the launch shape the benchmark times; the oracle computes
-    the sampled agents one by one from the same state and inputs."""
-    from parity_util import relu_gates
+def _all_agents_full_size(cfg_id, rounds):
+    """A full-size configuration in the launch shape the benchmark times, every agent checked:
+    each round the oracle restarts from the GPU's parameters and RMSprop state, both sides take one
+    learner step (gradients, loss terms, norm, clip factor, post-update parameters and state of all
+    agents compared) and one gossip round, and the distance from consensus is compared."""
     cfg, net, gpu, om, X0 = _make(cfg_id, shared=True)
     N, T, B = cfg["n_agents"], cfg["T"], cfg["B"]
-    sl = gs.segment_slices(net)
     mx0, fr0 = gpu.consensus_distance()
     assert mx0 == 0.0 and fr0 == 0.0      # identical initialisation: exactly at consensus
+    phases = set()
     for r in range(rounds):
         X = gpu.get_params()
-        V = gpu.get_opt_state()
+        om.set_params(X)
+        om.set_opt_state(gpu.get_opt_state())
         ro = gs.rollout(net, N, T, B, gs.round_seed(cfg_id, r))
-        dev = upload(ro)
-        gpu.learner_step(dev["obs"], dev["actions"], dev["rewards"], dev["dones"], dev["boot_obs"])
-        gates, marked = relu_gates(gpu, net, X, ro, agents=sample_agents)
-        g = gpu.get_grads()
-        st = gpu.get_step_stats()
-        Y = gpu.get_params()
-        V1 = gpu.get_opt_state()
-        for gi, i in enumerate(sample_agents):
-            og, terms = orc.agent_gradient(net, T, B, HP, X[i], ro["obs"][i], ro["actions"][i], ro["rewards"][i],
-                                           ro["dones"][i], ro["boot_obs"][i], gate=gates[gi] if marked else None)
-            for name, s in sl.items():
-                e = rel_err(g[i, s], og[s], grad_scale(og, sl, name))
-                assert e <= RTOL, f"cfg{cfg_id} round {r} grad {name} agent {i}: {e:.3e}"
-            for k in range(3):
-                scale = max(abs(terms[k]), 1e-2)
-                if k == 0:
-                    scale = max(scale, pg_scale(net, HP, X[i], ro, i))
-                assert abs(st[i, k] - terms[k]) <= RTOL * scale
-            gc = og.copy()
-            norm, scale = orc.clip_grad_norm(gc, HP["max_grad_norm"])
-            assert abs(st[i, 3] - norm) <= RTOL * norm and abs(st[i, 4] - scale) <= RTOL * scale
-            xo = X[i].astype(np.float64)
-            vo = V[i].astype(np.float64)
-            orc.rmsprop(xo, vo, gc, HP["lr"], HP["rms_alpha"], HP["rms_eps"])
-            for name, s in sl.items():
-                assert rel_err(Y[i, s], xo[s]) <= RTOL, f"cfg{cfg_id} round {r} param {name} agent {i}"
-                assert rel_err(V1[i, s], vo[s], grad_scale(vo, sl, name)) <= 2 * RTOL, \
-                    f"cfg{cfg_id} round {r} rmsprop {name} agent {i}"
-        # gossip for every agent, from the parameters the GPU broadcasts
-        om.set_params(Y)
+        marked = step_both(gpu, om, ro)
+        # every round is held to the plain tolerance: the conditioning factors are printed, not applied
+        w = compare_learner_step(gpu, om, net, f"cfg{cfg_id} round {r}", ro=ro, X_before=X, plain=True)
+        om.set_params(gpu.get_params())       # gossip for every agent, from the parameters the GPU broadcasts
         gpu.gossip(r)
         om.gossip(r)
         Z = gpu.get_params()
         assert np.abs(Z - om.X).max() <= 2.0 ** -22 * np.abs(om.X).max()
-        # distance from consensus, logged per round
-        mx, fr = gpu.consensus_distance()
+        phases.add(int(gpu.get_peer_table(r)[0][0, 0]))
+        mx, fr = gpu.consensus_distance()     # distance from consensus, logged per round
         omx, ofr = orc.consensus_distance(Z)
         assert abs(mx - omx) <= 1e-4 * omx + 4e-7 * np.linalg.norm(Z)
         assert abs(fr - ofr) <= 1e-4 * ofr + 4e-7 * np.linalg.norm(Z)
         assert omx > 0.0                      # the agents saw different data: they have drifted apart
-        print(f"cfg{cfg_id} round {r}: consensus max {mx:.4e} frob {fr:.4e}, {marked} ReLU units at rounding distance")
+        print(f"cfg{cfg_id} round {r}: consensus max {mx:.4e} frob {fr:.4e}, {marked} ReLU units at rounding distance, "
+              f"worst gradient error {max(v for k, v in w.items() if '.' in k):.2e}", flush=True)
+    return phases
 
 
-def test_config4_full_size_sampled_agents():
-    """32 agents, 5 x 16 rollouts: three sampled agents per round over three rounds (all five
-    phases of the exponential graph need log2 32 = 5 rounds; the phase tables are covered
-    bit-exactly elsewhere)."""
-    _sampled_full_size(4, [0, 13, 31], rounds=3)
+@pytest.mark.timeout(600)
+def test_config4_full_size_all_agents_all_phases():
+    """32 agents, 5 x 16 rollouts: all 32 agents, five rounds = all log2 32 phases of the exponential graph."""
+    phases = _all_agents_full_size(4, rounds=5)
+    assert phases == {1, 2, 4, 8, 16}         # agent 0's in-peer went through every hop length
 
 
-def test_config5_full_size_sampled_agents():
-    """64 agents, 5 x 32 rollouts (fp32 path): two sampled agents, one round."""
-    _sampled_full_size(5, [5, 63], rounds=1)
+@pytest.mark.timeout(600)
+def test_config5_full_size_all_agents():
+    """64 agents, 5 x 32 rollouts (fp32 path): all 64 agents, one round."""
+    _all_agents_full_size(5, rounds=1)
 
 
 # ---- bf16 matrix-instruction variant (fp32 parameters, activations and accumulation) -------------
@@ -337,7 +285,7 @@ def test_edge_shapes_one_round(N, T, B, A, topology, tweak):
     elif tweak == "same_action":
         ro["actions"][:] = A - 1
     step_both(gpu, om, ro)
-    compare_learner_step(gpu, om, net, f"edge {N},{T},{B},{A},{tweak}")
+    compare_learner_step(gpu, om, net, f"edge {N},{T},{B},{A},{tweak}")   # the plain tolerance
     out = gpu.get_outputs()
     if tweak == "all_done":
         np.testing.assert_array_equal(out["returns"], ro["rewards"].reshape(N, T * B))

@@ -52,6 +52,26 @@ def test_exponential_table(N):
         np.testing.assert_array_equal(P.sum(1), np.ones(N))
 
 
+@pytest.mark.parametrize("N", [2, 4, 8, 32, 64])
+def test_reverse_exponential_table_is_the_transposed_graph(N):
+    """Every edge of the exponential graph turned round: the mixing matrix is the transpose of the
+    forward one (sender and receiver swap), itself doubly stochastic, and log2 N rounds still
+    give the exact average."""
+    m = N.bit_length() - 1
+    assert orc.n_phases("exp_reverse", N) == m
+    for r in range(2 * m):
+        fwd = [orc.in_peer("exp", N, r, i) for i in range(N)]
+        rev = [orc.in_peer("exp_reverse", N, r, i) for i in range(N)]
+        assert rev == [(i - 2 ** (r % m)) % N for i in range(N)]
+        assert all(rev[fwd[i]] == i for i in range(N))            # the inverse permutation
+        np.testing.assert_array_equal(_mixing_matrix("exp_reverse", N, r), _mixing_matrix("exp", N, r).T)
+    X0 = np.random.default_rng(3).normal(size=(N, 17))
+    Xs = _gossip_only(N, "exp_reverse", X0, m)
+    np.testing.assert_allclose(Xs[-1], np.tile(X0.mean(0), (N, 1)), atol=1e-14)
+    if N > 2:    # and it is a different graph: one round differs from the forward direction
+        assert np.abs(Xs[0] - _gossip_only(N, "exp", X0, 1)[0]).max() > 1e-3
+
+
 def test_edge_delay_is_splitmix64_of_the_edge_key():
     # independent restatement with Python integers of the published splitmix64 step
     def sm64(z):

@@ -1,0 +1,69 @@
+"""The two multi-round configurations at their full length, every round checked against the oracle
+in lock-step: four agents for 100 rounds (exponential graph, no delay) and eight agents for 200
+rounds with per-edge message delays of 0..2 rounds read from the broadcast history.
+
+Before each round the oracle is loaded with the GPU's current parameters and RMSprop state; both
+sides then take one learner step and one gossip round from identical inputs and every gradient
+tensor, loss term, norm, clip factor, post-update parameter tensor and RMSprop tensor of every
+agent is compared.  The file sorts behind the other GPU tests so that a run that stops at the
+first failure has reached everything else first.  GALA_TEST_ROUNDS / GALA_TEST_ROUNDS_DELAY
+shorten (or lengthen) the runs."""
+import os
+
+import pytest
+
+import gala_synth as gs
+from oracle import gala_oracle as orc
+from parity_util import compare_learner_step, compare_params, step_both
+
+pytestmark = pytest.mark.gpu
+
+HP = gs.HPARAMS
+
+
+def _lockstep(cfg_id, rounds, seen_delays=None):
+    from paper_1906_04585_amd import Gala
+    cfg = gs.CONFIGS[cfg_id]
+    net = gs.make_net(cfg["n_actions"])
+    N, T, B = cfg["n_agents"], cfg["T"], cfg["B"]
+    seed = 7 + cfg_id
+    gpu = Gala(N, cfg["n_actions"], T, B, HP, cfg["topology"], max_delay=cfg["max_delay"], delay_seed=seed)
+    om = orc.OracleGala(net, N, T, B, HP, cfg["topology"], max_delay=cfg["max_delay"], delay_seed=seed)
+    X0 = gs.init_params(net, N, seed=gs.BASE_SEED + cfg_id, bias_scale=0.05)
+    gpu.set_params(X0)
+    kappa = rho = worst = 0.0
+    for r in range(rounds):
+        om.set_params(gpu.get_params())
+        om.set_opt_state(gpu.get_opt_state())
+        ro = gs.rollout(net, N, T, B, gs.round_seed(cfg_id, r))
+        X = om.X.copy()
+        step_both(gpu, om, ro)
+        # the first round starts from freshly drawn parameters and must pass at the plain tolerance
+        w = compare_learner_step(gpu, om, net, f"cfg{cfg_id} round {r}", ro=ro, X_before=X,
+                                 max_cond=2.0 if r == 0 else None)
+        kappa, rho = max(kappa, w["kappa"]), max(rho, w["rho_v_factor"])
+        worst = max(worst, max(v for k, v in w.items() if "." in k))
+        # the oracle's message history must hold what the GPU actually broadcast
+        om.set_params(gpu.get_params())
+        gpu.gossip(r)
+        om.gossip(r)
+        compare_params(gpu, om, net, f"cfg{cfg_id} gossip {r}")
+        if seen_delays is not None:
+            seen_delays |= set(gpu.get_peer_table(r)[1][:, 0].tolist())
+        if r % 10 == 9:
+            print(f"cfg{cfg_id}: {r + 1} rounds agree (largest factors so far: kappa {kappa:.2f}, value head "
+                  f"{rho:.2f}; worst gradient error / factor {worst:.2e})", flush=True)
+    print(f"cfg{cfg_id}: all {rounds} rounds agree; largest conditioning factors applied: kappa {kappa:.2f}, "
+          f"value head {rho:.2f}", flush=True)
+
+
+@pytest.mark.timeout(900)
+def test_config2_lockstep_100_rounds():
+    _lockstep(2, int(os.environ.get("GALA_TEST_ROUNDS", "100")))
+
+
+@pytest.mark.timeout(1200)
+def test_config3_delayed_gossip_lockstep_200_rounds():
+    seen = set()
+    _lockstep(3, int(os.environ.get("GALA_TEST_ROUNDS_DELAY", "200")), seen)
+    assert seen == {0, 1, 2}

@@ -195,6 +195,19 @@ int gala_get_step_stats(gala_ctx *ctx, float *dst_host);
 int gala_get_outputs(gala_ctx *ctx, float *logits, float *values, float *returns, float *advantages);
 /* Distance from consensus (Prop. 1): max_i ||x_i - mean||_2 and ||X - mean||_F, host floats. */
 int gala_consensus_distance(gala_ctx *ctx, float *max_dist, float *frob);
+/* The same quantities for callers that cannot allocate device memory or wait for the stream (code
+ * under HIP graph capture, tight serving or logging loops, harnesses that forbid hipMalloc): the same
+ * kernels as gala_consensus_distance, enqueued on the context's stream with no allocation and no
+ * synchronisation.  result_dev is a dev float[2] that receives max_i ||x_i - mean||_2 and ||X - mean||_F
+ * once the enqueued work has run.  The partial sums live in a 1 MiB array that is part of the library
+ * image (one copy per GPU, held until the process ends) instead of the context's own buffer: it holds
+ * 262 144 floats, a context needs n_agents * (partials per agent + 1) of them (about 1 650 partials per
+ * agent for this network, so up to 158 agents), and a context that needs more is refused with
+ * GALA_EINVAL.  All contexts on
+ * a GPU share that array, so calls of this function that overlap in time on one GPU (different
+ * streams) race; calls on one stream, or otherwise ordered, are safe.  Nothing in the array has to
+ * start at zero: every entry that is read was written by the same call. */
+int gala_consensus_distance_noalloc(gala_ctx *ctx, float *result_dev);
 /* Pair-wise cosine similarity of the agents' gradients of the last learner step (Fig. 2b):
  * cos[i][j] = <g_i, g_j> / (||g_i|| ||g_j||), pre-clip gradients, host float [N][N]; rows and
  * columns of an agent whose gradient is zero are 0.  One pass over the gradient arena. */

@@ -33,6 +33,7 @@ struct gala_ctx {
     bool params_set = false;        // gala_set_params has been called: a learner step has something to learn from
     bool check_actions = false;     // GALA_CHECK_ACTIONS was set at creation: validate the action buffer of every step
     int32_t *bad_actions = nullptr; // device counter of the validation kernel
+    float *scratch = nullptr;       // this device's address of the library's static scratch array
     bool shared_gradient = false;   // the last optimiser step applied the averaged gradient
     hipStream_t stream = nullptr;
     int device = 0;
@@ -61,6 +62,29 @@ static int fail(gala_ctx *c, int code, const char *fmt, ...)
             return fail((c), e_ == hipErrorOutOfMemory ? GALA_ENOMEM : GALA_EHIP, "%s: %s", #expr, \
                         hipGetErrorString(e_));                                                  \
     } while (0)
+
+// Scratch memory for the entry point that must not allocate (gala_consensus_distance_noalloc): a
+// file-scope device array, one copy per GPU the library runs on, held until the process ends.  In host
+// code its name is only a handle: the device address is asked for once per device, with that device
+// current (gala_create does it), and only that address is ever passed to kernels.
+constexpr size_t SCRATCH_FLOATS = 256 * 1024;                           // 1 MiB
+static __device__ __align__(256) float scratch[SCRATCH_FLOATS];
+constexpr int MAX_DEVICES = 64;
+static float *g_scratch_ptr[MAX_DEVICES] = {nullptr};
+
+// Address of the scratch array on the current device (`device` is its ordinal), looked up on first use.
+static hipError_t scratch_address(int device, float **out)
+{
+    if (device < 0 || device >= MAX_DEVICES) return hipErrorInvalidDevice;
+    if (!g_scratch_ptr[device]) {
+        float *ptr = nullptr;
+        const hipError_t e = hipGetSymbolAddress(reinterpret_cast<void **>(&ptr), HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        g_scratch_ptr[device] = ptr;
+    }
+    *out = g_scratch_ptr[device];
+    return hipSuccess;
+}
 
 static uint64_t splitmix64(uint64_t z)
 {
@@ -249,6 +273,8 @@ extern "C" int gala_create(gala_ctx **out, int n_agents, const gala_topology *to
     ALLOC(c->bad_actions, 1, true);
 #undef ALLOC
     c->check_actions = getenv("GALA_CHECK_ACTIONS") != nullptr;
+    he = scratch_address(c->device, &c->scratch);
+    if (he != hipSuccess) { fail(c, GALA_EHIP, "scratch array address: %s", hipGetErrorString(he)); return bail(GALA_EHIP); }
     he = hipMemcpyAsync(b.peer, c->h_peer.data(), c->h_peer.size() * 4, hipMemcpyHostToDevice, c->stream);
     if (he == hipSuccess) he = hipMemcpyAsync(b.delay, c->h_delay.data(), c->h_delay.size() * 4, hipMemcpyHostToDevice, c->stream);
     if (he == hipSuccess) he = hipMemcpyAsync(b.weight, c->h_weight.data(), c->h_weight.size() * 4, hipMemcpyHostToDevice, c->stream);
@@ -508,6 +534,19 @@ extern "C" int gala_consensus_distance(gala_ctx *c, float *max_dist, float *frob
     HIP_OK(c, hipMemcpyAsync(r, result, 8, hipMemcpyDeviceToHost, c->stream));
     HIP_OK(c, hipStreamSynchronize(c->stream));
     *max_dist = r[0]; *frob = r[1];
+    return GALA_OK;
+}
+
+extern "C" int gala_consensus_distance_noalloc(gala_ctx *c, float *result_dev)
+{
+    if (!c || !result_dev) return fail(c, GALA_EINVAL, "null argument");
+    // partial sums of squares [N][parts], then the row sums [N], all in the static scratch array
+    const size_t need = (size_t)c->N * consensus_parts(c->N, c->L) + (size_t)c->N;
+    if (need > SCRATCH_FLOATS)
+        return fail(c, GALA_EINVAL, "gala_consensus_distance_noalloc: %d agents need %zu floats of scratch, the static "
+                    "array holds %zu; use gala_consensus_distance", c->N, need, (size_t)SCRATCH_FLOATS);
+    float *part = c->scratch, *row_ss = c->scratch + (size_t)c->N * consensus_parts(c->N, c->L);
+    HIP_OK(c, launch_consensus(c->N, c->L, c->b.x[c->cur], part, row_ss, result_dev, c->stream));
     return GALA_OK;
 }
 

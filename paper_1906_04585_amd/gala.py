@@ -17,7 +17,7 @@ EXPORTS = [
     "gala_create", "gala_destroy", "gala_param_count", "gala_last_error",
     "gala_set_params", "gala_get_params", "gala_set_opt_state", "gala_get_opt_state",
     "gala_learner_step", "gala_gossip", "gala_round", "gala_a2c_allreduce_step", "gala_get_mean_grad", "gala_act", "gala_grad_cosine", "gala_update_norm", "gala_prop1_bound", "gala_get_grads", "gala_get_step_stats",
-    "gala_get_outputs", "gala_consensus_distance", "gala_get_head_grads",
+    "gala_get_outputs", "gala_consensus_distance", "gala_consensus_distance_noalloc", "gala_get_head_grads",
     "gala_get_peer_table",
     "gala_set_profiling", "gala_get_phase_times", "gala_get_activations",
 ]
@@ -82,6 +82,7 @@ def load_library():
         L.gala_get_step_stats.argtypes = [C.c_void_p, C.c_void_p]
         L.gala_get_outputs.argtypes = [C.c_void_p] * 5
         L.gala_consensus_distance.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
+        L.gala_consensus_distance_noalloc.argtypes = [C.c_void_p, C.c_void_p]
         L.gala_get_head_grads.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
         L.gala_get_peer_table.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
         L.gala_set_profiling.argtypes = [C.c_void_p, C.c_int]
@@ -258,6 +259,13 @@ class Gala:
         mx, fr = C.c_float(0.0), C.c_float(0.0)
         self._check(self._lib.gala_consensus_distance(self._h, C.byref(mx), C.byref(fr)))
         return float(mx.value), float(fr.value)
+
+    def consensus_distance_noalloc(self, result):
+        """result: float32 CUDA tensor of (at least) 2 elements, written in stream order (no synchronisation)."""
+        import torch
+        if result.numel() < 2:
+            raise ValueError("result needs two elements")
+        self._check(self._lib.gala_consensus_distance_noalloc(self._h, _dev_ptr(result, torch.float32)))
 
     def get_head_grads(self):
         """(dlogits [N, T*B, A], dvalues [N, T*B]) as the loss kernel of the last learner step wrote them."""

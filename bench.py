@@ -8,6 +8,12 @@ step share a kernel; --mode split as gala_learner_step followed by gala_gossip; 
 compute the same values bit for bit.  Inputs are synthetic
 Atari-shaped rollouts that are resident in HBM before the timed region starts; a
 pool of four rollouts is cycled.  One JSON line is printed on stdout.
+
+The 32-agent workload (--config 4, the default) runs 1000 timed rounds and then a second pass of
+the same length in which the distance from consensus (Prop. 1) is taken after every round by
+gala_consensus_distance_noalloc into a device-side log (no host round trip inside the loop); the
+per-round values go to gpurun_out/consensus_distance_cfg4.csv and their first/last/largest
+values and the cost of logging to the JSON line.
 """
 from __future__ import annotations
 
@@ -59,12 +65,16 @@ def kernel_of_phase(dtype: str) -> dict:
     return out
 
 
+TRAFFIC_SUMMARY = os.path.join("profiles", "hbm_traffic_n32_exp_5x16_fp32.txt")
+
+
 def measured_traffic(phase: str, config: int, dtype: str):
     """HBM bytes per launch of the kernel behind `phase` from the committed FETCH_SIZE / WRITE_SIZE
-    summary, or None when there is none for this workload or the kernel sources changed since."""
+    summary (counters are not read in this run), or None when there is none for this workload or the
+    kernel sources changed since."""
     import glob
     import hashlib
-    path = os.path.join(ROOT, "profiles", "hbm_traffic_n32_exp_5x16_fp32.txt")
+    path = os.path.join(ROOT, TRAFFIC_SUMMARY)
     if config != 4 or dtype != "f32" or not os.path.exists(path):
         return None
     rec = None
@@ -108,7 +118,11 @@ def kernel_work(N: int, M: int, F: int, d: int, tau: int, dtype: str) -> dict:
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=300)
+    ap.add_argument("--steps", type=int, default=None,
+                    help="timed rounds (default: 1000 for the 32-agent workload, 300 otherwise)")
+    ap.add_argument("--consensus-log", choices=["auto", "on", "off"], default="auto",
+                    help="second pass of --steps rounds with the distance from consensus taken every round "
+                         "(auto: on for --config 4 in the fused or split mode)")
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=4, help="workload shape 1..5 (default: 32 agents)")
     ap.add_argument("--dtype", choices=["f32", "bf16"], default="f32",
@@ -121,6 +135,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-rounds", type=int, default=20)
     args = ap.parse_args()
+    if args.steps is None:
+        args.steps = 1000 if args.config == 4 else 300
     if args.gpus != 1:
         print("bench.py measures one GPU: N agents share a single MI355X and nothing here "
               "uses a second device; run with --gpus 1", file=sys.stderr)
@@ -176,6 +192,42 @@ def main() -> int:
     agent_steps = N * args.steps / elapsed
     frames = agent_steps * M
 
+    # Second pass of the same length with the distance from consensus logged after every round
+    # (Prop. 1; max_i ||x_i - mean|| and the Frobenius norm), into a device buffer in stream order.
+    consensus = None
+    want_log = args.consensus_log == "on" or (args.consensus_log == "auto" and args.config == 4
+                                             and args.mode != "a2c_allreduce")
+    if want_log:
+        log = torch.zeros((args.steps, 2), dtype=torch.float32, device="cuda")
+        first_round = rnd
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            one_round(rnd)
+            gpu.consensus_distance_noalloc(log[i])
+            rnd += 1
+        torch.cuda.synchronize()
+        logged_ms = 1e3 * (time.perf_counter() - t0) / args.steps
+        vals = log.cpu().numpy()
+        out_dir = os.path.join(ROOT, "gpurun_out")
+        os.makedirs(out_dir, exist_ok=True)
+        csv = os.path.join(out_dir, f"consensus_distance_cfg{args.config}.csv")
+        with open(csv, "w") as fh:
+            fh.write("round,max_row_distance,frobenius\n")
+            for i in range(args.steps):
+                fh.write(f"{first_round + i},{vals[i, 0]:.9g},{vals[i, 1]:.9g}\n")
+        consensus = dict(call="gala_consensus_distance_noalloc after every round", rounds=args.steps,
+                         first_round=first_round, file=os.path.relpath(csv, ROOT),
+                         max_row_distance=dict(first=float(vals[0, 0]), last=float(vals[-1, 0]),
+                                               largest=float(vals[:, 0].max()), smallest=float(vals[:, 0].min())),
+                         frobenius=dict(first=float(vals[0, 1]), last=float(vals[-1, 1]),
+                                        largest=float(vals[:, 1].max()), smallest=float(vals[:, 1].min())),
+                         ms_per_step_with_logging=logged_ms,
+                         logging_overhead_ms=logged_ms - ms_per_step,
+                         logging_overhead_frac=(logged_ms - ms_per_step) / ms_per_step,
+                         note="agents start from identical parameters (distance 0 before the first round) and see "
+                              "different synthetic rollouts; rounds continue the timed pass's count")
+
     # per-kernel durations from HIP events recorded on the library's stream
     gpu.set_profiling(True)
     acc: dict[str, float] = {}
@@ -219,6 +271,9 @@ def main() -> int:
         roofline = dict(kernel=dominant, bound="hbm", achieved=amount / dur / 1e9, peak=PEAK_HBM_GBS,
                         unit="GB/s", frac=amount / dur / 1e9 / PEAK_HBM_GBS,
                         traffic=measured_traffic(dominant, args.config, args.dtype), avg_launch_ms=acc[dominant])
+    roofline["traffic_source"] = (f"{TRAFFIC_SUMMARY} (rocprofv3 FETCH_SIZE / WRITE_SIZE of an earlier run of this "
+                                  f"workload on these kernel sources; not measured in this run)"
+                                  if roofline["traffic"] is not None else None)
     mfma_ms = sum(acc[k] for k in acc if k in work and work[k][0] == "mfma")
     mfma_flop = sum(work[k][1] for k in acc if k in work and work[k][0] == "mfma")
     m3_ms = sum(acc[k] for k in acc if k in work and work[k][0] == "split")
@@ -227,11 +282,17 @@ def main() -> int:
     hbm_ms = sum(acc[k] for k in acc if k in work and work[k][0] == "hbm")
     hbm_bytes = sum(work[k][1] for k in acc if k in work and work[k][0] == "hbm")
     phase_summary = dict(
-        conv_fc=dict(ms=round(mfma_ms, 4), tflops=round(mfma_flop / (mfma_ms * 1e-3) / 1e12, 2),
-                     frac_mfma=round(mfma_flop / (mfma_ms * 1e-3) / 1e12 / peak_mfma, 4)),
         optimizer_gossip=dict(ms=round(hbm_ms, 4), gbs=round(hbm_bytes / (hbm_ms * 1e-3) / 1e9, 1),
                               frac_hbm=round(hbm_bytes / (hbm_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)),
         other_ms=round(sum(acc.values()) - mfma_ms - m3_ms - hbm_ms, 4))
+    if mfma_ms > 0:
+        # the conv/fc kernels that run plain matrix instructions of the run's dtype (in an fp32 run: the few
+        # kernels left on fp32 MFMAs; in a bf16 run: all of them)
+        phase_summary["fp32_mfma_kernels" if args.dtype == "f32" else "bf16_mfma_kernels"] = dict(
+            ms=round(mfma_ms, 4), tflops=round(mfma_flop / (mfma_ms * 1e-3) / 1e12, 2),
+            frac_mfma=round(mfma_flop / (mfma_ms * 1e-3) / 1e12 / peak_mfma, 4))
+    conv_fc_ms, conv_fc_flop = mfma_ms + m3_ms, mfma_flop + m3_flop
+    conv_fc_exec = mfma_flop + m3_exec
     if m3_ms > 0:
         # kernels on bf16 pieces: algorithmic (fp32-equivalent) rate and the rate of the bf16 matrix work they
         # execute; then all conv/fc kernels together
@@ -239,9 +300,25 @@ def main() -> int:
             ms=round(m3_ms, 4), algorithmic_tflops=round(m3_flop / (m3_ms * 1e-3) / 1e12, 2),
             executed_bf16_tflops=round(m3_exec / (m3_ms * 1e-3) / 1e12, 2),
             frac_of_bf16_mfma_peak=round(m3_exec / (m3_ms * 1e-3) / 1e12 / PEAK_MFMA_TFLOPS["bf16"], 4))
-        all_tf = (mfma_flop + m3_flop) / ((mfma_ms + m3_ms) * 1e-3) / 1e12
-        phase_summary["conv_fc_all"] = dict(ms=round(mfma_ms + m3_ms, 4), algorithmic_tflops=round(all_tf, 2),
-                                            frac_of_fp32_mfma_peak=round(all_tf / PEAK_MFMA_TFLOPS["f32"], 4))
+    # the whole conv/fc phase (every contraction kernel of the round, forward and backward)
+    all_tf = conv_fc_flop / (conv_fc_ms * 1e-3) / 1e12
+    phase_summary["conv_fc"] = dict(ms=round(conv_fc_ms, 4), algorithmic_tflops=round(all_tf, 2))
+    if args.dtype == "f32":
+        phase_summary["conv_fc"].update(
+            frac_of_fp32_mfma_peak=round(all_tf / PEAK_MFMA_TFLOPS["f32"], 4),
+            note="algorithmic flops against the fp32 matrix peak; most kernels execute them as 3 or 6 exact bf16 piece "
+                 "products on the bf16 matrix pipe, see conv_fc_bf16_pieces for the executed rate against that pipe's peak")
+    else:
+        phase_summary["conv_fc"]["frac_of_bf16_mfma_peak"] = round(all_tf / PEAK_MFMA_TFLOPS["bf16"], 4)
+    # beside the top-level `roofline` (the single longest kernel of the round): the phase that takes most of it
+    roofline_conv_fc = dict(
+        phase="conv_fc (all contraction kernels of the round)", bound="mfma", ms=conv_fc_ms,
+        share_of_round=conv_fc_ms / sum(acc.values()), algorithmic_tflops=all_tf,
+        frac_of_fp32_mfma_peak=all_tf / PEAK_MFMA_TFLOPS["f32"] if args.dtype == "f32" else None,
+        executed_tflops=conv_fc_exec / (conv_fc_ms * 1e-3) / 1e12,
+        frac_of_bf16_mfma_peak=(m3_exec / (m3_ms * 1e-3) / 1e12 / PEAK_MFMA_TFLOPS["bf16"]) if m3_ms > 0 else
+                               (all_tf / PEAK_MFMA_TFLOPS["bf16"] if args.dtype == "bf16" else None),
+        unit="TFLOP/s")
 
     acting = diagnostics = None
     if args.extras == "on":
@@ -375,6 +452,8 @@ def main() -> int:
                    "calls": {"fused": "gala_round", "split": "gala_learner_step + gala_gossip",
                              "a2c_allreduce": "gala_a2c_allreduce_step (comparator, not GALA)"}[args.mode]},
         "roofline": roofline,
+        "roofline_conv_fc": roofline_conv_fc,
+        "consensus_distance": consensus,
         "phases": phase_summary,
         "kernels": kernels,
         "acting": acting,

@@ -9,9 +9,11 @@ typedef float diag_f32x4 __attribute__((ext_vector_type(4)));
 
 // ---- Gram matrix  G G^T  of the gradient arena ------------------------------------------------
 // Agents are cut into tiles of GRAM_T rows; a workgroup owns one pair of tiles (ti <= tj) and
-// one contiguous range of parameter columns, which its four wavefronts walk interleaved in
-// steps of 16 columns.  No LDS staging is needed: lane l loads the float4 of agent l % 16 at
-// columns 4 (l / 16) .. + 3 of the step, and element e of that float4 is the lane's operand of
+// one contiguous range of parameter columns, which its four wavefronts walk in steps of 16
+// columns, GRAM_UNROLL consecutive steps per wavefront at a time (256 contiguous bytes of every
+// row, so that both halves of a cache line are asked for by the same wavefront back to back).
+// No LDS staging is needed: lane l loads the float4 of agent l % 16 at columns
+// 4 (l / 16) .. + 3 of the step, and element e of that float4 is the lane's operand of
 // the e-th 16x16x4 fp32 MFMA.  That pairs the MFMA's k index (l / 16) with column
 // 4 (l / 16) + e, a permutation of the step's 16 columns that is the same for both operands,
 // which is all a sum over columns needs.  The wavefronts' results are added in a fixed order
@@ -19,6 +21,7 @@ typedef float diag_f32x4 __attribute__((ext_vector_type(4)));
 // the kernel is bound by HBM.
 constexpr int GRAM_STEP = 16;           // columns per MFMA group
 constexpr int GRAM_UNROLL = 4;          // steps in flight per wavefront
+constexpr int GRAM_WORKGROUPS = 256;    // workgroups in all (more, or more steps in flight, change nothing: measured)
 
 __global__ __launch_bounds__(256) void gram_kernel(const float *__restrict__ g, int N, long d_pad, int tiles,
                                                    int chunks, float *__restrict__ part)
@@ -66,20 +69,20 @@ __global__ __launch_bounds__(256) void gram_kernel(const float *__restrict__ g, 
     };
     if (same) {
         constexpr int U = GRAM_UNROLL;
-        for (long s = s0 + wave; s < s1; s += 4 * U) {
+        for (long s = s0 + wave * U; s < s1; s += 4 * U) {
             float4 a0[U], a1[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u) { a0[u] = ld(pa0, va0, s + 4 * u); a1[u] = ld(pa1, va1, s + 4 * u); }
+            for (int u = 0; u < U; ++u) { a0[u] = ld(pa0, va0, s + u); a1[u] = ld(pa1, va1, s + u); }
 #pragma unroll
             for (int u = 0; u < U; ++u) mma4(a0[u], a1[u], a0[u], a1[u]);
         }
     } else {
-        for (long s = s0 + wave; s < s1; s += 4 * GRAM_UNROLL) {
+        for (long s = s0 + wave * GRAM_UNROLL; s < s1; s += 4 * GRAM_UNROLL) {
             float4 a0[GRAM_UNROLL], a1[GRAM_UNROLL], b0[GRAM_UNROLL], b1[GRAM_UNROLL];
 #pragma unroll
             for (int u = 0; u < GRAM_UNROLL; ++u) {
-                a0[u] = ld(pa0, va0, s + 4 * u); a1[u] = ld(pa1, va1, s + 4 * u);
-                b0[u] = ld(pb0, vb0, s + 4 * u); b1[u] = ld(pb1, vb1, s + 4 * u);
+                a0[u] = ld(pa0, va0, s + u); a1[u] = ld(pa1, va1, s + u);
+                b0[u] = ld(pb0, vb0, s + u); b1[u] = ld(pb1, vb1, s + u);
             }
 #pragma unroll
             for (int u = 0; u < GRAM_UNROLL; ++u) mma4(a0[u], a1[u], b0[u], b1[u]);
@@ -101,32 +104,31 @@ __global__ __launch_bounds__(256) void gram_kernel(const float *__restrict__ g, 
 }
 
 // Sum the chunks of a tile pair and scatter the tile (and its mirror image) into gram [N][N].
-// One workgroup per (pair, tile row): 32 elements, eight threads each over interleaved chunks,
-// combined in thread order.
-__global__ __launch_bounds__(256) void gram_reduce_kernel(const float *__restrict__ part, int N, int tiles,
-                                                          int chunks, float *gram)
+// One workgroup per (pair, tile row): 32 elements, 32 threads each over interleaved chunks (four
+// chains per thread), combined in thread order.
+__global__ __launch_bounds__(1024) void gram_reduce_kernel(const float *__restrict__ part, int N, int tiles,
+                                                           int chunks, float *gram)
 {
-    __shared__ float red[8][GRAM_T];
+    __shared__ float red[32][GRAM_T];
     int ti = 0, rest = blockIdx.x;
     while (rest >= tiles - ti) { rest -= tiles - ti; ++ti; }
     const int tj = ti + rest;
     const int r = blockIdx.y, c = threadIdx.x % GRAM_T, q = threadIdx.x / GRAM_T;
     const float *p = part + (long)blockIdx.x * chunks * (GRAM_T * GRAM_T) + r * GRAM_T + c;
-    // four independent chains keep the loads of a thread in flight; combined in a fixed order
     float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
     int k = q;
-    for (; k + 24 < chunks; k += 32) {
+    for (; k + 96 < chunks; k += 128) {
         a0 += p[(long)k * (GRAM_T * GRAM_T)];
-        a1 += p[(long)(k + 8) * (GRAM_T * GRAM_T)];
-        a2 += p[(long)(k + 16) * (GRAM_T * GRAM_T)];
-        a3 += p[(long)(k + 24) * (GRAM_T * GRAM_T)];
+        a1 += p[(long)(k + 32) * (GRAM_T * GRAM_T)];
+        a2 += p[(long)(k + 64) * (GRAM_T * GRAM_T)];
+        a3 += p[(long)(k + 96) * (GRAM_T * GRAM_T)];
     }
-    for (; k < chunks; k += 8) a0 += p[(long)k * (GRAM_T * GRAM_T)];
+    for (; k < chunks; k += 32) a0 += p[(long)k * (GRAM_T * GRAM_T)];
     red[q][c] = (a0 + a1) + (a2 + a3);
     __syncthreads();
     if (q == 0) {
         float t = 0.f;
-        for (int w = 0; w < 8; ++w) t += red[w][c];
+        for (int w = 0; w < 32; ++w) t += red[w][c];
         const int i = ti * GRAM_T + r, j = tj * GRAM_T + c;
         if (i < N && j < N) {
             gram[(long)i * N + j] = t;
@@ -149,7 +151,7 @@ int gram_tiles(int N) { return (N + GRAM_T - 1) / GRAM_T; }
 int gram_pairs(int N) { const int t = gram_tiles(N); return t * (t + 1) / 2; }
 int gram_chunks(int N)
 {
-    int c = 256 / gram_pairs(N);
+    int c = GRAM_WORKGROUPS / gram_pairs(N);
     return c < 1 ? 1 : c;
 }
 
@@ -160,7 +162,7 @@ hipError_t launch_grad_cosine(int N, const Layout &L, const float *g, float *par
     hipLaunchKernelGGL(gram_kernel, dim3(chunks, pairs), dim3(256), 0, s, g, N, L.d_pad, tiles, chunks, part);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(gram_reduce_kernel, dim3(pairs, GRAM_T), dim3(256), 0, s, part, N, tiles, chunks, gram);
+    hipLaunchKernelGGL(gram_reduce_kernel, dim3(pairs, GRAM_T), dim3(1024), 0, s, part, N, tiles, chunks, gram);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(cosine_kernel, dim3((unsigned)(((long)N * N + 255) / 256)), dim3(256), 0, s, gram, N, cosm);

@@ -615,6 +615,70 @@ hipError_t launch_rmsprop_mix(int N, const Layout &L, const HParams &hp, float *
 // barrier; the order of every sum is fixed by the launch shape.
 constexpr int CONS_KEEP = 32;
 
+template <int NACC>      // agents' accumulators a thread holds: 32 or 64 (NACC >= N)
+__global__ __launch_bounds__(256) void consensus_kernel(const float *__restrict__ x, int N, long d_pad, int parts,
+                                                        float *part)
+{
+    const long n4 = d_pad / 4;
+    constexpr int CHUNK = 8;                             // rows beyond CONS_KEEP are taken this many at a time
+    // row i of column e: uniform row pointer (scalar registers) + the thread's 32-bit byte offset
+    auto ld = [&](int i, unsigned boff) -> float4 {
+        return *reinterpret_cast<const float4 *>(reinterpret_cast<const char *>(x + (long)min(i, N - 1) * d_pad) + boff);
+    };
+    float ss[NACC];
+#pragma unroll
+    for (int i = 0; i < NACC; ++i) ss[i] = 0.f;
+    // Rows i >= N do not exist: their loads are redirected to the last row, so that the loop below is
+    // free of branches (all loads of a batch in flight together).  The mean takes the sum of all NACC
+    // loaded rows and removes the NACC - N extra copies of the last row again; sums of at most 64 single
+    // precision values in double precision are exact here for identical rows, which keeps the distance
+    // of agents at consensus at exactly zero.  Accumulators of rows that do not exist are never stored.
+    const double extra = (double)(NACC - N), inv_n = 1.0 / (double)N;
+    for (long e = (long)blockIdx.x * 256 + threadIdx.x; e < n4; e += (long)gridDim.x * 256) {
+        const unsigned boff = (unsigned)e * 16u;         // d_pad * 4 bytes stay far below 2^32
+        float4 keep[CONS_KEEP];
+#pragma unroll
+        for (int i = 0; i < CONS_KEEP; ++i) keep[i] = ld(i, boff);
+        const float4 last = ld(N - 1, boff);
+        double m0 = 0.0, m1 = 0.0, m2 = 0.0, m3 = 0.0;
+#pragma unroll
+        for (int i = 0; i < CONS_KEEP; ++i) { m0 += keep[i].x; m1 += keep[i].y; m2 += keep[i].z; m3 += keep[i].w; }
+#pragma unroll
+        for (int base = CONS_KEEP; base < NACC; base += CHUNK) {
+            float4 t[CHUNK];
+#pragma unroll
+            for (int i = 0; i < CHUNK; ++i) t[i] = ld(base + i, boff);
+#pragma unroll
+            for (int i = 0; i < CHUNK; ++i) { m0 += t[i].x; m1 += t[i].y; m2 += t[i].z; m3 += t[i].w; }
+        }
+        m0 = (m0 - extra * last.x) * inv_n; m1 = (m1 - extra * last.y) * inv_n;
+        m2 = (m2 - extra * last.z) * inv_n; m3 = (m3 - extra * last.w) * inv_n;
+        auto dev2 = [&](float4 v) {
+            // an opaque copy: otherwise the compiler keeps the double-precision conversions of the mean's
+            // pass alive for this one, which doubles the registers a column takes
+            asm volatile("" : "+v"(v.x), "+v"(v.y), "+v"(v.z), "+v"(v.w));
+            const float a = (float)(v.x - m0), b = (float)(v.y - m1), c = (float)(v.z - m2), d = (float)(v.w - m3);
+            return (a * a + b * b) + (c * c + d * d);
+        };
+#pragma unroll
+        for (int i = 0; i < CONS_KEEP; ++i) ss[i] += dev2(keep[i]);
+#pragma unroll
+        for (int base = CONS_KEEP; base < NACC; base += CHUNK) {
+            float4 t[CHUNK];
+#pragma unroll
+            for (int i = 0; i < CHUNK; ++i) t[i] = ld(base + i, boff);     // second read: from cache
+#pragma unroll
+            for (int i = 0; i < CHUNK; ++i) ss[base + i] += dev2(t[i]);
+        }
+    }
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int i = 0; i < NACC; ++i) {
+        const float t = wave_sum(ss[i]);
+        if (lane == 0 && i < N) part[(long)i * parts + blockIdx.x * 4 + wave] = t;
+    }
+}
+
 // More than 64 agents: a workgroup owns 1024 element columns, forms the mean in registers and
 // block-reduces every agent's squared deviation over those columns into part[agent][chunk]; the
 // second pass over the agents hits cache.
@@ -644,96 +708,44 @@ __global__ __launch_bounds__(256) void consensus_wide_kernel(const float *__rest
     }
 }
 
-template <int NACC>      // agents' accumulators a thread holds: 32 or 64 (NACC >= N)
-__global__ __launch_bounds__(256) void consensus_kernel(const float *__restrict__ x, int N, long d_pad, int parts,
-                                                        float *part)
+// Row sums of a [rows][cols] array of partial sums of squares and the norms made of them, in one
+// workgroup of sixteen wavefronts: wavefront w sums rows w, w + 16, ... (lane l takes columns l, l + 64,
+// ... in four interleaved chains, combined in a fixed order), then row_norm[i] = sqrt(row sum)
+// (optional), result[0] = sqrt(largest row sum), result[1] = sqrt(total).  row_ss receives the row sums.
+__global__ __launch_bounds__(1024) void row_norms_kernel(const float *__restrict__ part, int rows, int cols,
+                                                         float *row_ss, float *row_norm, float *result)
 {
-    const long n4 = d_pad / 4;
-    const float4 *x4 = reinterpret_cast<const float4 *>(x);
-    float ss[NACC];
-#pragma unroll
-    for (int i = 0; i < NACC; ++i) ss[i] = 0.f;
-    for (long e = (long)blockIdx.x * 256 + threadIdx.x; e < n4; e += (long)gridDim.x * 256) {
-        float4 keep[CONS_KEEP];
-#pragma unroll
-        for (int i = 0; i < CONS_KEEP; ++i)
-            keep[i] = x4[(long)(i < N ? i : N - 1) * n4 + e];        // the last row again where fewer agents exist
-        double m0 = 0.0, m1 = 0.0, m2 = 0.0, m3 = 0.0;
-#pragma unroll
-        for (int i = 0; i < CONS_KEEP; ++i)
-            if (i < N) { m0 += keep[i].x; m1 += keep[i].y; m2 += keep[i].z; m3 += keep[i].w; }
-        if (NACC > CONS_KEEP)
-            for (int i = CONS_KEEP; i < N; ++i) {
-                const float4 v = x4[(long)i * n4 + e];
-                m0 += v.x; m1 += v.y; m2 += v.z; m3 += v.w;
-            }
-        m0 /= (double)N; m1 /= (double)N; m2 /= (double)N; m3 /= (double)N;
-        auto dev2 = [&](float4 v) {
-            const float a = (float)(v.x - m0), b = (float)(v.y - m1), c = (float)(v.z - m2), d = (float)(v.w - m3);
-            return (a * a + b * b) + (c * c + d * d);
-        };
-#pragma unroll
-        for (int i = 0; i < CONS_KEEP; ++i)
-            if (i < N) ss[i] += dev2(keep[i]);
-        if (NACC > CONS_KEEP) {
-#pragma unroll
-            for (int i = CONS_KEEP; i < NACC; ++i)
-                if (i < N) ss[i] += dev2(x4[(long)i * n4 + e]);
-        }
-    }
+    __shared__ float red_max[16], red_sum[16];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-#pragma unroll
-    for (int i = 0; i < NACC; ++i) {
-        if (i < N) {
-            const float t = wave_sum(ss[i]);
-            if (lane == 0) part[(long)i * parts + blockIdx.x * 4 + wave] = t;
+    float mx = 0.f, tot = 0.f;                             // this wavefront's rows (the same in every lane)
+    for (int r = wave; r < rows; r += 16) {
+        const float *p = part + (long)r * cols;
+        float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+        int c = lane;
+        for (; c + 192 < cols; c += 256) { a0 += p[c]; a1 += p[c + 64]; a2 += p[c + 128]; a3 += p[c + 192]; }
+        for (; c < cols; c += 64) a0 += p[c];
+        const float ss = wave_sum((a0 + a1) + (a2 + a3));
+        if (lane == 0) {
+            row_ss[r] = ss;
+            if (row_norm) row_norm[r] = sqrtf(ss);
         }
-    }
-}
-
-// Row sums of a [rows][cols] array of partial sums of squares, one wavefront per row, and the
-// norms made of them: row_norm[i] = sqrt(row sum) (optional), result[0] = sqrt(largest row sum),
-// result[1] = sqrt(total).  Fixed summation order.
-__global__ __launch_bounds__(64) void row_sums_kernel(const float *__restrict__ part, int cols, float *row_ss)
-{
-    const float *p = part + (long)blockIdx.x * cols;
-    float acc = 0.f;
-    for (int c = threadIdx.x; c < cols; c += 64) acc += p[c];
-    acc = wave_sum(acc);
-    if (threadIdx.x == 0) row_ss[blockIdx.x] = acc;
-}
-
-__global__ __launch_bounds__(256) void norms_finish_kernel(const float *__restrict__ row_ss, int rows, float *row_norm,
-                                                           float *result)
-{
-    __shared__ float red_max[4], red_sum[4];
-    float mx = 0.f, tot = 0.f;
-    for (int i = threadIdx.x; i < rows; i += 256) {
-        const float ss = row_ss[i];
-        if (row_norm) row_norm[i] = sqrtf(ss);
         mx = fmaxf(mx, ss);
         tot += ss;
     }
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) {
-        mx = fmaxf(mx, __shfl_xor(mx, off, 64));
-        tot += __shfl_xor(tot, off, 64);
-    }
-    if ((threadIdx.x & 63) == 0) { red_max[threadIdx.x >> 6] = mx; red_sum[threadIdx.x >> 6] = tot; }
+    if (lane == 0) { red_max[wave] = mx; red_sum[wave] = tot; }
     __syncthreads();
     if (threadIdx.x == 0) {
-        result[0] = sqrtf(fmaxf(fmaxf(red_max[0], red_max[1]), fmaxf(red_max[2], red_max[3])));
-        result[1] = sqrtf((red_sum[0] + red_sum[1]) + (red_sum[2] + red_sum[3]));
+        float m = 0.f, t = 0.f;
+        for (int w = 0; w < 16; ++w) { m = fmaxf(m, red_max[w]); t += red_sum[w]; }
+        result[0] = sqrtf(m);
+        result[1] = sqrtf(t);
     }
 }
 
 hipError_t launch_row_norms(const float *part, int rows, int cols, float *row_ss, float *row_norm, float *result,
                             hipStream_t s)
 {
-    hipLaunchKernelGGL(row_sums_kernel, dim3(rows), dim3(64), 0, s, part, cols, row_ss);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(norms_finish_kernel, dim3(1), dim3(256), 0, s, row_ss, rows, row_norm, result);
+    hipLaunchKernelGGL(row_norms_kernel, dim3(1), dim3(1024), 0, s, part, rows, cols, row_ss, row_norm, result);
     return hipGetLastError();
 }
 

@@ -132,6 +132,9 @@ def main() -> int:
                          "the synchronous comparator (gradients averaged over agents, no gossip) instead")
     ap.add_argument("--extras", choices=["on", "off"], default="on",
                     help="off: skip the acting and diagnostics measurements (profiling runs of the headline path)")
+    ap.add_argument("--overlap-optimizer", action="store_true",
+                    help="create the context with GALA_OVERLAP_OPTIMIZER set: the hidden layer's share of the fused "
+                         "optimizer + mixing pass runs on the library's side stream beside the next round's convolutions")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-rounds", type=int, default=20)
     args = ap.parse_args()
@@ -157,6 +160,8 @@ def main() -> int:
     net = gs.make_net(A)
     hparams = dict(gs.HPARAMS, compute_dtype=1 if args.dtype == "bf16" else 0)
     peak_mfma = PEAK_MFMA_TFLOPS[args.dtype]
+    if args.overlap_optimizer:
+        os.environ["GALA_OVERLAP_OPTIMIZER"] = "1"
     gpu = Gala(N, A, T, B, hparams, cfg["topology"], max_delay=cfg["max_delay"], delay_seed=7)
     X0 = gs.init_params(net, N, shared=True)
     gpu.set_params(X0)
@@ -449,6 +454,7 @@ def main() -> int:
                                f"{'fp32' if args.dtype == 'f32' else 'bf16 operands / fp32 accumulation'}",
                    "n_agents": N, "T": T, "B": B, "n_actions": A, "topology": cfg["topology"],
                    "max_delay": cfg["max_delay"],
+                   "overlap_optimizer": bool(args.overlap_optimizer),
                    "calls": {"fused": "gala_round", "split": "gala_learner_step + gala_gossip",
                              "a2c_allreduce": "gala_a2c_allreduce_step (comparator, not GALA)"}[args.mode]},
         "roofline": roofline,

@@ -109,7 +109,12 @@ typedef struct {
  * kernels of a learner step run beside the data-gradient chain; it is forked from and joined
  * back into hip_stream inside every call, so callers only ever order against hip_stream.
  * Setting the environment variable GALA_SINGLE_STREAM before gala_create keeps everything on
- * hip_stream (same kernels, same results). */
+ * hip_stream (same kernels, same results).
+ * Setting GALA_OVERLAP_OPTIMIZER before gala_create makes gala_round (one in-peer, no delays) run the
+ * hidden layer's share of its optimizer + mixing pass on the internal stream, beside the convolutions
+ * of the next gala_round's forward pass, which waits for it in front of the hidden layer; every other
+ * entry point waits for it first.  Same kernels on the same values: identical results.  Measured no
+ * faster on one device (the pass and the byte-reading convolution compete for memory), hence opt-in. */
 int gala_create(gala_ctx **out, int n_agents, const gala_topology *topo,
                 const gala_net_dims *net, const gala_hparams *hp, void *hip_stream);
 int gala_destroy(gala_ctx *ctx);

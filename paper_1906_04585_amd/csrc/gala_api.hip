@@ -35,6 +35,10 @@ struct gala_ctx {
     int32_t *bad_actions = nullptr; // device counter of the validation kernel
     float *scratch = nullptr;       // this device's address of the library's static scratch array
     bool shared_gradient = false;   // the last optimiser step applied the averaged gradient
+    // GALA_OVERLAP_OPTIMIZER at creation: gala_round puts the hidden layer's share of its optimizer + mixing
+    // pass on the side stream, where it runs beside the convolutions of the next round's forward pass
+    bool overlap_optimizer = false;
+    bool opt_pending = false;       // that share has been enqueued and the context's stream has not waited for it yet
     hipStream_t stream = nullptr;
     int device = 0;
     std::vector<void *> allocs;
@@ -286,6 +290,9 @@ extern "C" int gala_create(gala_ctx **out, int n_agents, const gala_topology *to
         he = hipStreamCreateWithFlags(&c->side.stream, hipStreamNonBlocking);
         for (int i = 0; i < 4 && he == hipSuccess; ++i) he = hipEventCreateWithFlags(&c->side.fork[i], hipEventDisableTiming);
         if (he == hipSuccess) he = hipEventCreateWithFlags(&c->side.join, hipEventDisableTiming);
+        if (he == hipSuccess) he = hipEventCreateWithFlags(&c->side.opt_fork, hipEventDisableTiming);
+        if (he == hipSuccess) he = hipEventCreateWithFlags(&c->side.opt_done, hipEventDisableTiming);
+        c->overlap_optimizer = getenv("GALA_OVERLAP_OPTIMIZER") != nullptr;
         if (he != hipSuccess) { fail(c, GALA_EHIP, "side stream: %s", hipGetErrorString(he)); return bail(GALA_EHIP); }
     }
     *out = c;
@@ -299,6 +306,8 @@ extern "C" int gala_destroy(gala_ctx *c)
     if (c->stream || !c->allocs.empty()) (void)hipStreamSynchronize(c->stream);
     for (hipEvent_t e : c->side.fork) if (e) (void)hipEventDestroy(e);
     if (c->side.join) (void)hipEventDestroy(c->side.join);
+    if (c->side.opt_fork) (void)hipEventDestroy(c->side.opt_fork);
+    if (c->side.opt_done) (void)hipEventDestroy(c->side.opt_done);
     if (c->side.stream) (void)hipStreamDestroy(c->side.stream);
     for (void *p : c->allocs) (void)hipFree(p);
     for (hipEvent_t e : c->timer.ev) (void)hipEventDestroy(e);
@@ -310,10 +319,23 @@ extern "C" size_t gala_param_count(const gala_ctx *c) { return c ? (size_t)c->L.
 
 extern "C" const char *gala_last_error(const gala_ctx *c) { return c ? c->err : g_create_err; }
 
+// The hidden layer's share of the last gala_round's optimizer pass may still be running on the side
+// stream: everything that reads or writes parameters or optimizer state orders itself behind it.
+static int join_optimizer(gala_ctx *c)
+{
+    if (c->opt_pending) {
+        HIP_OK(c, hipStreamWaitEvent(c->stream, c->side.opt_done, 0));
+        c->opt_pending = false;
+    }
+    return GALA_OK;
+}
+#define JOIN_OPT(c) do { int rc_ = join_optimizer(c); if (rc_ != GALA_OK) return rc_; } while (0)
+
 // canonical [N][d] <-> an internal arena
 static int export_arena(gala_ctx *c, const float *arena, float *dst, int dst_is_device)
 {
     if (!c || !dst) return fail(c, GALA_EINVAL, "null argument");
+    JOIN_OPT(c);
     float *stage = dst_is_device ? dst : c->canon;
     HIP_OK(c, launch_permute(c->N, c->L, c->seg, stage, const_cast<float *>(arena), 0, c->stream));
     if (!dst_is_device) {
@@ -326,6 +348,7 @@ static int export_arena(gala_ctx *c, const float *arena, float *dst, int dst_is_
 static int import_arena(gala_ctx *c, float *arena, const float *src, int src_is_device)
 {
     if (!c || !src) return fail(c, GALA_EINVAL, "null argument");
+    JOIN_OPT(c);
     const float *stage = src;
     if (!src_is_device) {
         HIP_OK(c, hipMemcpyAsync(c->canon, src, (size_t)c->N * c->L.d * 4, hipMemcpyHostToDevice, c->stream));
@@ -362,7 +385,8 @@ extern "C" int gala_get_mean_grad(gala_ctx *c, float *dst, int dst_is_device)
 
 // forward, loss, backward and the per-agent gradient norm / clip factor
 static int enqueue_gradients(gala_ctx *c, const uint8_t *obs_u8, const int32_t *actions, const float *rewards,
-                             const uint8_t *dones, const uint8_t *bootstrap_obs, bool own_norm = true)
+                             const uint8_t *dones, const uint8_t *bootstrap_obs, bool own_norm = true,
+                             bool late_join = false)
 {
     if (!obs_u8 || !actions || !rewards || !dones || !bootstrap_obs) return fail(c, GALA_EINVAL, "null input buffer");
     if ((reinterpret_cast<uintptr_t>(obs_u8) | reinterpret_cast<uintptr_t>(bootstrap_obs)) & 3)
@@ -382,7 +406,12 @@ static int enqueue_gradients(gala_ctx *c, const uint8_t *obs_u8, const int32_t *
     a.bf16 = c->hp.compute_dtype == 1;
     PhaseTimer *pt = &c->timer;
     pt->begin();
-    HIP_OK(c, launch_forward(a, c->stream, pt));
+    // a pending share of the previous optimizer pass covers the hidden layer's weights only: the
+    // convolutions may start, the stream waits in front of the hidden layer (late_join) or right here
+    hipEvent_t before_fc = nullptr;
+    if (c->opt_pending && late_join) { before_fc = c->side.opt_done; c->opt_pending = false; }
+    else JOIN_OPT(c);
+    HIP_OK(c, launch_forward(a, c->stream, pt, before_fc));
     HIP_OK(c, launch_loss(a, c->hp, actions, rewards, dones, c->stream));
     pt->mark("loss_heads_dgrad");
     HIP_OK(c, launch_backward(a, c->stream, pt, &c->side));
@@ -436,6 +465,7 @@ extern "C" int gala_gossip(gala_ctx *c, int64_t round)
     if (!c) return GALA_EINVAL;
     int rc = check_round(c, round);
     if (rc != GALA_OK) return rc;
+    JOIN_OPT(c);
     if (c->tau > 0) {
         float *slot = c->b.hist + (size_t)(round % (c->tau + 1)) * c->N * c->L.d_pad;
         HIP_OK(c, launch_publish(c->N, c->L, c->b.x[c->cur], slot, c->stream));
@@ -460,14 +490,30 @@ extern "C" int gala_round(gala_ctx *c, const uint8_t *obs_u8, const int32_t *act
         rc = gala_learner_step(c, obs_u8, actions, rewards, dones, bootstrap_obs);
         return rc != GALA_OK ? rc : gala_gossip(c, round);
     }
-    rc = enqueue_gradients(c, obs_u8, actions, rewards, dones, bootstrap_obs);
+    rc = enqueue_gradients(c, obs_u8, actions, rewards, dones, bootstrap_obs, true, true);
     if (rc != GALA_OK) return rc;
     const int phase = (int)(round % c->n_phases);
     if (c->cycles_ok) {
-        HIP_OK(c, launch_rmsprop_mix_cycles(c->N, c->L, c->hp, c->b.x[c->cur], c->b.v, c->b.g,
-                                            c->b.cyc_order + (size_t)phase * c->N,
-                                            c->b.cyc_start + (size_t)phase * (c->N + 1), c->n_cycles[phase],
-                                            c->b.weight + (size_t)phase * c->N * 2, c->b.stats, c->stream));
+        auto pass = [&](hipStream_t s, long col0, long col1) {
+            return launch_rmsprop_mix_cycles(c->N, c->L, c->hp, c->b.x[c->cur], c->b.v, c->b.g,
+                                             c->b.cyc_order + (size_t)phase * c->N,
+                                             c->b.cyc_start + (size_t)phase * (c->N + 1), c->n_cycles[phase],
+                                             c->b.weight + (size_t)phase * c->N * 2, c->b.stats, s, col0, col1);
+        };
+        if (c->overlap_optimizer && c->side.stream && !c->timer.on) {
+            // the hidden layer's weights (95 % of the parameters) are first read by the fourth kernel of a
+            // forward pass: their share of this pass goes to the side stream, the rest stays here
+            const long w0 = c->L.fcw, w1 = c->L.fcw + (long)FC * FLAT;
+            HIP_OK(c, hipEventRecord(c->side.opt_fork, c->stream));
+            HIP_OK(c, hipStreamWaitEvent(c->side.stream, c->side.opt_fork, 0));
+            HIP_OK(c, pass(c->side.stream, w0, w1));
+            HIP_OK(c, hipEventRecord(c->side.opt_done, c->side.stream));
+            HIP_OK(c, pass(c->stream, 0, w0));
+            HIP_OK(c, pass(c->stream, w1, c->L.d_pad));
+            c->opt_pending = true;
+        } else {
+            HIP_OK(c, pass(c->stream, 0, c->L.d_pad));
+        }
         c->timer.mark("clip_rmsprop_mix");
         c->shared_gradient = false;
         c->last_round = round;
@@ -489,6 +535,7 @@ extern "C" int gala_act(gala_ctx *c, const uint8_t *obs_u8, uint64_t seed, int64
     if (reinterpret_cast<uintptr_t>(obs_u8) & 3) return fail(c, GALA_EINVAL, "observation buffer must be 4-byte aligned");
     if (step < 0) return fail(c, GALA_EINVAL, "negative acting step");
     if (!c->params_set) return fail(c, GALA_ESTATE, "acting step before gala_set_params: the parameters are all zero");
+    JOIN_OPT(c);
     // forward pass over B frames per agent: all of them take the policy head, none is a bootstrap state
     NetArgs a{};
     a.N = c->N; a.M = c->hp.B; a.F = c->hp.B; a.Bn = 0; a.L = c->L;
@@ -526,6 +573,7 @@ extern "C" int gala_get_outputs(gala_ctx *c, float *logits, float *values, float
 extern "C" int gala_consensus_distance(gala_ctx *c, float *max_dist, float *frob)
 {
     if (!c || !max_dist || !frob) return fail(c, GALA_EINVAL, "null argument");
+    JOIN_OPT(c);
     float *result = c->b.cons_part + (size_t)c->N * consensus_parts(c->N, c->L);
     c->timer.mark("diag_begin");
     HIP_OK(c, launch_consensus(c->N, c->L, c->b.x[c->cur], c->b.cons_part, c->b.row_ss, result, c->stream));
@@ -540,6 +588,7 @@ extern "C" int gala_consensus_distance(gala_ctx *c, float *max_dist, float *frob
 extern "C" int gala_consensus_distance_noalloc(gala_ctx *c, float *result_dev)
 {
     if (!c || !result_dev) return fail(c, GALA_EINVAL, "null argument");
+    JOIN_OPT(c);
     // partial sums of squares [N][parts], then the row sums [N], all in the static scratch array
     const size_t need = (size_t)c->N * consensus_parts(c->N, c->L) + (size_t)c->N;
     if (need > SCRATCH_FLOATS)
@@ -575,6 +624,7 @@ extern "C" int gala_grad_cosine(gala_ctx *c, float *cos_host)
 extern "C" int gala_update_norm(gala_ctx *c, float *row_norms_host, float *frob_host)
 {
     if (!c || !frob_host) return fail(c, GALA_EINVAL, "null argument");
+    JOIN_OPT(c);
     c->timer.mark("diag_begin");
     HIP_OK(c, launch_update_norm(c->N, c->L, c->hp, c->shared_gradient ? c->b.gbar : c->b.g, c->shared_gradient,
                                  c->b.v, c->b.stats, c->b.upd_part, c->b.row_ss, c->b.upd_norm, c->stream));
@@ -610,6 +660,7 @@ extern "C" int gala_get_peer_table(gala_ctx *c, int64_t round, int32_t *peer, in
 extern "C" int gala_set_profiling(gala_ctx *c, int enabled)
 {
     if (!c) return GALA_EINVAL;
+    JOIN_OPT(c);
     c->timer.on = enabled != 0;
     c->timer.n = 0;
     return GALA_OK;

@@ -138,7 +138,9 @@ struct NetArgs {
     bool bf16;                   // conv/fc operands rounded to bf16 in LDS, fp32 accumulation
 };
 
-hipError_t launch_forward(const NetArgs &a, hipStream_t s, PhaseTimer *pt);
+// before_fc: an event the stream waits for in front of the hidden layer (the first kernel that reads the
+// hidden layer's weights), or nullptr
+hipError_t launch_forward(const NetArgs &a, hipStream_t s, PhaseTimer *pt, hipEvent_t before_fc = nullptr);
 // returns, advantages, loss terms per sample, head output gradients and the hidden layer's dzh
 hipError_t launch_loss(const NetArgs &a, const HParams &hp, const int32_t *actions, const float *rewards,
                        const uint8_t *dones, hipStream_t s);
@@ -153,6 +155,7 @@ struct SideStream {
     hipStream_t stream = nullptr;
     hipEvent_t fork[4] = {nullptr, nullptr, nullptr, nullptr};
     hipEvent_t join = nullptr;
+    hipEvent_t opt_fork = nullptr, opt_done = nullptr;   // the hidden layer's share of the optimizer pass (optional overlap)
 };
 hipError_t launch_backward(const NetArgs &a, hipStream_t s, PhaseTimer *pt, const SideStream *side);
 size_t workspace_floats(int N, int M, int F);
@@ -167,7 +170,7 @@ hipError_t launch_grad_mean(int N, const Layout &L, const HParams &hp, const flo
 bool fused_mix_available(int N);
 hipError_t launch_rmsprop_mix_cycles(int N, const Layout &L, const HParams &hp, float *x, float *v, const float *g,
                                      const int32_t *order, const int32_t *cstart, int n_cycles, const float *weight,
-                                     const float *stats, hipStream_t s);
+                                     const float *stats, hipStream_t s, long col_begin = 0, long col_end = -1);
 hipError_t launch_rmsprop_mix(int N, const Layout &L, const HParams &hp, float *x, float *v, const float *g,
                               float *hist, int tau, long round, int phase, int max_in, const int32_t *peer,
                               const int32_t *delay, const float *weight, const float *stats, hipStream_t s);

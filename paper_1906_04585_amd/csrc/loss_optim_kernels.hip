@@ -529,15 +529,16 @@ __global__ __launch_bounds__(256) void rmsprop_mix_kernel(float *x, float *v, co
 // as rmsprop_kernel + mix_kernel.  order[] lists the agents cycle by cycle, cstart[] the cycles'
 // first entries (n_cycles + 1 values), both for the phase of this round.
 __global__ __launch_bounds__(256) void rmsprop_mix_cycle_kernel(float *x, float *v, const float *__restrict__ g,
-                                                                long d_pad, const int32_t *__restrict__ order,
+                                                                long d_pad, long e_begin, long e_end,
+                                                                const int32_t *__restrict__ order,
                                                                 const int32_t *__restrict__ cstart,
                                                                 const float *__restrict__ weight,
                                                                 const float *__restrict__ stats, float lr, float alpha,
                                                                 float eps)
 {
     const long n4 = d_pad / 4;
-    const long e = (long)blockIdx.x * 256 + threadIdx.x;
-    if (e >= n4) return;
+    const long e = e_begin + (long)blockIdx.x * 256 + threadIdx.x;       // float4 column inside an agent's slice
+    if (e >= e_end) return;
     const int b0 = cstart[blockIdx.y], b1 = cstart[blockIdx.y + 1];
     const float om = 1.f - alpha;
     auto update = [&](int agent) -> float4 {
@@ -566,13 +567,17 @@ __global__ __launch_bounds__(256) void rmsprop_mix_cycle_kernel(float *x, float 
     mix_store(prev_agent, prev, first);
 }
 
+// Parameters [col_begin, col_end) (floats, multiples of 4) of every agent's slice; the whole slice by default.
 hipError_t launch_rmsprop_mix_cycles(int N, const Layout &L, const HParams &hp, float *x, float *v, const float *g,
                                      const int32_t *order, const int32_t *cstart, int n_cycles, const float *weight,
-                                     const float *stats, hipStream_t s)
+                                     const float *stats, hipStream_t s, long col_begin, long col_end)
 {
-    const int blocks = (int)((L.d_pad / 4 + 255) / 256);
-    hipLaunchKernelGGL(rmsprop_mix_cycle_kernel, dim3(blocks, n_cycles), dim3(256), 0, s, x, v, g, L.d_pad, order, cstart,
-                       weight, stats, hp.lr, hp.rms_alpha, hp.rms_eps);
+    if (col_end < 0) col_end = L.d_pad;
+    const long e0 = col_begin / 4, e1 = col_end / 4;
+    if (e1 <= e0) return hipSuccess;
+    const int blocks = (int)((e1 - e0 + 255) / 256);
+    hipLaunchKernelGGL(rmsprop_mix_cycle_kernel, dim3(blocks, n_cycles), dim3(256), 0, s, x, v, g, L.d_pad, e0, e1, order,
+                       cstart, weight, stats, hp.lr, hp.rms_alpha, hp.rms_eps);
     (void)N;
     return hipGetLastError();
 }

@@ -836,7 +836,7 @@ static_assert(SSQ_CONV3 + reduce_blocks(Conv3Wgrad::PART) == NORM_USED, "gradien
 
 #define GALA_TRY(expr) do { hipError_t e_ = (expr); if (e_ != hipSuccess) return e_; } while (0)
 
-hipError_t launch_forward(const NetArgs &a, hipStream_t s, PhaseTimer *pt)
+hipError_t launch_forward(const NetArgs &a, hipStream_t s, PhaseTimer *pt, hipEvent_t before_fc)
 {
     const Layout &L = a.L;
     {
@@ -861,6 +861,7 @@ hipError_t launch_forward(const NetArgs &a, hipStream_t s, PhaseTimer *pt)
         GALA_TRY(igemm_launch(p, a.N, s, a.bf16));
         pt->mark("conv3_fwd");
     }
+    if (before_fc) GALA_TRY(hipStreamWaitEvent(s, before_fc, 0));
     {
         auto run = [&](auto p, int kchunk) -> hipError_t {
             typedef decltype(p) P;

@@ -198,3 +198,37 @@ def test_single_stream_and_event_timing_give_the_same_bits(monkeypatch):
             np.testing.assert_array_equal(other.get_opt_state(), two.get_opt_state())
             np.testing.assert_array_equal(other.get_params(), two.get_params())
     assert set(timed.get_phase_times()) >= {"conv1_fwd", "loss_heads_dgrad", "clip_rmsprop_mix"}
+
+
+@pytest.mark.parametrize("N,topology", [(4, "exp"), (5, "ring"), (32, "exp")])
+def test_overlapped_optimizer_share_gives_the_same_bits(monkeypatch, N, topology):
+    """GALA_OVERLAP_OPTIMIZER at creation: the hidden layer's share of the fused optimizer + mixing pass
+    runs on the internal stream next to the following round's convolutions.  Same kernels on the same
+    values: gradients, statistics, RMSprop state and parameters of every round are those of the plain
+    context, also when other entry points (which must wait for the pending share) come in between."""
+    from paper_1906_04585_amd import Gala
+    A, T, B = 6, 2, 3
+    net = gs.make_net(A)
+    X0 = gs.init_params(net, N, seed=35, bias_scale=0.05)
+    plain = Gala(N, A, T, B, HP, topology)
+    monkeypatch.setenv("GALA_OVERLAP_OPTIMIZER", "1")
+    over = Gala(N, A, T, B, HP, topology)
+    monkeypatch.delenv("GALA_OVERLAP_OPTIMIZER")
+    for g in (plain, over):
+        g.set_params(X0)
+    for r in range(6):
+        dev = upload(gs.rollout(net, N, T, B, 500 + r))
+        for g in (plain, over):
+            g.round(dev["obs"], dev["actions"], dev["rewards"], dev["dones"], dev["boot_obs"], r)
+        if r % 2 == 1:            # every other round is followed directly by the next round (late wait)
+            np.testing.assert_array_equal(over.get_grads(), plain.get_grads())
+            np.testing.assert_array_equal(over.get_step_stats(), plain.get_step_stats())
+            np.testing.assert_array_equal(over.get_opt_state(), plain.get_opt_state(), err_msg=f"round {r}")
+            np.testing.assert_array_equal(over.get_params(), plain.get_params(), err_msg=f"round {r}")
+            assert over.consensus_distance() == plain.consensus_distance()
+    # a split step and a gossip round after an overlapped round
+    dev = upload(gs.rollout(net, N, T, B, 520))
+    for g in (plain, over):
+        g.learner_step(dev["obs"], dev["actions"], dev["rewards"], dev["dones"], dev["boot_obs"])
+        g.gossip(6)
+    np.testing.assert_array_equal(over.get_params(), plain.get_params())

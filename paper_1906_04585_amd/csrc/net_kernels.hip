@@ -184,6 +184,20 @@ struct ConvFwd : ProblemBase {
     }
     __device__ void prep_b(CtxB &c, int kl, int n) const { c.off = (kl * CO + n) * 4; }
     __device__ float4 fetch_b(CtxB &c, int kt0, bool &) const { return ldg4b(w_ + kt0 * CO, c.off); }
+    // Order of the k-tiles: an input element is read by (KS / ST)^2 output positions of a workgroup's rows,
+    // through the taps of one parity class (kh % ST, kw % ST).  Per 128-byte line of a pixel's channels the
+    // taps of a class are walked back to back (the two 16-channel halves of the line innermost), which
+    // brings the reads of the same cache lines within a few k-tiles of each other; in (kh, kw, c) order
+    // they lie up to half the loop apart, by which time the lines have left the cache.
+    __device__ int ktile_k0(int i, int) const
+    {
+        static_assert(KS % ST == 0 && CI % 32 == 0 && BK == 16, "parity classes of equal size, whole lines");
+        constexpr int Q = KS / ST, TPC = Q * Q, LINES = CI / 32;
+        const int half = i % 2, ab = (i / 2) % TPC, cls = (i / (2 * TPC)) % (ST * ST), line = i / (2 * TPC * ST * ST);
+        (void)LINES;
+        const int kh = cls / ST + ST * (ab / Q), kw = cls % ST + ST * (ab % Q);
+        return (kh * KS + kw) * CI + line * 32 + half * BK;
+    }
     __device__ float4 col_value4(int n) const { return *reinterpret_cast<const float4 *>(b_ + n); }
     __device__ bool tile_full(int m0, int) const { return m0 + BM <= rows_; }
     template <bool CHECK> __device__ void store4(int m, int n, float4 v, float4 bias, float4) const

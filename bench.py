@@ -57,7 +57,7 @@ def kernel_of_phase(dtype: str) -> dict:
     }
     out = {ph: f"igemm_kernel<{nm}, {mode(ph)}>" for ph, nm in names.items()}
     out.update({
-        "grad_norm": "grad_norm_kernel", "clip_rmsprop": "rmsprop_kernel", "gossip_mix": "mix_kernel",
+        "conv1_wgrad_reduce": "reduce_grads_kernel", "step_stats": "step_stats_kernel", "clip_rmsprop": "rmsprop_kernel", "gossip_mix": "mix_kernel",
         # one in-peer per agent and no delays (the only workload with a committed traffic summary): the
         # cycle-walking pass; with delays or several in-peers the same phase runs rmsprop_mix_kernel<..>
         "gossip_publish": "copy_kernel", "clip_rmsprop_mix": "rmsprop_mix_cycle_kernel",

@@ -414,11 +414,8 @@ static int enqueue_gradients(gala_ctx *c, const uint8_t *obs_u8, const int32_t *
     HIP_OK(c, launch_forward(a, c->stream, pt, before_fc));
     HIP_OK(c, launch_loss(a, c->hp, actions, rewards, dones, c->stream));
     pt->mark("loss_heads_dgrad");
-    HIP_OK(c, launch_backward(a, c->stream, pt, &c->side));
-    if (own_norm) {
-        HIP_OK(c, launch_grad_norm(c->N, c->L, c->hp, c->b.g, c->b.norm_part, c->b.stats, c->stream));
-        pt->mark("grad_norm");
-    }
+    HIP_OK(c, launch_backward(a, c->hp, c->stream, pt, &c->side));
+    (void)own_norm;          // the backward pass always leaves every agent's own norm and clip factor in stats
     return GALA_OK;
 }
 

@@ -144,8 +144,6 @@ hipError_t launch_forward(const NetArgs &a, hipStream_t s, PhaseTimer *pt, hipEv
 // returns, advantages, loss terms per sample, head output gradients and the hidden layer's dzh
 hipError_t launch_loss(const NetArgs &a, const HParams &hp, const int32_t *actions, const float *rewards,
                        const uint8_t *dones, hipStream_t s);
-// the three loss terms of every agent from the per-sample terms (any stream ordered after launch_loss)
-hipError_t launch_loss_stats(const NetArgs &a, hipStream_t s);
 // number of entries of actions[0..n) outside [0, A), written to *count (one workgroup, no atomics)
 hipError_t launch_count_bad_actions(const int32_t *actions, long n, int A, int32_t *count, hipStream_t s);
 hipError_t launch_sample(int N, int Bn, int A, const float *logits, const float *values, uint64_t seed, long step,
@@ -157,11 +155,11 @@ struct SideStream {
     hipEvent_t join = nullptr;
     hipEvent_t opt_fork = nullptr, opt_done = nullptr;   // the hidden layer's share of the optimizer pass (optional overlap)
 };
-hipError_t launch_backward(const NetArgs &a, hipStream_t s, PhaseTimer *pt, const SideStream *side);
+// data gradients on `s`, weight gradients on the side stream; ends with every agent's loss terms, gradient norm
+// and clip factor in stats
+hipError_t launch_backward(const NetArgs &a, const HParams &hp, hipStream_t s, PhaseTimer *pt, const SideStream *side);
 size_t workspace_floats(int N, int M, int F);
 
-hipError_t launch_grad_norm(int N, const Layout &L, const HParams &hp, const float *g, const float *norm_part,
-                            float *stats, hipStream_t s);
 hipError_t launch_rmsprop(int N, const Layout &L, const HParams &hp, float *x, float *v, const float *g,
                           bool shared_gradient, const float *stats, hipStream_t s);
 int grad_mean_blocks(const Layout &L);

@@ -32,7 +32,7 @@ static __device__ __forceinline__ float block_sum_256(float v, float *red)
 // One workgroup per (LOSS_FRAMES samples, agent), one wavefront per sample and one lane per action
 // for the loss part: every wavefront walks its simulator's rollout back from the last step to its
 // own (at most T steps) instead of waiting for a pass over the whole rollout.  The per-sample loss
-// terms go to loss_part[agent][sample][3] and are summed by loss_stats_kernel in sample order.
+// terms go to loss_part[agent][sample][3]; the kernel that ends the backward pass sums them in sample order.
 // Then a thread owns one hidden column j, reads each head weight once and applies it to all
 // LOSS_FRAMES samples, whose output gradients sit in LDS.
 constexpr int MAX_ACTIONS = 64;
@@ -124,17 +124,6 @@ __global__ __launch_bounds__(LOSS_THREADS) void loss_heads_kernel(
     }
 }
 
-// stats[agent][0..2] = means over the agent's samples of the policy term, the squared value error and
-// the entropy: one wavefront per agent and term, samples taken in order (lane l: l, l + 64, ...).
-__global__ __launch_bounds__(192) void loss_stats_kernel(int M, const float *__restrict__ loss_part, float *stats)
-{
-    const int agent = blockIdx.x, term = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    float t = 0.f;
-    for (int m = lane; m < M; m += 64) t += loss_part[((long)agent * M + m) * 3 + term];
-    t = wave_sum(t);
-    if (lane == 0) stats[agent * 5 + term] = t * (1.0f / (float)M);
-}
-
 // Opt-in validation of the action buffer: one workgroup counts the entries outside [0, A).
 __global__ __launch_bounds__(1024) void count_bad_actions_kernel(const int32_t *__restrict__ actions, long n, int A,
                                                                  int32_t *count)
@@ -165,12 +154,6 @@ hipError_t launch_loss(const NetArgs &a, const HParams &hp, const int32_t *actio
     hipLaunchKernelGGL(loss_heads_kernel, dim3((a.M + LOSS_FRAMES - 1) / LOSS_FRAMES, a.N), dim3(LOSS_THREADS), 0, s,
                        hp.T, hp.B, hp.gamma, hp.vf_coef, hp.ent_coef, a.L, a.b.logits, a.b.values, actions, rewards,
                        dones, a.b.h, a.x, a.b.ret, a.b.adv, a.b.dlogits, a.b.dvalues, a.b.loss_part, a.b.dzh);
-    return hipGetLastError();
-}
-
-hipError_t launch_loss_stats(const NetArgs &a, hipStream_t s)
-{
-    hipLaunchKernelGGL(loss_stats_kernel, dim3(a.N), dim3(192), 0, s, a.M, a.b.loss_part, a.b.stats);
     return hipGetLastError();
 }
 
@@ -224,39 +207,6 @@ hipError_t launch_sample(int N, int Bn, int A, const float *logits, const float 
     return hipGetLastError();
 }
 
-// ---- global gradient norm per agent and clip factor (Table 2: clip global gradient norm) ----------
-// The convolution and hidden-layer weight gradients (with their biases, 99 % of the parameters)
-// arrive as partial sums of squares from the kernels that produced them; this kernel adds the
-// squares of the tensors behind them in the slice (hidden-layer bias, both heads) and turns the total
-// into  c = min(1, max_norm / (||g|| + 1e-6)).  One workgroup per agent, fixed summation order.
-constexpr int NORM_THREADS = 256;
-
-__global__ __launch_bounds__(NORM_THREADS) void grad_norm_kernel(const float *__restrict__ g, long d_pad, long tail_begin,
-                                                                 const float *__restrict__ part, float max_norm,
-                                                                 float *stats)
-{
-    __shared__ float red[NORM_THREADS / 64];
-    const int agent = blockIdx.x;
-    const float4 *p = reinterpret_cast<const float4 *>(g + agent * d_pad);
-    float acc = 0.f;
-#pragma unroll 4
-    for (long i = tail_begin / 4 + threadIdx.x; i < d_pad / 4; i += NORM_THREADS) {
-        const float4 v = p[i];
-        acc += (v.x * v.x + v.y * v.y) + (v.z * v.z + v.w * v.w);
-    }
-    if (threadIdx.x < NORM_USED) acc += part[agent * NORM_PARTS + threadIdx.x];
-    acc = wave_sum(acc);
-    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = acc;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        float ss = 0.f;
-        for (int w = 0; w < NORM_THREADS / 64; ++w) ss += red[w];
-        const float norm = sqrtf(ss);
-        stats[agent * 5 + 3] = norm;
-        stats[agent * 5 + 4] = fminf(1.f, max_norm / (norm + 1e-6f));
-    }
-}
-
 // ---- clip + RMSprop (Table 2; momentum 0) ---------------------------------------------------------------
 // The gradient and the second-moment estimate are touched once per round, hundreds of MB apart
 // in time: their loads and stores carry the non-temporal hint so that they stream past the
@@ -307,16 +257,6 @@ __global__ __launch_bounds__(256) void rmsprop_kernel(float *x, float *v, const 
         rmsprop4(xx, vv, g_stride ? stream_load4(ga, i) : reinterpret_cast<const float4 *>(ga)[i], c, lr, alpha, om, eps);
         stream_store4(va, i, vv); x4[i] = xx;
     }
-}
-
-hipError_t launch_grad_norm(int N, const Layout &L, const HParams &hp, const float *g, const float *norm_part,
-                            float *stats, hipStream_t s)
-{
-    // everything from the hidden layer's bias on is summed here; every tensor starts on a multiple of 64 floats
-    static_assert(NORM_USED <= NORM_THREADS, "one partial per thread");
-    hipLaunchKernelGGL(grad_norm_kernel, dim3(N), dim3(NORM_THREADS), 0, s, g, L.d_pad, L.fcb, norm_part,
-                       hp.max_grad_norm, stats);
-    return hipGetLastError();
 }
 
 hipError_t launch_rmsprop(int N, const Layout &L, const HParams &hp, float *x, float *v, const float *g,

@@ -683,15 +683,31 @@ struct Conv1Wgrad : ProblemBase {
     __device__ void store_sum_b(int n, float v) const { out_[KW1 * C1 + n] = v; }
 };
 
-// ---- sum of split-K partials ----------------------------------------------------------------------
-// out[agent][i] = sum_s part[agent][s][i].  Every workgroup also leaves the sum of squares of what
-// it wrote in ssq[agent * NORM_PARTS + ssq_slot + blockIdx.x]: its share of the gradient norm.
-__global__ __launch_bounds__(256) void reduce_splits_kernel(const float *__restrict__ part, int S, long len, float *out,
-                                                            long out_stride, float *ssq, int ssq_slot)
+// ---- sum of split-K partials of the convolutions' weight gradients (up to three layers per launch) ----------
+// A workgroup owns 1024 consecutive floats of one
+// layer's gradient (weights, then bias): out[i] = sum_s part[s][i], partials added in index order, and
+// leaves the sum of squares of what it wrote in its slot of the agent's row of gradient-norm partials.
+struct ReduceSeg {
+    const float *part;      // [N][S][len] partial sums
+    int S, blocks, ssq_slot;
+    long len, out_off;      // floats per agent and partial; offset of the tensor inside an agent's gradient slice
+};
+
+__global__ __launch_bounds__(256) void reduce_grads_kernel(ReduceSeg s3, ReduceSeg s2, ReduceSeg s1, float *g, long d_pad,
+                                                           float *ssq)
 {
     __shared__ float red[4];
     const int agent = blockIdx.y;
-    const long i = ((long)blockIdx.x * 256 + threadIdx.x) * 4;
+    int b = blockIdx.x;
+    // the workgroup's layer (uniform): fields picked one by one, so that the arguments stay in scalar registers
+    const int which = b < s3.blocks ? 0 : (b < s3.blocks + s2.blocks ? 1 : 2);
+    b -= which == 0 ? 0 : (which == 1 ? s3.blocks : s3.blocks + s2.blocks);
+    const float *part = which == 0 ? s3.part : (which == 1 ? s2.part : s1.part);
+    const int S = which == 0 ? s3.S : (which == 1 ? s2.S : s1.S);
+    const long len = which == 0 ? s3.len : (which == 1 ? s2.len : s1.len);
+    const long out_off = which == 0 ? s3.out_off : (which == 1 ? s2.out_off : s1.out_off);
+    const int slot = which == 0 ? s3.ssq_slot : (which == 1 ? s2.ssq_slot : s1.ssq_slot);
+    const long i = ((long)b * 256 + threadIdx.x) * 4;
     float sq = 0.f;
     if (i < len) {
         const float *p = part + (long)agent * S * len + i;
@@ -705,25 +721,59 @@ __global__ __launch_bounds__(256) void reduce_splits_kernel(const float *__restr
             for (int u = 0; u < 8; ++u)
                 if (s0 + u < S) { acc.x += t[u].x; acc.y += t[u].y; acc.z += t[u].z; acc.w += t[u].w; }
         }
-        *reinterpret_cast<float4 *>(out + agent * out_stride + i) = acc;
+        *reinterpret_cast<float4 *>(g + agent * d_pad + out_off + i) = acc;
         sq = (acc.x * acc.x + acc.y * acc.y) + (acc.z * acc.z + acc.w * acc.w);
     }
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) sq += __shfl_xor(sq, off, 64);
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = sq;
     __syncthreads();
-    if (threadIdx.x == 0) ssq[agent * NORM_PARTS + ssq_slot + blockIdx.x] = (red[0] + red[1]) + (red[2] + red[3]);
+    if (threadIdx.x == 0) ssq[agent * NORM_PARTS + slot + b] = (red[0] + red[1]) + (red[2] + red[3]);
+}
+
+// ---- an agent's statistics of the step, one workgroup per agent, every sum in a fixed order ---------------------
+//   stats[0..2]  means over the agent's samples of the policy term, the squared value error and the entropy
+//                (one wavefront per term, lane l takes samples l, l + 64, ...)
+//   stats[3]     ||g||_2 over all parameters: the partials of the hidden layer's tiles and of the three
+//                convolutions' reductions, plus the squares of the tensors behind them in the slice
+//                (hidden-layer bias, both heads), which are summed here
+//   stats[4]     the clip factor min(1, max_norm / (||g|| + 1e-6))   (Table 2: clip global gradient norm)
+__global__ __launch_bounds__(256) void step_stats_kernel(const float *__restrict__ g, long d_pad, long tail_begin,
+                                                         const float *__restrict__ ssq, int M,
+                                                         const float *__restrict__ loss_part, float max_norm, float *stats)
+{
+    __shared__ float red[4];
+    const int agent = blockIdx.x;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (wave < 3) {
+        float t = 0.f;
+        for (int m = lane; m < M; m += 64) t += loss_part[((long)agent * M + m) * 3 + wave];
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) t += __shfl_xor(t, off, 64);
+        if (lane == 0) stats[agent * 5 + wave] = t * (1.0f / (float)M);
+    }
+    const float4 *pg = reinterpret_cast<const float4 *>(g + agent * d_pad);
+    float acc = 0.f;
+#pragma unroll 4
+    for (long k = tail_begin / 4 + threadIdx.x; k < d_pad / 4; k += 256) {
+        const float4 v = pg[k];
+        acc += (v.x * v.x + v.y * v.y) + (v.z * v.z + v.w * v.w);
+    }
+    if (threadIdx.x < NORM_USED) acc += ssq[agent * NORM_PARTS + threadIdx.x];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off, 64);
+    if (lane == 0) red[wave] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float ss = 0.f;
+        for (int w = 0; w < 4; ++w) ss += red[w];
+        const float norm = sqrtf(ss);
+        stats[agent * 5 + 3] = norm;
+        stats[agent * 5 + 4] = fminf(1.f, max_norm / (norm + 1e-6f));
+    }
 }
 
 static constexpr int reduce_blocks(long len) { return (int)((len / 4 + 255) / 256); }
-
-static hipError_t reduce_splits(const float *part, int S, long len, int N, float *out, long out_stride,
-                                float *ssq, int ssq_slot, hipStream_t s)
-{
-    hipLaunchKernelGGL(reduce_splits_kernel, dim3(reduce_blocks(len), N), dim3(256), 0, s, part, S, len, out,
-                       out_stride, ssq, ssq_slot);
-    return hipGetLastError();
-}
 
 // ---- hidden layer epilogue + heads ---------------------------------------------------------------
 // One workgroup of 128 threads per (frame, agent): h = relu(sum of the split-K partials + b_fc),
@@ -828,16 +878,24 @@ static inline int cdiv(long a, long b) { return (int)((a + b - 1) / b); }
 constexpr int FC_KCHUNK = 784;          // 3136 = 4 * 784
 constexpr int FC_KCHUNK_SMALL = 224;    // few frames: twice the splits, so that enough workgroups stream the weights
 constexpr int FC_SMALL_FRAMES = 32;
-constexpr int FPS_CONV1 = 2, FPS_CONV2 = 8, FPS_CONV3 = 16;   // frames per split of the weight gradients
+constexpr int FPS_CONV1 = 2, FPS_CONV2 = 8, FPS_CONV3 = 16;   // frames per split of the weight gradients (conv1: at least)
+// conv1's weight gradient is one tile per agent and split: enough splits to fill the machine, no more (every split
+// is a partial the reduction has to read again: 40 splits of two frames at 32 agents x 80 frames cost 12 us of
+// reading, 20 splits of four frames 6 us, with the same kernel time)
+static inline int conv1_frames_per_split(int N, int M)
+{
+    long fps = (long)N * M / 640;                        // about 640 workgroups
+    return (int)(fps < FPS_CONV1 ? FPS_CONV1 : (fps > 8 ? 8 : fps));
+}
 
 size_t workspace_floats(int N, int M, int F)
 {
     size_t need = (size_t)N * cdiv(FLAT, FC_KCHUNK) * F * FC;
     auto mx = [&](size_t v) { if (v > need) need = v; };
     mx((size_t)N * cdiv(FLAT, FC_KCHUNK_SMALL) * FC_SMALL_FRAMES * FC);
-    mx((size_t)N * cdiv(M, FPS_CONV1) * Conv1Wgrad::PART);
-    mx((size_t)N * cdiv(M, FPS_CONV2) * Conv2Wgrad::PART);
-    mx((size_t)N * cdiv(M, FPS_CONV3) * Conv3Wgrad::PART);
+    // the three convolutions' weight-gradient partials live side by side until one kernel sums them all
+    mx((size_t)N * cdiv(M, FPS_CONV1) * Conv1Wgrad::PART + (size_t)N * cdiv(M, FPS_CONV2) * Conv2Wgrad::PART +
+       (size_t)N * cdiv(M, FPS_CONV3) * Conv3Wgrad::PART);
     return need + 1024;
 }
 
@@ -846,7 +904,7 @@ size_t workspace_floats(int N, int M, int F)
 constexpr int SSQ_CONV1 = FC_WGRAD_TILES;
 constexpr int SSQ_CONV2 = SSQ_CONV1 + reduce_blocks(Conv1Wgrad::PART);
 constexpr int SSQ_CONV3 = SSQ_CONV2 + reduce_blocks(Conv2Wgrad::PART);
-static_assert(SSQ_CONV3 + reduce_blocks(Conv3Wgrad::PART) == NORM_USED, "gradient-norm partial slots");
+static_assert(SSQ_CONV3 + reduce_blocks(Conv3Wgrad::PART) == NORM_USED && NORM_USED <= 256, "gradient-norm partial slots");
 
 #define GALA_TRY(expr) do { hipError_t e_ = (expr); if (e_ != hipSuccess) return e_; } while (0)
 
@@ -900,9 +958,13 @@ hipError_t launch_forward(const NetArgs &a, hipStream_t s, PhaseTimer *pt, hipEv
 // gradient needs only that layer's output gradient.  With a side stream the weight-gradient
 // kernels run next to the chain, so that the partly filled last round of workgroups of one
 // kernel overlaps work of the other; the same kernels run in both modes, results are identical.
-hipError_t launch_backward(const NetArgs &a, hipStream_t s, PhaseTimer *pt, const SideStream *side)
+hipError_t launch_backward(const NetArgs &a, const HParams &hp, hipStream_t s, PhaseTimer *pt, const SideStream *side)
 {
     const Layout &L = a.L;
+    // regions of the workspace for the three convolutions' weight-gradient partials
+    const int fps1 = conv1_frames_per_split(a.N, a.M);
+    const int S3 = cdiv(a.M, FPS_CONV3), S2 = cdiv(a.M, FPS_CONV2), S1 = cdiv(a.M, fps1);
+    float *ws3 = a.b.ws, *ws2 = ws3 + (size_t)a.N * S3 * Conv3Wgrad::PART, *ws1 = ws2 + (size_t)a.N * S2 * Conv2Wgrad::PART;
     const bool fork = side && side->stream && !pt->on;     // per-phase timing needs one stream
     hipStream_t w = fork ? side->stream : s;                // where weight gradients go
     int n_ev = 0;
@@ -913,10 +975,8 @@ hipError_t launch_backward(const NetArgs &a, hipStream_t s, PhaseTimer *pt, cons
         GALA_TRY(hipEventRecord(e, s));
         return hipStreamWaitEvent(w, e, 0);
     };
-    // dzh came with the loss; the loss terms' means are off the data-gradient chain
+    // dzh came with the loss
     GALA_TRY(publish());
-    GALA_TRY(launch_loss_stats(a, w));
-    pt->mark("loss_stats");
     hipLaunchKernelGGL(heads_wgrad_kernel, dim3(L.n_actions + 1, a.N, FC / 256), dim3(256), 0, w, a.b.h, L, a.M, a.F,
                        a.b.dlogits, a.b.dvalues, a.b.g);
     GALA_TRY(hipGetLastError());
@@ -941,12 +1001,10 @@ hipError_t launch_backward(const NetArgs &a, hipStream_t s, PhaseTimer *pt, cons
     // conv3
     {
         Conv3Wgrad p{};
-        p.in = a.b.a2; p.dz = a.b.dz3; p.ws = a.b.ws; p.M = a.M; p.F = a.F; p.fps = FPS_CONV3;
-        p.tiles_m = cdiv(KW3, Conv3Wgrad::BM); p.tiles_n = 1; p.splits = cdiv(a.M, FPS_CONV3);
+        p.in = a.b.a2; p.dz = a.b.dz3; p.ws = ws3; p.M = a.M; p.F = a.F; p.fps = FPS_CONV3;
+        p.tiles_m = cdiv(KW3, Conv3Wgrad::BM); p.tiles_n = 1; p.splits = S3;
         GALA_TRY(igemm_launch(p, a.N, w, a.bf16));
         pt->mark("conv3_wgrad");
-        GALA_TRY(reduce_splits(a.b.ws, p.splits, Conv3Wgrad::PART, a.N, a.b.g + L.w3, L.d_pad, a.b.norm_part, SSQ_CONV3, w));
-        pt->mark("conv3_wgrad_reduce");
     }
     {
         Conv3Dgrad p{};
@@ -960,12 +1018,18 @@ hipError_t launch_backward(const NetArgs &a, hipStream_t s, PhaseTimer *pt, cons
     // conv2
     {
         Conv2Wgrad p{};
-        p.in = a.b.a1; p.dz = a.b.dz2; p.ws = a.b.ws; p.M = a.M; p.F = a.F; p.fps = FPS_CONV2;
-        p.tiles_m = cdiv(KW2, Conv2Wgrad::BM); p.tiles_n = 1; p.splits = cdiv(a.M, FPS_CONV2);
+        p.in = a.b.a1; p.dz = a.b.dz2; p.ws = ws2; p.M = a.M; p.F = a.F; p.fps = FPS_CONV2;
+        p.tiles_m = cdiv(KW2, Conv2Wgrad::BM); p.tiles_n = 1; p.splits = S2;
         GALA_TRY(igemm_launch(p, a.N, w, a.bf16));
         pt->mark("conv2_wgrad");
-        GALA_TRY(reduce_splits(a.b.ws, p.splits, Conv2Wgrad::PART, a.N, a.b.g + L.w2, L.d_pad, a.b.norm_part, SSQ_CONV2, w));
-        pt->mark("conv2_wgrad_reduce");
+        // the partials of conv3 and conv2 in one launch, beside the data-gradient chain
+        ReduceSeg none{nullptr, 0, 0, 0, 0, 0};
+        ReduceSeg r3{ws3, S3, reduce_blocks(Conv3Wgrad::PART), SSQ_CONV3, Conv3Wgrad::PART, L.w3};
+        ReduceSeg r2{ws2, S2, reduce_blocks(Conv2Wgrad::PART), SSQ_CONV2, Conv2Wgrad::PART, L.w2};
+        hipLaunchKernelGGL(reduce_grads_kernel, dim3(r3.blocks + r2.blocks, a.N), dim3(256), 0, w, r3, r2, none, a.b.g,
+                           L.d_pad, a.b.norm_part);
+        GALA_TRY(hipGetLastError());
+        pt->mark("conv32_wgrad_reduce");
     }
     {
         Conv2Dgrad p{};
@@ -979,12 +1043,23 @@ hipError_t launch_backward(const NetArgs &a, hipStream_t s, PhaseTimer *pt, cons
     // conv1 (the input needs no gradient)
     {
         Conv1Wgrad p{};
-        p.obs = a.obs; p.dz1 = a.b.dz1; p.ws = a.b.ws; p.M = a.M; p.fps = FPS_CONV1;
-        p.tiles_m = 1; p.tiles_n = 1; p.splits = cdiv(a.M, FPS_CONV1);
+        p.obs = a.obs; p.dz1 = a.b.dz1; p.ws = ws1; p.M = a.M; p.fps = fps1;
+        p.tiles_m = 1; p.tiles_n = 1; p.splits = S1;
         GALA_TRY(igemm_launch(p, a.N, w, a.bf16));
         pt->mark("conv1_wgrad");
-        GALA_TRY(reduce_splits(a.b.ws, p.splits, Conv1Wgrad::PART, a.N, a.b.g + L.w1, L.d_pad, a.b.norm_part, SSQ_CONV1, w));
+    }
+    {
+        // every weight gradient is out (same stream): conv1's partials, then each agent's statistics
+        ReduceSeg none{nullptr, 0, 0, 0, 0, 0};
+        ReduceSeg r1{ws1, S1, reduce_blocks(Conv1Wgrad::PART), SSQ_CONV1, Conv1Wgrad::PART, L.w1};
+        hipLaunchKernelGGL(reduce_grads_kernel, dim3(r1.blocks, a.N), dim3(256), 0, w, none, none, r1, a.b.g, L.d_pad,
+                           a.b.norm_part);
+        GALA_TRY(hipGetLastError());
         pt->mark("conv1_wgrad_reduce");
+        hipLaunchKernelGGL(step_stats_kernel, dim3(a.N), dim3(256), 0, w, a.b.g, L.d_pad, L.fcb, a.b.norm_part, a.M,
+                           a.b.loss_part, hp.max_grad_norm, a.b.stats);
+        GALA_TRY(hipGetLastError());
+        pt->mark("step_stats");
     }
     if (fork) {                                             // the gradient is complete once both streams are
         GALA_TRY(hipEventRecord(side->join, w));

@@ -134,6 +134,15 @@ static __device__ __forceinline__ gala_bf16x8 gala_cat(gala_s16x4 lo, gala_s16x4
     return __builtin_bit_cast(gala_bf16x8, v);
 }
 
+// ds_read_b64_tr_b16: every lane gives the LDS address of four consecutive 16-bit values.  Within each
+// block of 16 lanes the 16 x 4 values addressed are taken as four rows of 16 (row r = what lanes 4r .. 4r + 3
+// address, in lane order) and arrive transposed: lane i receives column i of rows 0..3 as its four values.
+static __device__ __forceinline__ gala_s16x4 gala_lds_read_tr(const unsigned short *p)
+{
+    typedef gala_s16x4 __attribute__((address_space(3))) *lds_ptr;
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p));
+}
+
 // two floats -> two bf16 (round to nearest even) packed in 32 bits
 static __device__ __forceinline__ unsigned gala_pack_bf16(float lo, float hi)
 {
@@ -213,6 +222,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MODE == 3 ?
     //  - row-contiguous operand (four rows at one k, stored as single shorts by lanes whose rows lie
     //    four apart): rows padded to BK + 4 shorts (ten dwords, sixteen rows on sixteen bank pairs) and
     //    the quads exchanged by the row's bits 4..5, which spreads the stores of rows four apart.
+    //    (this second layout serves only a build with GALA_NO_TR_READ; see below)
     constexpr int RA = BK + (P::A_KC ? 0 : 4), RB = BK + (P::B_KC ? 0 : 4);     // row lengths in shorts
     // A_DIRECT: with one column of wavefronts (WN == 1) no two wavefronts need the same A rows, and a
     // k-contiguous A group (one row, four consecutive k) is exactly what an MFMA lane holds: every
@@ -225,7 +235,22 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MODE == 3 ?
     constexpr bool B_DIRECT = BF16 && P::B_DIRECT && (MODE != 1 || P::DIRECT_SINGLE_PIECE);
     static_assert(!B_DIRECT || (P::B_KC && P::WM == 1 && !P::SUM_B && P::MFMA16 && !A_DIRECT), "direct B operands: k-contiguous, one wavefront row");
     constexpr int NB_LDS = B_DIRECT ? 0 : NB;
-    constexpr int LDS_F32 = 2 * BK * (SA + SB), LDS_BF16 = BF16 ? (2 * (NA_LDS * BM * RA + NB_LDS * BN * RB) + 1) / 2 : 0;
+    // Row-contiguous operands (weight-gradient operands, weights stored [k][n]) keep their memory order in
+    // LDS, [piece][k][row] with 16 shorts of padding per k-row: a thread stores the four rows it loaded at
+    // one k as 8 bytes per piece, and the MFMA operand is fetched by the transposing LDS read of gfx950
+    // (ds_read_b64_tr_b16): within each block of 16 lanes, lane i reads rows 4 (i % 4) .. + 3 at k-row i / 4
+    // and receives row i at those four k.  The padding moves consecutive k-rows by 8 banks, so the four
+    // 32-byte segments a block reads lie on distinct banks, and a k-row's 16 storing lanes write 128
+    // contiguous bytes.  (Single 16-bit stores into a [row][k] tile, four per thread, group and piece, were
+    // the alternative.)
+#ifdef GALA_NO_TR_READ
+    constexpr bool A_TR = false, B_TR = false;
+#else
+    constexpr bool A_TR = BF16 && !P::A_KC, B_TR = BF16 && !P::B_KC;
+#endif
+    constexpr int PITCH_A = BM + 16, PITCH_B = BN + 16;                           // shorts per k-row of a transposed tile
+    constexpr int SZA = A_TR ? BK * PITCH_A : BM * RA, SZB = B_TR ? BK * PITCH_B : BN * RB;   // shorts per piece and buffer
+    constexpr int LDS_F32 = 2 * BK * (SA + SB), LDS_BF16 = BF16 ? (2 * (NA_LDS * SZA + NB_LDS * SZB) + 1) / 2 : 0;
     constexpr int LDS_LOOP = (A_DIRECT || B_DIRECT) ? LDS_BF16 : (LDS_F32 > LDS_BF16 ? LDS_F32 : LDS_BF16), LDS_OUT = SLAB * SC;
     constexpr int LDS_FLOATS = LDS_LOOP > LDS_OUT ? LDS_LOOP : LDS_OUT;
     __shared__ __attribute__((aligned(16))) float smem[LDS_FLOATS];
@@ -233,15 +258,18 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MODE == 3 ?
     auto Bs = [&](int buf, int k, int c) -> float & { return smem[OFFB + (buf * BK + k) * SB + c]; };
     // bf16 tiles: [buf][row][BK + 4] shorts (the padding keeps 8-byte alignment and spreads banks)
     static_assert(!BF16 || (P::MFMA16 && BK == 16), "bf16 path: 16x16 blocks, four k-quads per tile row");
-    constexpr int OFFBH = 2 * NA_LDS * BM * RA;
-    static_assert(!BF16 || (2 * (NA_LDS * BM * RA + NB_LDS * BN * RB) * 2 <= LDS_FLOATS * 4), "bf16 tiles fit the allocation");
+    constexpr int OFFBH = 2 * NA_LDS * SZA;
+    static_assert(!BF16 || (2 * (NA_LDS * SZA + NB_LDS * SZB) * 2 <= LDS_FLOATS * 4), "bf16 tiles fit the allocation");
+    static_assert(OFFBH % 4 == 0 && SZA % 4 == 0 && SZB % 4 == 0, "8-byte aligned tiles");
     unsigned short *hs = reinterpret_cast<unsigned short *>(smem);
     auto swz = [](bool kc, int row, int k) { return k ^ ((((kc ? row >> 2 : row >> 4)) & 3) << 2); };
     auto Ah = [&](int buf, int piece, int m, int k) -> unsigned short & {
-        return hs[((buf * NA + piece) * BM + m) * RA + swz(P::A_KC, m, k)];
+        if constexpr (A_TR) return hs[(buf * NA + piece) * SZA + k * PITCH_A + m];
+        else return hs[((buf * NA + piece) * BM + m) * RA + swz(P::A_KC, m, k)];
     };
     auto Bh = [&](int buf, int piece, int n, int k) -> unsigned short & {
-        return hs[OFFBH + ((buf * NB_LDS + piece) * BN + n) * RB + swz(P::B_KC, n, k)];
+        if constexpr (B_TR) return hs[OFFBH + (buf * NB_LDS + piece) * SZB + k * PITCH_B + n];
+        else return hs[OFFBH + ((buf * NB_LDS + piece) * BN + n) * RB + swz(P::B_KC, n, k)];
     };
 
     const int bid = blockIdx.x;
@@ -369,6 +397,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MODE == 3 ?
                 }
             }
             int kl, q; map_a(0, kl, q);
+            if constexpr (A_TR) {
+#pragma unroll
+                for (int i = 0; i < PA; ++i) {               // four rows at k = kl + i: 8 bytes per piece
+                    unsigned lo[NA], hi[NA];
+                    gala_pieces4<NA>(rr[i], lo, hi);
+#pragma unroll
+                    for (int pc = 0; pc < NA; ++pc)
+                        *reinterpret_cast<uint2 *>(&Ah(buf, pc, q * 4, kl + i)) = make_uint2(lo[pc], hi[pc]);
+                }
+            } else
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const float along_k[4] = {rr[0][j], rr[1][j], PA == 4 ? rr[2 % PA][j] : 0.f, PA == 4 ? rr[3 % PA][j] : 0.f};
@@ -403,6 +441,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MODE == 3 ?
 #pragma unroll
                     for (int pc = 0; pc < NA; ++pc)
                         *reinterpret_cast<uint2 *>(&Ah(buf, pc, row, kq * 4)) = make_uint2(lo[pc], hi[pc]);
+                } else if (BF16 && A_TR) {
+                    int k, mq; map_a(i, k, mq);
+                    unsigned lo[NA], hi[NA];
+                    gala_pieces4<NA>(r, lo, hi);
+#pragma unroll
+                    for (int pc = 0; pc < NA; ++pc)
+                        *reinterpret_cast<uint2 *>(&Ah(buf, pc, mq * 4, k)) = make_uint2(lo[pc], hi[pc]);
                 } else if (BF16) {
                     int k, mq; map_a(i, k, mq);
                     unsigned lo[NA], hi[NA];
@@ -450,6 +495,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MODE == 3 ?
 #pragma unroll
                     for (int pc = 0; pc < NB; ++pc)
                         *reinterpret_cast<uint2 *>(&Bh(buf, pc, col, kq * 4)) = make_uint2(lo[pc], hi[pc]);
+                } else if (BF16 && B_TR) {
+                    int k, nq; map_mc(QB{}, i, k, nq);
+                    unsigned lo[NB], hi[NB];
+                    gala_pieces4<NB>(r, lo, hi);
+#pragma unroll
+                    for (int pc = 0; pc < NB; ++pc)
+                        *reinterpret_cast<uint2 *>(&Bh(buf, pc, nq * 4, k)) = make_uint2(lo[pc], hi[pc]);
                 } else if (BF16) {
                     int k, nq; map_mc(QB{}, i, k, nq);
                     unsigned lo[NB], hi[NB];
@@ -512,6 +564,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MODE == 3 ?
 #pragma unroll
                     for (int i = 0; i < BI; ++i) {
                         if constexpr (A_DIRECT) a[pc][i] = areg[pc][i];
+                        else if constexpr (A_TR) a[pc][i] = gala_lds_read_tr(&Ah(buf, pc, wm0 + i * MB + 4 * (lr & 3), kk + lk * 4 + (lr >> 2)));
                         else a[pc][i] = *reinterpret_cast<const gala_s16x4 *>(&Ah(buf, pc, wm0 + i * MB + lr, kk + lk * 4));
                     }
 #pragma unroll
@@ -519,6 +572,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MODE == 3 ?
 #pragma unroll
                     for (int j = 0; j < BJ; ++j) {
                         if constexpr (B_DIRECT) b[q][j] = breg[q][j];
+                        else if constexpr (B_TR) b[q][j] = gala_lds_read_tr(&Bh(buf, q, wn0 + j * MB + 4 * (lr & 3), kk + lk * 4 + (lr >> 2)));
                         else b[q][j] = *reinterpret_cast<const gala_s16x4 *>(&Bh(buf, q, wn0 + j * MB + lr, kk + lk * 4));
                     }
                 // Products of pieces a_pc b_q with pc + q <= NB - 1, the small ones first.  The

@@ -36,7 +36,7 @@ PEAK_HBM_GBS = 8000.0
 # phases whose kernels reach fp32 accuracy with bf16 matrix instructions on exact bf16 pieces of the
 # operands: pieces multiplied per algorithmic product
 SPLIT_PRODUCTS = {"conv1_fwd": 3, "conv1_wgrad": 3, "conv2_fwd": 6, "conv3_fwd": 6, "fc_fwd": 6,
-                  "fc_dgrad": 6, "fc_wgrad": 6, "conv3_dgrad": 6, "conv2_wgrad": 6, "conv2_dgrad": 6}
+                  "fc_dgrad": 6, "fc_wgrad": 6, "conv3_dgrad": 6, "conv3_wgrad": 6, "conv2_wgrad": 6, "conv2_dgrad": 6}
 
 
 def kernel_of_phase(dtype: str) -> dict:

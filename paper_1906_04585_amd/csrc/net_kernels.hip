@@ -524,7 +524,8 @@ struct WalkCtx { unsigned moff; int p; unsigned foff; int k; };
 // live in zero-paged buffers: groups past the end of the split's k-range read zeros.
 template <int CI, int HI, int WI, int CO, int HO, int WO, int KS, int ST, int BM_>
 struct ConvWgrad : ProblemBase {
-    static constexpr bool SPLIT3 = BM_ >= 128;     // the 64 x 64 tile of the third convolution is faster on fp32 MFMAs
+    static constexpr bool SPLIT3 = true;           // (conv3's 64 x 64 tile: 97 us on fp32 MFMAs, 87 us here; a 192 x 64 tile is
+                                                   // faster alone, 75 us, but its 480 workgroups cost the round more beside conv3's data gradient)
     static constexpr int BM = BM_, BN = 64, BK = 16, WM = 2, WN = 2;
     static constexpr bool A_KC = false, B_KC = false;
     static constexpr bool SUM_B = true;

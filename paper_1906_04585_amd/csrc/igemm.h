@@ -241,7 +241,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MODE == 3 ?
     // (ds_read_b64_tr_b16): within each block of 16 lanes, lane i reads rows 4 (i % 4) .. + 3 at k-row i / 4
     // and receives row i at those four k.  The padding moves consecutive k-rows by 8 banks, so the four
     // 32-byte segments a block reads lie on distinct banks, and a k-row's 16 storing lanes write 128
-    // contiguous bytes.  (Single 16-bit stores into a [row][k] tile, four per thread, group and piece, were
+    // contiguous bytes.  Blocks of 16 rows are exchanged by bits 2..3 of k, which the four k-rows of a read
+    // share: it separates the k-rows four apart that the lanes of one store instruction hit where a thread
+    // owns consecutive k of one quad of rows (bank conflicts 55 % -> measured below).  (Single 16-bit stores into a [row][k] tile, four per thread, group and piece, were
     // the alternative.)
 #ifdef GALA_NO_TR_READ
     constexpr bool A_TR = false, B_TR = false;
@@ -264,11 +266,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MODE == 3 ?
     unsigned short *hs = reinterpret_cast<unsigned short *>(smem);
     auto swz = [](bool kc, int row, int k) { return k ^ ((((kc ? row >> 2 : row >> 4)) & 3) << 2); };
     auto Ah = [&](int buf, int piece, int m, int k) -> unsigned short & {
-        if constexpr (A_TR) return hs[(buf * NA + piece) * SZA + k * PITCH_A + m];
+        if constexpr (A_TR) return hs[(buf * NA + piece) * SZA + k * PITCH_A + (m ^ (((k >> 2) << 4) & (BM - 1) & 0x30))];
         else return hs[((buf * NA + piece) * BM + m) * RA + swz(P::A_KC, m, k)];
     };
     auto Bh = [&](int buf, int piece, int n, int k) -> unsigned short & {
-        if constexpr (B_TR) return hs[OFFBH + (buf * NB_LDS + piece) * SZB + k * PITCH_B + n];
+        if constexpr (B_TR) return hs[OFFBH + (buf * NB_LDS + piece) * SZB + k * PITCH_B + (n ^ (((k >> 2) << 4) & (BN - 1) & 0x30))];
         else return hs[OFFBH + ((buf * NB_LDS + piece) * BN + n) * RB + swz(P::B_KC, n, k)];
     };
 
@@ -336,8 +338,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MODE == 3 ?
     // bf16 tiles are [row][k]: an m-contiguous A operand would scatter single bf16 values.  Where
     // possible a thread therefore takes PA consecutive k of one quad of rows, so that it owns a
     // 4 x PA block and stores PA consecutive bf16 per row in one piece.
+    // (a transposed tile takes 8-byte stores anyway: only a block fetch still wants this arrangement)
     constexpr bool KCONS_A = BF16 && !P::A_KC && !P::SUM_A && GA % 256 == 0 && 256 % (BM / 4) == 0 &&
-                             (PA == 2 || PA == 4);
+                             (PA == 2 || PA == 4) && (!A_TR || P::BLOCK_FETCH_A);
     constexpr int KT_A = KCONS_A ? 256 / (BM / 4) : 1;          // threads that share a quad of rows
     auto map_a = [&](int i, int &kl, int &q) {
         if (KCONS_A) { kl = (tid % KT_A) * PA + i; q = tid / KT_A; }

@@ -81,6 +81,11 @@
 //                                           the global loads) in between the MFMAs of a tile; set where measured faster
 //   static constexpr int  PREFETCH          k-tiles of global loads in flight ahead of the MFMAs: 1, or 2 with a
 //                                           second set of load registers
+//   static constexpr bool PIPELINE          modes 2 and 3: the loop's steady state runs without branches, with two
+//                                           tiles of loads in flight and (direct operands) two register sets, so
+//                                           that the scheduler may place the staging of tile t + 1 among the MFMAs
+//                                           of tile t; set where measured faster (it costs registers)
+//   static constexpr bool PIPELINE_SINGLE   the same for mode 1
 //   static constexpr bool SUMSQ             optional: the workgroup also delivers the sum of
 //                                           squares of what it stored, through
 //                                           template <bool CHECK> float sumsq4(m, n, v) (the share of
@@ -300,7 +305,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MODE == 3 ?
     constexpr int GA = BM * BK / 4, GB = BN * BK / 4;       // groups of four per tile
     constexpr int PA = (GA + 255) / 256, PB = (GB + 255) / 256;
     // Global loads run PF k-tiles ahead of the MFMAs, one register set per tile in flight.
-    constexpr int PF = P::PREFETCH;
+    // PIPE: the k-loop's steady state has no branches and two tiles of loads in flight, so that the staging
+    // arithmetic of tile t + 1 (whose loads were issued a whole tile earlier) can be scheduled in between the
+    // MFMAs of tile t instead of behind a wait for loads just issued; direct operands take two register sets
+    // (one being multiplied, one being filled).
+    constexpr bool PIPE = BF16 && (MODE == 1 ? P::PIPELINE_SINGLE : P::PIPELINE);
+    constexpr int PF = PIPE ? 2 : P::PREFETCH;
     static_assert(PF == 1 || PF == 2, "one or two k-tiles of loads in flight");
     typename P::ARaw ra[PF][PA];
     typename P::BRaw rb[PF][PB];
@@ -308,9 +318,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MODE == 3 ?
     typename P::CtxB cb[PB];
     bool oka[PF][PA], okb[PF][PB];
     static_assert(!A_DIRECT || PA == BI, "direct A operands: one group per MFMA block row of the wavefront");
-    gala_s16x4 areg[NA][A_DIRECT ? BI : 1];       // A_DIRECT: the pieces of the tile about to be multiplied
+    constexpr int NR = PIPE ? 2 : 1;
+    gala_s16x4 areg[NR][NA][A_DIRECT ? BI : 1];   // A_DIRECT: the pieces of the tile about to be multiplied
     static_assert(!B_DIRECT || PB == BJ, "direct B operands: one group per MFMA block column of the wavefront");
-    gala_s16x4 breg[NB][B_DIRECT ? BJ : 1];
+    gala_s16x4 breg[NR][NB][B_DIRECT ? BJ : 1];
     static_assert(!P::SUM_A || (!P::A_KC && 256 % (BM / 4) == 0), "SUM_A needs m-contiguous groups");
     static_assert(!P::SUM_B || (!P::B_KC && 256 % (BN / 4) == 0), "SUM_B needs n-contiguous groups");
     static_assert(!P::SUM_A || (BM / 4) % (256 / BK) == 0 || PA == 1, "SUM_A: one pass unless k is shared");
@@ -436,7 +447,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MODE == 3 ?
                     unsigned lo[NA], hi[NA];
                     gala_pieces4<NA>(r, lo, hi);
 #pragma unroll
-                    for (int pc = 0; pc < NA; ++pc) areg[pc][i] = __builtin_bit_cast(gala_s16x4, make_uint2(lo[pc], hi[pc]));
+                    for (int pc = 0; pc < NA; ++pc) areg[PIPE ? buf : 0][pc][i] = __builtin_bit_cast(gala_s16x4, make_uint2(lo[pc], hi[pc]));
                 } else if (BF16 && P::A_KC) {
                     const int row = g / (BK / 4), kq = g % (BK / 4);
                     unsigned lo[NA], hi[NA];
@@ -490,7 +501,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MODE == 3 ?
                     unsigned lo[NB], hi[NB];
                     gala_pieces4<NB>(r, lo, hi);
 #pragma unroll
-                    for (int pc = 0; pc < NB; ++pc) breg[pc][i] = __builtin_bit_cast(gala_s16x4, make_uint2(lo[pc], hi[pc]));
+                    for (int pc = 0; pc < NB; ++pc) breg[PIPE ? buf : 0][pc][i] = __builtin_bit_cast(gala_s16x4, make_uint2(lo[pc], hi[pc]));
                 } else if (BF16 && P::B_KC) {
                     const int col = g / (BK / 4), kq = g % (BK / 4);
                     unsigned lo[NB], hi[NB];
@@ -551,10 +562,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MODE == 3 ?
     // One k-tile: request the next tile, run this tile's MFMAs out of buffer `buf`, stage the
     // next tile into the other buffer.  `buf` is a compile-time constant (the loop below is
     // unrolled by two) so that every LDS address is a per-lane base plus an immediate.
-    auto tile_step = [&](auto bufc, int kt) {
+    auto tile_step = [&](auto bufc, auto fullc, int kt) {
         constexpr int buf = decltype(bufc)::value;
+        constexpr bool FULL = decltype(fullc)::value;      // steady state: tiles kt + PF and kt + 1 exist
         // tile kt sits in LDS buffer kt % 2 and came through register set kt % PF
-        if (kt + PF < nkt) fetch(std::integral_constant<int, PF == 2 ? buf : 0>{}, p.ktile_k0(kt + PF, BK));
+        if (FULL || kt + PF < nkt) fetch(std::integral_constant<int, PF == 2 ? buf : 0>{}, p.ktile_k0(kt + PF, BK));
         // keep the global loads of the next tile ahead of this tile's MFMAs: without the fence
         // the scheduler sinks them next to their first use and their latency is exposed
         __builtin_amdgcn_sched_barrier(0);
@@ -566,7 +578,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MODE == 3 ?
                 for (int pc = 0; pc < NA; ++pc)
 #pragma unroll
                     for (int i = 0; i < BI; ++i) {
-                        if constexpr (A_DIRECT) a[pc][i] = areg[pc][i];
+                        if constexpr (A_DIRECT) a[pc][i] = areg[PIPE ? buf : 0][pc][i];
                         else if constexpr (A_TR) a[pc][i] = gala_lds_read_tr(&Ah(buf, pc, wm0 + i * MB + 4 * (lr & 3), kk + lk * 4 + (lr >> 2)));
                         else a[pc][i] = *reinterpret_cast<const gala_s16x4 *>(&Ah(buf, pc, wm0 + i * MB + lr, kk + lk * 4));
                     }
@@ -574,7 +586,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MODE == 3 ?
                 for (int q = 0; q < NB; ++q)
 #pragma unroll
                     for (int j = 0; j < BJ; ++j) {
-                        if constexpr (B_DIRECT) b[q][j] = breg[q][j];
+                        if constexpr (B_DIRECT) b[q][j] = breg[PIPE ? buf : 0][q][j];
                         else if constexpr (B_TR) b[q][j] = gala_lds_read_tr(&Bh(buf, q, wn0 + j * MB + 4 * (lr & 3), kk + lk * 4 + (lr >> 2)));
                         else b[q][j] = *reinterpret_cast<const gala_s16x4 *>(&Bh(buf, q, wn0 + j * MB + lr, kk + lk * 4));
                     }
@@ -647,12 +659,19 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MODE == 3 ?
         // loads: otherwise the scheduler mixes the staging code (and its wait) in between them and the
         // matrix instructions still to come sit behind a memory wait
         if constexpr (BF16 && P::FENCE_STAGING) __builtin_amdgcn_sched_barrier(0);
-        if (kt + 1 < nkt) stage(std::integral_constant<int, buf ^ 1>{}, std::integral_constant<int, PF == 2 ? buf ^ 1 : 0>{});
+        if (FULL || kt + 1 < nkt) stage(std::integral_constant<int, buf ^ 1>{}, std::integral_constant<int, PF == 2 ? buf ^ 1 : 0>{});
         __syncthreads();
     };
-    for (int kt = 0; kt < nkt; kt += 2) {
-        tile_step(std::integral_constant<int, 0>{}, kt);
-        if (kt + 1 < nkt) tile_step(std::integral_constant<int, 1>{}, kt + 1);
+    int kt = 0;
+    if constexpr (PIPE) {
+        for (; kt + PF + 1 < nkt; kt += 2) {
+            tile_step(std::integral_constant<int, 0>{}, std::true_type{}, kt);
+            tile_step(std::integral_constant<int, 1>{}, std::true_type{}, kt + 1);
+        }
+    }
+    for (; kt < nkt; kt += 2) {
+        tile_step(std::integral_constant<int, 0>{}, std::false_type{}, kt);
+        if (kt + 1 < nkt) tile_step(std::integral_constant<int, 1>{}, std::false_type{}, kt + 1);
     }
 
     // Operand sums: every thread holds partial sums of the four rows (columns) of each of its

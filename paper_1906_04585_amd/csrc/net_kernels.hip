@@ -63,6 +63,8 @@ struct ProblemBase {
     static constexpr bool A_EXACT_BF16 = false;   // true: every A value is an integer 0..255 (a byte image)
     static constexpr int PREFETCH = 1;            // k-tiles of global loads in flight (1 or 2)
     static constexpr bool FENCE_STAGING = false;  // bf16 modes: all MFMAs of a tile before the staging of the next
+    static constexpr bool PIPELINE = false;       // modes 2, 3: branch-free steady state, two tiles of loads in flight
+    static constexpr bool PIPELINE_SINGLE = false; // the same for mode 1
     static constexpr bool SPLIT3 = false;         // true: fp32 accuracy from three bf16 pieces of both operands
     static constexpr bool A_DIRECT = false;       // true: bf16 modes take A from global memory into the MFMA lanes
     static constexpr bool B_DIRECT = false;       // the same for B
@@ -96,6 +98,7 @@ struct Conv1Fwd : ProblemBase {
     static constexpr bool A_KC = true, B_KC = false;
     static constexpr bool A_EXACT_BF16 = true;
     static constexpr int PREFETCH = 2;            // little work per k-tile (byte loads, K = 256): 3 % faster; slower elsewhere
+    static constexpr bool PIPELINE = true, PIPELINE_SINGLE = true;      // 110 -> 103 us; bf16 variant 83 -> 81 us
     static constexpr bool FENCE_STAGING = true;   // 4 % faster
     static constexpr bool A_DIRECT = true;        // fp32: 121 -> 116 us; the bf16 variant: 104 -> 83 us
     static constexpr bool DIRECT_SINGLE_PIECE = true;
@@ -155,6 +158,7 @@ struct ConvFwd : ProblemBase {
     static constexpr bool A_KC = true, B_KC = false;
     static constexpr bool SPLIT3 = true;
     static constexpr bool A_DIRECT = true;
+    static constexpr bool PIPELINE = true, PIPELINE_SINGLE = true;      // conv3: 81 -> 74 us, conv2: 106 -> 104 us; bf16 variant 88 -> 85 us (conv2)
     static_assert((KS * CI) % BK == 0, "a k-tile stays inside one kernel row");
     const float *in, *x;
     float *out;
@@ -215,6 +219,7 @@ using Conv3Fwd = ConvFwd<C2, H2, W2, C3, H3, W3, K3, S3>;
 template <int BM_>
 struct FcFwdT : ProblemBase {
     static constexpr int BM = BM_, BN = 128, BK = 16, WM = 1, WN = 4;
+    static constexpr bool PIPELINE_SINGLE = true;  // bf16 variant: 74 -> 69 us; with three pieces the second register set costs a wavefront per SIMD
     static constexpr bool A_KC = true, B_KC = true;
     static constexpr bool SPLIT3 = true;
     static constexpr bool B_DIRECT = true;        // each wavefront has its own 32 weight columns: 82 -> 77 us
@@ -248,6 +253,7 @@ using FcFwd = FcFwdT<96>;
 // m = f, n = flattened a3 index, k = j.
 struct FcDgrad : ProblemBase {
     static constexpr int BM = 80, BN = 128, BK = 16, WM = 1, WN = 4;     // 5 x 16 rows: no padding at M = 80, 160
+    static constexpr bool PIPELINE = true;         // 95 -> 92 us (the bf16 variant: 81 -> 84 us, left as it was)
     static constexpr bool A_KC = true, B_KC = false;
     static constexpr bool HAS_AUX = true;
     static constexpr bool SPLIT3 = true;
@@ -527,6 +533,7 @@ struct ConvWgrad : ProblemBase {
     static constexpr bool SPLIT3 = true;           // (conv3's 64 x 64 tile: 97 us on fp32 MFMAs, 87 us here; a 192 x 64 tile is
                                                    // faster alone, 75 us, but its 480 workgroups cost the round more beside conv3's data gradient)
     static constexpr int BM = BM_, BN = 64, BK = 16, WM = 2, WN = 2;
+    static constexpr bool PIPELINE = true;         // conv3: 88 -> 77 us, conv2: 104 -> 98 us (the bf16 variant: 49 -> 51, 56 -> 59 us, left as it was)
     static constexpr bool A_KC = false, B_KC = false;
     static constexpr bool SUM_B = true;
     static constexpr int MT = KS * KS * CI;
@@ -600,6 +607,7 @@ using Conv3Wgrad = ConvWgrad<C2, H2, W2, C3, H3, W3, K3, S3, 64>;
 // the caller's buffer (no zero page): groups past the k-range are zeroed after the load.
 struct Conv1Wgrad : ProblemBase {
     static constexpr int BM = 256, BN = 32, BK = 16, WM = 4, WN = 1;
+    static constexpr bool PIPELINE = true, PIPELINE_SINGLE = true;      // 106 -> 104 us; bf16 variant 100 -> 93 us
     static constexpr bool A_KC = false, B_KC = false;
     static constexpr bool SUM_B = true;
     static constexpr bool A_EXACT_BF16 = true;

@@ -86,6 +86,7 @@
 //                                           that the scheduler may place the staging of tile t + 1 among the MFMAs
 //                                           of tile t; set where measured faster (it costs registers)
 //   static constexpr bool PIPELINE_SINGLE   the same for mode 1
+//   static constexpr int  WAVES_SPLIT3      mode 3: wavefronts per SIMD the register allocation must leave room for
 //   static constexpr bool SUMSQ             optional: the workgroup also delivers the sum of
 //                                           squares of what it stored, through
 //                                           template <bool CHECK> float sumsq4(m, n, v) (the share of
@@ -194,7 +195,7 @@ static __device__ __forceinline__ void gala_pieces4(const float (&r)[4], unsigne
 //   16 k, each adding two piece products, take 3/8 of the matrix time of the four fp32 MFMAs
 //   they replace.
 template <class P, int MODE>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MODE == 3 ? 2 : 4))) void igemm_kernel(P p, int n_agents)
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MODE == 3 ? P::WAVES_SPLIT3 : 4))) void igemm_kernel(P p, int n_agents)
 {
     constexpr bool BF16 = MODE != 0;
     constexpr int NA = MODE == 3 ? 3 : 1;                       // bf16 pieces of the A operand
@@ -241,25 +242,27 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MODE == 3 ?
     static_assert(!B_DIRECT || (P::B_KC && P::WM == 1 && !P::SUM_B && P::MFMA16 && !A_DIRECT), "direct B operands: k-contiguous, one wavefront row");
     constexpr int NB_LDS = B_DIRECT ? 0 : NB;
     // Row-contiguous operands (weight-gradient operands, weights stored [k][n]) keep their memory order in
-    // LDS, [piece][k][row] with 16 shorts of padding per k-row: a thread stores the four rows it loaded at
-    // one k as 8 bytes per piece, and the MFMA operand is fetched by the transposing LDS read of gfx950
-    // (ds_read_b64_tr_b16): within each block of 16 lanes, lane i reads rows 4 (i % 4) .. + 3 at k-row i / 4
-    // and receives row i at those four k.  The padding moves consecutive k-rows by 8 banks, so the four
-    // 32-byte segments a block reads lie on distinct banks, and a k-row's 16 storing lanes write 128
-    // contiguous bytes.  Blocks of 16 rows are exchanged by bits 2..3 of k, which the four k-rows of a read
-    // share: it separates the k-rows four apart that the lanes of one store instruction hit where a thread
-    // owns consecutive k of one quad of rows (bank conflicts 55 % -> measured below).  (Single 16-bit stores into a [row][k] tile, four per thread, group and piece, were
-    // the alternative.)
+    // LDS, [piece][k][row]: a thread stores the four rows it loaded at one k as 8 bytes per piece, and the
+    // MFMA operand is fetched by the transposing LDS read of gfx950 (ds_read_b64_tr_b16): within each block
+    // of 16 lanes, lane i reads rows 4 (i % 4) .. + 3 at k-row i / 4 and receives row i at those four k.
+    // Tiles of a multiple of 64 rows have no padding (k-rows of 128 or 256 bytes all start on bank 0); the
+    // 16-row blocks (32 bytes, 8 banks) of every 64 rows are exchanged by (k ^ k / 4) % 4 instead.  The four
+    // k-rows of a read share k / 4 and differ in k % 4, so their segments lie on the four bank groups; a
+    // k-row's 16 storing lanes write a whole 128-byte line whatever the exchange; and where a thread owns
+    // consecutive k of one quad of rows (a block fetch), the lanes of one store instruction hold k-rows four
+    // apart, which differ in k / 4.  Narrower tiles (32 rows) keep 16 shorts of padding per k-row, which
+    // moves consecutive k-rows by 8 banks, and exchange their two blocks by bit 2 of k.
 #ifdef GALA_NO_TR_READ
     constexpr bool A_TR = false, B_TR = false;
 #else
     constexpr bool A_TR = BF16 && !P::A_KC, B_TR = BF16 && !P::B_KC;
 #endif
-    constexpr int PITCH_A = BM + 16, PITCH_B = BN + 16;                           // shorts per k-row of a transposed tile
+    constexpr int PITCH_A = BM + (BM % 64 ? 16 : 0), PITCH_B = BN + (BN % 64 ? 16 : 0);   // shorts per k-row of a transposed tile
     constexpr int SZA = A_TR ? BK * PITCH_A : BM * RA, SZB = B_TR ? BK * PITCH_B : BN * RB;   // shorts per piece and buffer
     constexpr int LDS_F32 = 2 * BK * (SA + SB), LDS_BF16 = BF16 ? (2 * (NA_LDS * SZA + NB_LDS * SZB) + 1) / 2 : 0;
-    constexpr int LDS_LOOP = (A_DIRECT || B_DIRECT) ? LDS_BF16 : (LDS_F32 > LDS_BF16 ? LDS_F32 : LDS_BF16), LDS_OUT = SLAB * SC;
-    constexpr int LDS_FLOATS = LDS_LOOP > LDS_OUT ? LDS_LOOP : LDS_OUT;
+    constexpr int LDS_LOOP = BF16 ? LDS_BF16 : LDS_F32, LDS_OUT = SLAB * SC;
+    constexpr int LDS_SUMS = (P::SUM_A || P::SUM_B) ? 1024 : 0;
+    constexpr int LDS_FLOATS = (LDS_LOOP > LDS_OUT ? LDS_LOOP : LDS_OUT) > LDS_SUMS ? (LDS_LOOP > LDS_OUT ? LDS_LOOP : LDS_OUT) : LDS_SUMS;
     __shared__ __attribute__((aligned(16))) float smem[LDS_FLOATS];
     auto As = [&](int buf, int k, int c) -> float & { return smem[(buf * BK + k) * SA + c]; };
     auto Bs = [&](int buf, int k, int c) -> float & { return smem[OFFB + (buf * BK + k) * SB + c]; };
@@ -269,13 +272,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MODE == 3 ?
     static_assert(!BF16 || (2 * (NA_LDS * SZA + NB_LDS * SZB) * 2 <= LDS_FLOATS * 4), "bf16 tiles fit the allocation");
     static_assert(OFFBH % 4 == 0 && SZA % 4 == 0 && SZB % 4 == 0, "8-byte aligned tiles");
     unsigned short *hs = reinterpret_cast<unsigned short *>(smem);
+    // transposed tiles: which 16-row block of its 64 a row's block is exchanged with at k-row k
+    auto tr_swz = [](int rows, int k) { return rows % 64 == 0 ? ((k ^ (k >> 2)) & 3) << 4 : ((k >> 2) << 4) & (rows - 1) & 0x30; };
     auto swz = [](bool kc, int row, int k) { return k ^ ((((kc ? row >> 2 : row >> 4)) & 3) << 2); };
     auto Ah = [&](int buf, int piece, int m, int k) -> unsigned short & {
-        if constexpr (A_TR) return hs[(buf * NA + piece) * SZA + k * PITCH_A + (m ^ (((k >> 2) << 4) & (BM - 1) & 0x30))];
+        if constexpr (A_TR) return hs[(buf * NA + piece) * SZA + k * PITCH_A + (m ^ tr_swz(BM, k))];
         else return hs[((buf * NA + piece) * BM + m) * RA + swz(P::A_KC, m, k)];
     };
     auto Bh = [&](int buf, int piece, int n, int k) -> unsigned short & {
-        if constexpr (B_TR) return hs[OFFBH + (buf * NB_LDS + piece) * SZB + k * PITCH_B + (n ^ (((k >> 2) << 4) & (BN - 1) & 0x30))];
+        if constexpr (B_TR) return hs[OFFBH + (buf * NB_LDS + piece) * SZB + k * PITCH_B + (n ^ tr_swz(BN, k))];
         else return hs[OFFBH + ((buf * NB_LDS + piece) * BN + n) * RB + swz(P::B_KC, n, k)];
     };
 

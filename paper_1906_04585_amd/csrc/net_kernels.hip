@@ -65,6 +65,7 @@ struct ProblemBase {
     static constexpr bool FENCE_STAGING = false;  // bf16 modes: all MFMAs of a tile before the staging of the next
     static constexpr bool PIPELINE = false;       // modes 2, 3: branch-free steady state, two tiles of loads in flight
     static constexpr bool PIPELINE_SINGLE = false; // the same for mode 1
+    static constexpr int WAVES_SPLIT3 = 2;         // mode 3: wavefronts per SIMD that the registers must allow
     static constexpr bool SPLIT3 = false;         // true: fp32 accuracy from three bf16 pieces of both operands
     static constexpr bool A_DIRECT = false;       // true: bf16 modes take A from global memory into the MFMA lanes
     static constexpr bool B_DIRECT = false;       // the same for B
@@ -291,6 +292,7 @@ struct FcDgrad : ProblemBase {
 // k-tile: groups beyond it are read from the start of the buffer and zeroed.
 struct FcWgrad : ProblemBase {
     static constexpr int BM = 128, BN = 128, BK = 16, WM = 2, WN = 2;
+    static constexpr int WAVES_SPLIT3 = 3;        // 168 registers and 48 KB of tiles: three workgroups per CU instead of two, 73 -> 66 us
     static constexpr bool A_KC = false, B_KC = false;
     static constexpr bool SUM_A = true, A_ZERO = true, B_ZERO = true;
     static constexpr bool SPLIT3 = true;

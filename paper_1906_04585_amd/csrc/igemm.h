@@ -87,6 +87,7 @@
 //                                           of tile t; set where measured faster (it costs registers)
 //   static constexpr bool PIPELINE_SINGLE   the same for mode 1
 //   static constexpr int  WAVES_SPLIT3      mode 3: wavefronts per SIMD the register allocation must leave room for
+//   static constexpr int  WAVES             the same for the other modes
 //   static constexpr bool SUMSQ             optional: the workgroup also delivers the sum of
 //                                           squares of what it stored, through
 //                                           template <bool CHECK> float sumsq4(m, n, v) (the share of
@@ -195,7 +196,7 @@ static __device__ __forceinline__ void gala_pieces4(const float (&r)[4], unsigne
 //   16 k, each adding two piece products, take 3/8 of the matrix time of the four fp32 MFMAs
 //   they replace.
 template <class P, int MODE>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MODE == 3 ? P::WAVES_SPLIT3 : 4))) void igemm_kernel(P p, int n_agents)
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MODE == 3 ? P::WAVES_SPLIT3 : P::WAVES))) void igemm_kernel(P p, int n_agents)
 {
     constexpr bool BF16 = MODE != 0;
     constexpr int NA = MODE == 3 ? 3 : 1;                       // bf16 pieces of the A operand

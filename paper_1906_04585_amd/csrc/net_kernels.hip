@@ -66,6 +66,7 @@ struct ProblemBase {
     static constexpr bool PIPELINE = false;       // modes 2, 3: branch-free steady state, two tiles of loads in flight
     static constexpr bool PIPELINE_SINGLE = false; // the same for mode 1
     static constexpr int WAVES_SPLIT3 = 2;         // mode 3: wavefronts per SIMD that the registers must allow
+    static constexpr int WAVES = 4;                // the other modes
     static constexpr bool SPLIT3 = false;         // true: fp32 accuracy from three bf16 pieces of both operands
     static constexpr bool A_DIRECT = false;       // true: bf16 modes take A from global memory into the MFMA lanes
     static constexpr bool B_DIRECT = false;       // the same for B
@@ -610,6 +611,7 @@ using Conv3Wgrad = ConvWgrad<C2, H2, W2, C3, H3, W3, K3, S3, 64>;
 struct Conv1Wgrad : ProblemBase {
     static constexpr int BM = 256, BN = 32, BK = 16, WM = 4, WN = 1;
     static constexpr bool PIPELINE = true, PIPELINE_SINGLE = true;      // 106 -> 104 us; bf16 variant 100 -> 93 us
+    static constexpr int WAVES = 3;                // four would spill to scratch memory (110 instead of 104 us)
     static constexpr bool A_KC = false, B_KC = false;
     static constexpr bool SUM_B = true;
     static constexpr bool A_EXACT_BF16 = true;

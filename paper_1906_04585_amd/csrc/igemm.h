@@ -246,13 +246,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MODE == 3 ?
     // LDS, [piece][k][row]: a thread stores the four rows it loaded at one k as 8 bytes per piece, and the
     // MFMA operand is fetched by the transposing LDS read of gfx950 (ds_read_b64_tr_b16): within each block
     // of 16 lanes, lane i reads rows 4 (i % 4) .. + 3 at k-row i / 4 and receives row i at those four k.
-    // Tiles of a multiple of 64 rows have no padding (k-rows of 128 or 256 bytes all start on bank 0); the
-    // 16-row blocks (32 bytes, 8 banks) of every 64 rows are exchanged by (k ^ k / 4) % 4 instead.  The four
-    // k-rows of a read share k / 4 and differ in k % 4, so their segments lie on the four bank groups; a
-    // k-row's 16 storing lanes write a whole 128-byte line whatever the exchange; and where a thread owns
-    // consecutive k of one quad of rows (a block fetch), the lanes of one store instruction hold k-rows four
-    // apart, which differ in k / 4.  Narrower tiles (32 rows) keep 16 shorts of padding per k-row, which
-    // moves consecutive k-rows by 8 banks, and exchange their two blocks by bit 2 of k.
+    // LDS serves these reads 32 lanes (256 bytes, 64 banks) at a time, i.e. two such blocks holding eight
+    // consecutive k-rows, and stores 16 lanes (128 bytes) at a time.  Tiles of a multiple of 64 rows have no
+    // padding; their 16-row blocks (32 bytes, 8 banks) are exchanged instead.  128 or 256 rows (k-rows start
+    // on bank 0): the block index is XORed with (k ^ k / 8) % 8, which puts the eight k-rows of a read on the
+    // eight bank groups; where a thread owns consecutive k of one quad of rows (a block fetch), the lanes of
+    // one store hold k-rows four apart, which that term separates as well.  64 rows (k-rows alternate between
+    // the two halves of the banks): XOR with (k ^ k / 4) % 4.  A k-row's 16 storing lanes write whole
+    // 128-byte lines whatever the exchange.  32-row tiles keep 16 shorts of padding per k-row instead, which
+    // moves consecutive k-rows by 24 banks: eight of them fall on eight different groups.
 #ifdef GALA_NO_TR_READ
     constexpr bool A_TR = false, B_TR = false;
 #else
@@ -273,8 +275,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MODE == 3 ?
     static_assert(!BF16 || (2 * (NA_LDS * SZA + NB_LDS * SZB) * 2 <= LDS_FLOATS * 4), "bf16 tiles fit the allocation");
     static_assert(OFFBH % 4 == 0 && SZA % 4 == 0 && SZB % 4 == 0, "8-byte aligned tiles");
     unsigned short *hs = reinterpret_cast<unsigned short *>(smem);
-    // transposed tiles: which 16-row block of its 64 a row's block is exchanged with at k-row k
-    auto tr_swz = [](int rows, int k) { return rows % 64 == 0 ? ((k ^ (k >> 2)) & 3) << 4 : ((k >> 2) << 4) & (rows - 1) & 0x30; };
+    // transposed tiles: the 16-row block a row's block is exchanged with at k-row k (see above)
+    auto tr_swz = [](int rows, int k) {
+        return rows % 128 == 0 ? ((k ^ (k >> 3)) & 7) << 4 : rows % 64 == 0 ? ((k ^ (k >> 2)) & 3) << 4 : 0;
+    };
     auto swz = [](bool kc, int row, int k) { return k ^ ((((kc ? row >> 2 : row >> 4)) & 3) << 2); };
     auto Ah = [&](int buf, int piece, int m, int k) -> unsigned short & {
         if constexpr (A_TR) return hs[(buf * NA + piece) * SZA + k * PITCH_A + (m ^ tr_swz(BM, k))];

@@ -8,34 +8,95 @@ namespace gala {
 typedef float diag_f32x4 __attribute__((ext_vector_type(4)));
 
 // ---- Gram matrix  G G^T  of the gradient arena ------------------------------------------------
-// Agents are cut into tiles of GRAM_T rows; a workgroup owns one pair of tiles (ti <= tj) and
-// one contiguous range of parameter columns, which its four wavefronts walk in steps of 16
-// columns, GRAM_UNROLL consecutive steps per wavefront at a time (256 contiguous bytes of every
-// row, so that both halves of a cache line are asked for by the same wavefront back to back).
-// No LDS staging is needed: lane l loads the float4 of agent l % 16 at columns
-// 4 (l / 16) .. + 3 of the step, and element e of that float4 is the lane's operand of
-// the e-th 16x16x4 fp32 MFMA.  That pairs the MFMA's k index (l / 16) with column
-// 4 (l / 16) + e, a permutation of the step's 16 columns that is the same for both operands,
-// which is all a sum over columns needs.  The wavefronts' results are added in a fixed order
-// and stored per (pair, chunk).  Every gradient is read once per tile pair it takes part in:
-// the kernel is bound by HBM.
+// Agents are cut into tiles of GRAM_T rows; a workgroup owns one pair of tiles (ti <= tj) and one
+// contiguous range of parameter columns, which it walks GRAM_COLS columns at a time.  Memory is read
+// the way it is laid out: every wavefront load takes one KB of one agent's row (lane l the float4
+// at columns 4 l), eight rows per wavefront and tile side; the next slab's loads are in flight while
+// the current one is multiplied.  The slab goes to LDS ([row][GRAM_COLS + 4]: the four floats of
+// padding put the sixteen rows of an operand read on sixteen groups of four banks), from where a
+// wavefront reads its own 64 columns as MFMA operands: lane l takes the float4 of agent l % 16 at
+// columns 4 (l / 16) .. + 3 of a 16-column step, and element e of that float4 is the lane's operand
+// of the e-th 16x16x4 fp32 MFMA.  That pairs the MFMA's k index (l / 16) with column 4 (l / 16) + e,
+// a permutation of the step's 16 columns that is the same for both operands, which is all a sum
+// over columns needs.  On the diagonal (ti == tj) the lower left block is the transpose of the upper
+// right one and is not computed.  The wavefronts' results are added in a fixed order and stored per
+// (pair, chunk).  Every gradient is read once per tile pair it takes part in: the kernel is bound by
+// HBM (loading the operands from global memory straight into the MFMA lanes, 64 bytes per row and
+// load, ran at 3.0 TB/s; this form reads whole lines).
 constexpr int GRAM_STEP = 16;           // columns per MFMA group
-constexpr int GRAM_UNROLL = 4;          // steps in flight per wavefront
-constexpr int GRAM_WORKGROUPS = 256;    // workgroups in all (more, or more steps in flight, change nothing: measured)
+constexpr int GRAM_COLS = 256;          // columns per slab: one KB per row
+constexpr int GRAM_PITCH = GRAM_COLS + 4;
+constexpr int GRAM_WORKGROUPS = 1024;   // workgroups in all
 
+template <bool SAME>
+__device__ __forceinline__ void gram_body(const float *__restrict__ g, int N, long d_pad, int ti, int tj,
+                                          long t0, long t1, float *smem, diag_f32x4 (&acc)[2][2])
+{
+    constexpr int SIDES = SAME ? 1 : 2;
+    constexpr int NL = 8 * SIDES;                       // float4 loads per thread and slab
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int lr = lane & 15, lk = lane >> 4;
+    // rows this thread loads: 8 per side, rows of a missing agent are read from row 0 and zeroed
+    const float *src[NL];
+    bool valid[NL];
+#pragma unroll
+    for (int i = 0; i < NL; ++i) {
+        const int r = (i < 8 ? ti : tj) * GRAM_T + wave * 8 + (i & 7);
+        valid[i] = r < N;
+        src[i] = g + (valid[i] ? (long)r * d_pad : 0L) + 4 * lane;
+    }
+    float4 regs[NL];
+    auto fetch = [&](long t) {
+#pragma unroll
+        for (int i = 0; i < NL; ++i) regs[i] = *reinterpret_cast<const float4 *>(src[i] + t * GRAM_COLS);
+    };
+    auto lds_row = [&](int side, int row) { return smem + (side * GRAM_T + row) * GRAM_PITCH; };
+    if (t0 < t1) fetch(t0);
+    for (long t = t0; t < t1; ++t) {
+#pragma unroll
+        for (int i = 0; i < NL; ++i) {
+            const float4 v = valid[i] ? regs[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+            *reinterpret_cast<float4 *>(lds_row(i >> 3, wave * 8 + (i & 7)) + 4 * lane) = v;
+        }
+        __syncthreads();
+        if (t + 1 < t1) fetch(t + 1);
+#pragma unroll
+        for (int st = 0; st < GRAM_COLS / 4 / GRAM_STEP; ++st) {
+            const int col = wave * (GRAM_COLS / 4) + st * GRAM_STEP + 4 * lk;
+            const float4 x0 = *reinterpret_cast<const float4 *>(lds_row(0, lr) + col);
+            const float4 x1 = *reinterpret_cast<const float4 *>(lds_row(0, lr + 16) + col);
+            const float4 y0 = SAME ? x0 : *reinterpret_cast<const float4 *>(lds_row(1, lr) + col);
+            const float4 y1 = SAME ? x1 : *reinterpret_cast<const float4 *>(lds_row(1, lr + 16) + col);
+            const float xa[4] = {x0.x, x0.y, x0.z, x0.w}, xb[4] = {x1.x, x1.y, x1.z, x1.w};
+            const float ya[4] = {y0.x, y0.y, y0.z, y0.w}, yb[4] = {y1.x, y1.y, y1.z, y1.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                acc[0][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[e], ya[e], acc[0][0], 0, 0, 0);
+                acc[0][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[e], yb[e], acc[0][1], 0, 0, 0);
+                if (!SAME) acc[1][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(xb[e], ya[e], acc[1][0], 0, 0, 0);
+                acc[1][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(xb[e], yb[e], acc[1][1], 0, 0, 0);
+            }
+        }
+        __syncthreads();
+    }
+}
+
+// SIDES = 1: a single tile of agents (N <= GRAM_T), half the LDS
+template <int SIDES>
 __global__ __launch_bounds__(256) void gram_kernel(const float *__restrict__ g, int N, long d_pad, int tiles,
                                                    int chunks, float *__restrict__ part)
 {
-    __shared__ float red[4 * GRAM_T * GRAM_T];
+    __shared__ __attribute__((aligned(16))) float smem[SIDES * GRAM_T * GRAM_PITCH];
+    static_assert(GRAM_T * GRAM_PITCH >= 4 * GRAM_T * GRAM_T, "the slab also holds the wavefronts' results");
     // pair index -> (ti, tj), ti <= tj
     int ti = 0, rest = blockIdx.y;
     while (rest >= tiles - ti) { rest -= tiles - ti; ++ti; }
     const int tj = ti + rest;
     const bool same = ti == tj;
     const int chunk = blockIdx.x;
-    const long steps = d_pad / GRAM_STEP;
-    const long per = (steps + chunks - 1) / chunks;
-    const long s0 = chunk * per, s1 = s0 + per < steps ? s0 + per : steps;
+    const long slabs = d_pad / GRAM_COLS;               // the arena's row length is a multiple of GRAM_COLS
+    const long per = (slabs + chunks - 1) / chunks;
+    const long t0 = chunk * per, t1 = t0 + per < slabs ? t0 + per : slabs;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int lr = lane & 15, lk = lane >> 4;
@@ -45,58 +106,23 @@ __global__ __launch_bounds__(256) void gram_kernel(const float *__restrict__ g, 
     for (int i = 0; i < 2; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j) acc[i][j] = diag_f32x4{0.f, 0.f, 0.f, 0.f};
+    if (SIDES == 1 || same) gram_body<true>(g, N, d_pad, ti, tj, t0, t1, smem, acc);
+    else if constexpr (SIDES == 2) gram_body<false>(g, N, d_pad, ti, tj, t0, t1, smem, acc);
 
-    // this lane's two agents per tile; rows beyond the last agent are read as zero from row 0
-    const int ra0 = ti * GRAM_T + lr, ra1 = ra0 + 16, rb0 = tj * GRAM_T + lr, rb1 = rb0 + 16;
-    const bool va0 = ra0 < N, va1 = ra1 < N, vb0 = rb0 < N, vb1 = rb1 < N;
-    const float *pa0 = g + (va0 ? (long)ra0 * d_pad : 0L) + 4 * lk, *pa1 = g + (va1 ? (long)ra1 * d_pad : 0L) + 4 * lk;
-    const float *pb0 = g + (vb0 ? (long)rb0 * d_pad : 0L) + 4 * lk, *pb1 = g + (vb1 ? (long)rb1 * d_pad : 0L) + 4 * lk;
-    auto ld = [&](const float *p, bool valid, long ss) -> float4 {
-        float4 v = *reinterpret_cast<const float4 *>(p + (ss < s1 ? ss : s0) * GRAM_STEP);   // always in range
-        if (!(valid && ss < s1)) v = make_float4(0.f, 0.f, 0.f, 0.f);
-        return v;
-    };
-    auto mma4 = [&](const float4 &x0, const float4 &x1, const float4 &y0, const float4 &y1) {
-        const float xa[4] = {x0.x, x0.y, x0.z, x0.w}, xb[4] = {x1.x, x1.y, x1.z, x1.w};
-        const float ya[4] = {y0.x, y0.y, y0.z, y0.w}, yb[4] = {y1.x, y1.y, y1.z, y1.w};
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            acc[0][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[e], ya[e], acc[0][0], 0, 0, 0);
-            acc[0][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[e], yb[e], acc[0][1], 0, 0, 0);
-            acc[1][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(xb[e], ya[e], acc[1][0], 0, 0, 0);
-            acc[1][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(xb[e], yb[e], acc[1][1], 0, 0, 0);
-        }
-    };
-    if (same) {
-        constexpr int U = GRAM_UNROLL;
-        for (long s = s0 + wave * U; s < s1; s += 4 * U) {
-            float4 a0[U], a1[U];
-#pragma unroll
-            for (int u = 0; u < U; ++u) { a0[u] = ld(pa0, va0, s + u); a1[u] = ld(pa1, va1, s + u); }
-#pragma unroll
-            for (int u = 0; u < U; ++u) mma4(a0[u], a1[u], a0[u], a1[u]);
-        }
-    } else {
-        for (long s = s0 + wave * GRAM_UNROLL; s < s1; s += 4 * GRAM_UNROLL) {
-            float4 a0[GRAM_UNROLL], a1[GRAM_UNROLL], b0[GRAM_UNROLL], b1[GRAM_UNROLL];
-#pragma unroll
-            for (int u = 0; u < GRAM_UNROLL; ++u) {
-                a0[u] = ld(pa0, va0, s + u); a1[u] = ld(pa1, va1, s + u);
-                b0[u] = ld(pb0, vb0, s + u); b1[u] = ld(pb1, vb1, s + u);
-            }
-#pragma unroll
-            for (int u = 0; u < GRAM_UNROLL; ++u) mma4(a0[u], a1[u], b0[u], b1[u]);
-        }
-    }
     // accumulator register v of lane l holds row 4 * (l / 16) + v, column l % 16 of its block
     static_assert(GRAM_T == 32, "two 16-row blocks per tile side");
+    float *red = smem;                                   // the loop ended with a barrier
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j)
 #pragma unroll
-            for (int v = 0; v < 4; ++v)
-                red[wave * (GRAM_T * GRAM_T) + (i * 16 + 4 * lk + v) * GRAM_T + j * 16 + lr] = acc[i][j][v];
+            for (int v = 0; v < 4; ++v) {
+                if (same && i == 1 && j == 0)            // mirror image of the upper right block
+                    red[wave * (GRAM_T * GRAM_T) + (16 + lr) * GRAM_T + 4 * lk + v] = acc[0][1][v];
+                else
+                    red[wave * (GRAM_T * GRAM_T) + (i * 16 + 4 * lk + v) * GRAM_T + j * 16 + lr] = acc[i][j][v];
+            }
     __syncthreads();
     float *out = part + ((long)blockIdx.y * chunks + chunk) * (GRAM_T * GRAM_T);
     for (int e = tid; e < GRAM_T * GRAM_T; e += 256)
@@ -154,12 +180,15 @@ int gram_chunks(int N)
     int c = GRAM_WORKGROUPS / gram_pairs(N);
     return c < 1 ? 1 : c;
 }
+static_assert(GRAM_WORKGROUPS >= 1, "at least one chunk");
 
 hipError_t launch_grad_cosine(int N, const Layout &L, const float *g, float *part, float *gram, float *cosm,
                               hipStream_t s)
 {
     const int tiles = gram_tiles(N), pairs = gram_pairs(N), chunks = gram_chunks(N);
-    hipLaunchKernelGGL(gram_kernel, dim3(chunks, pairs), dim3(256), 0, s, g, N, L.d_pad, tiles, chunks, part);
+    if (L.d_pad % GRAM_COLS != 0) return hipErrorInvalidValue;      // the layout pads every agent's slice to whole KB
+    if (tiles == 1) hipLaunchKernelGGL(gram_kernel<1>, dim3(chunks, pairs), dim3(256), 0, s, g, N, L.d_pad, tiles, chunks, part);
+    else hipLaunchKernelGGL(gram_kernel<2>, dim3(chunks, pairs), dim3(256), 0, s, g, N, L.d_pad, tiles, chunks, part);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(gram_reduce_kernel, dim3(pairs, GRAM_T), dim3(1024), 0, s, part, N, tiles, chunks, gram);

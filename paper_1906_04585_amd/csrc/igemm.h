@@ -220,17 +220,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MODE == 3 ?
     constexpr int OFFB = 2 * BK * SA;
     constexpr int SC = BN + 4;                  // row stride of the output slab
     constexpr int SLAB = P::WM * MB;            // rows per epilogue pass: one block-row per wavefront row
-    // bf16 tiles are [row][k] in one of two layouts, chosen per operand so that its staging stores and
-    // the MFMA operand read (8 bytes per lane: sixteen consecutive rows at one k-quad) both spread over
-    // the LDS banks:
-    //  - k-contiguous operand (four neighbouring lanes store one row's four quads, 8 bytes each): rows of
-    //    exactly BK shorts, so sixteen lanes store 128 contiguous bytes; the quads of a row are exchanged
-    //    by the row's bits 2..3, which puts the sixteen rows of an operand read on sixteen bank pairs;
-    //  - row-contiguous operand (four rows at one k, stored as single shorts by lanes whose rows lie
-    //    four apart): rows padded to BK + 4 shorts (ten dwords, sixteen rows on sixteen bank pairs) and
-    //    the quads exchanged by the row's bits 4..5, which spreads the stores of rows four apart.
-    //    (this second layout serves only a build with GALA_NO_TR_READ; see below)
-    constexpr int RA = BK + (P::A_KC ? 0 : 4), RB = BK + (P::B_KC ? 0 : 4);     // row lengths in shorts
+    // bf16 tiles of a k-contiguous operand are [piece][row][BK]: four neighbouring lanes store one row's four
+    // k-quads (8 bytes each), so sixteen lanes store 128 contiguous bytes, and an MFMA operand read is 8 bytes
+    // per lane (sixteen consecutive rows at one k-quad); the quads of a row are exchanged by the row's bits
+    // 2..3, which puts the sixteen rows of an operand read on sixteen bank pairs.  Row-contiguous operands
+    // use the transposed tiles described below.
+    constexpr int RA = BK, RB = BK;                                             // row lengths in shorts
     // A_DIRECT: with one column of wavefronts (WN == 1) no two wavefronts need the same A rows, and a
     // k-contiguous A group (one row, four consecutive k) is exactly what an MFMA lane holds: every
     // lane loads the groups of its own operand position, splits them into pieces in registers and
@@ -255,11 +250,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MODE == 3 ?
     // the two halves of the banks): XOR with (k ^ k / 4) % 4.  A k-row's 16 storing lanes write whole
     // 128-byte lines whatever the exchange.  32-row tiles keep 16 shorts of padding per k-row instead, which
     // moves consecutive k-rows by 24 banks: eight of them fall on eight different groups.
-#ifdef GALA_NO_TR_READ
-    constexpr bool A_TR = false, B_TR = false;
-#else
     constexpr bool A_TR = BF16 && !P::A_KC, B_TR = BF16 && !P::B_KC;
-#endif
     constexpr int PITCH_A = BM + (BM % 64 ? 16 : 0), PITCH_B = BN + (BN % 64 ? 16 : 0);   // shorts per k-row of a transposed tile
     constexpr int SZA = A_TR ? BK * PITCH_A : BM * RA, SZB = B_TR ? BK * PITCH_B : BN * RB;   // shorts per piece and buffer
     constexpr int LDS_F32 = 2 * BK * (SA + SB), LDS_BF16 = BF16 ? (2 * (NA_LDS * SZA + NB_LDS * SZB) + 1) / 2 : 0;
@@ -279,14 +270,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MODE == 3 ?
     auto tr_swz = [](int rows, int k) {
         return rows % 128 == 0 ? ((k ^ (k >> 3)) & 7) << 4 : rows % 64 == 0 ? ((k ^ (k >> 2)) & 3) << 4 : 0;
     };
-    auto swz = [](bool kc, int row, int k) { return k ^ ((((kc ? row >> 2 : row >> 4)) & 3) << 2); };
+    auto swz = [](int row, int k) { return k ^ (((row >> 2) & 3) << 2); };
     auto Ah = [&](int buf, int piece, int m, int k) -> unsigned short & {
         if constexpr (A_TR) return hs[(buf * NA + piece) * SZA + k * PITCH_A + (m ^ tr_swz(BM, k))];
-        else return hs[((buf * NA + piece) * BM + m) * RA + swz(P::A_KC, m, k)];
+        else return hs[((buf * NA + piece) * BM + m) * RA + swz(m, k)];
     };
     auto Bh = [&](int buf, int piece, int n, int k) -> unsigned short & {
         if constexpr (B_TR) return hs[OFFBH + (buf * NB_LDS + piece) * SZB + k * PITCH_B + (n ^ tr_swz(BN, k))];
-        else return hs[OFFBH + ((buf * NB_LDS + piece) * BN + n) * RB + swz(P::B_KC, n, k)];
+        else return hs[OFFBH + ((buf * NB_LDS + piece) * BN + n) * RB + swz(n, k)];
     };
 
     const int bid = blockIdx.x;
@@ -356,12 +347,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MODE == 3 ?
     };
     typedef std::integral_constant<int, BM / 4> QA;
     typedef std::integral_constant<int, BN / 4> QB;
-    // bf16 tiles are [row][k]: an m-contiguous A operand would scatter single bf16 values.  Where
-    // possible a thread therefore takes PA consecutive k of one quad of rows, so that it owns a
-    // 4 x PA block and stores PA consecutive bf16 per row in one piece.
-    // (a transposed tile takes 8-byte stores anyway: only a block fetch still wants this arrangement)
+    // A functor with a block fetch loads PA consecutive k of one quad of rows per thread (one wide load); the
+    // thread then owns a 4 x PA block of the tile and stores it as PA 8-byte k-rows per piece.
     constexpr bool KCONS_A = BF16 && !P::A_KC && !P::SUM_A && GA % 256 == 0 && 256 % (BM / 4) == 0 &&
-                             (PA == 2 || PA == 4) && (!A_TR || P::BLOCK_FETCH_A);
+                             (PA == 2 || PA == 4) && P::BLOCK_FETCH_A;
     constexpr int KT_A = KCONS_A ? 256 / (BM / 4) : 1;          // threads that share a quad of rows
     auto map_a = [&](int i, int &kl, int &q) {
         if (KCONS_A) { kl = (tid % KT_A) * PA + i; q = tid / KT_A; }
@@ -421,26 +410,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MODE == 3 ?
                 }
             }
             int kl, q; map_a(0, kl, q);
-            if constexpr (A_TR) {
 #pragma unroll
-                for (int i = 0; i < PA; ++i) {               // four rows at k = kl + i: 8 bytes per piece
-                    unsigned lo[NA], hi[NA];
-                    gala_pieces4<NA>(rr[i], lo, hi);
-#pragma unroll
-                    for (int pc = 0; pc < NA; ++pc)
-                        *reinterpret_cast<uint2 *>(&Ah(buf, pc, q * 4, kl + i)) = make_uint2(lo[pc], hi[pc]);
-                }
-            } else
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const float along_k[4] = {rr[0][j], rr[1][j], PA == 4 ? rr[2 % PA][j] : 0.f, PA == 4 ? rr[3 % PA][j] : 0.f};
+            for (int i = 0; i < PA; ++i) {                   // four rows at k = kl + i: 8 bytes per piece
                 unsigned lo[NA], hi[NA];
-                gala_pieces4<NA>(along_k, lo, hi);
+                gala_pieces4<NA>(rr[i], lo, hi);
 #pragma unroll
-                for (int pc = 0; pc < NA; ++pc) {
-                    if (PA == 4) *reinterpret_cast<uint2 *>(&Ah(buf, pc, q * 4 + j, kl)) = make_uint2(lo[pc], hi[pc]);
-                    else *reinterpret_cast<unsigned *>(&Ah(buf, pc, q * 4 + j, kl)) = lo[pc];
-                }
+                for (int pc = 0; pc < NA; ++pc)
+                    *reinterpret_cast<uint2 *>(&Ah(buf, pc, q * 4, kl + i)) = make_uint2(lo[pc], hi[pc]);
             }
         }
 #pragma unroll
@@ -472,17 +448,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MODE == 3 ?
 #pragma unroll
                     for (int pc = 0; pc < NA; ++pc)
                         *reinterpret_cast<uint2 *>(&Ah(buf, pc, mq * 4, k)) = make_uint2(lo[pc], hi[pc]);
-                } else if (BF16) {
-                    int k, mq; map_a(i, k, mq);
-                    unsigned lo[NA], hi[NA];
-                    gala_pieces4<NA>(r, lo, hi);
-#pragma unroll
-                    for (int pc = 0; pc < NA; ++pc) {
-                        Ah(buf, pc, mq * 4 + 0, k) = (unsigned short)(lo[pc] & 0xffffu);
-                        Ah(buf, pc, mq * 4 + 1, k) = (unsigned short)(lo[pc] >> 16);
-                        Ah(buf, pc, mq * 4 + 2, k) = (unsigned short)(hi[pc] & 0xffffu);
-                        Ah(buf, pc, mq * 4 + 3, k) = (unsigned short)(hi[pc] >> 16);
-                    }
                 } else if (P::A_KC) {
                     const int row = g / (BK / 4), kq = g % (BK / 4);
 #pragma unroll
@@ -526,17 +491,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MODE == 3 ?
 #pragma unroll
                     for (int pc = 0; pc < NB; ++pc)
                         *reinterpret_cast<uint2 *>(&Bh(buf, pc, nq * 4, k)) = make_uint2(lo[pc], hi[pc]);
-                } else if (BF16) {
-                    int k, nq; map_mc(QB{}, i, k, nq);
-                    unsigned lo[NB], hi[NB];
-                    gala_pieces4<NB>(r, lo, hi);
-#pragma unroll
-                    for (int pc = 0; pc < NB; ++pc) {
-                        Bh(buf, pc, nq * 4 + 0, k) = (unsigned short)(lo[pc] & 0xffffu);
-                        Bh(buf, pc, nq * 4 + 1, k) = (unsigned short)(lo[pc] >> 16);
-                        Bh(buf, pc, nq * 4 + 2, k) = (unsigned short)(hi[pc] & 0xffffu);
-                        Bh(buf, pc, nq * 4 + 3, k) = (unsigned short)(hi[pc] >> 16);
-                    }
                 } else if (P::B_KC) {
                     const int col = g / (BK / 4), kq = g % (BK / 4);
 #pragma unroll

@@ -288,10 +288,13 @@ extern "C" int gala_create(gala_ctx **out, int n_agents, const gala_topology *to
     if (he != hipSuccess) { fail(c, GALA_EHIP, "table upload: %s", hipGetErrorString(he)); return bail(GALA_EHIP); }
     if (!getenv("GALA_SINGLE_STREAM")) {
         he = hipStreamCreateWithFlags(&c->side.stream, hipStreamNonBlocking);
-        for (int i = 0; i < 4 && he == hipSuccess; ++i) he = hipEventCreateWithFlags(&c->side.fork[i], hipEventDisableTiming);
-        if (he == hipSuccess) he = hipEventCreateWithFlags(&c->side.join, hipEventDisableTiming);
-        if (he == hipSuccess) he = hipEventCreateWithFlags(&c->side.opt_fork, hipEventDisableTiming);
-        if (he == hipSuccess) he = hipEventCreateWithFlags(&c->side.opt_done, hipEventDisableTiming);
+        // the events order two streams of this device only: no system-scope fence (host or peer visibility) when
+        // one is recorded; a kernel's end still releases its writes to the device (8 us per round)
+        const unsigned evf = hipEventDisableTiming | hipEventDisableSystemFence;
+        for (int i = 0; i < 4 && he == hipSuccess; ++i) he = hipEventCreateWithFlags(&c->side.fork[i], evf);
+        if (he == hipSuccess) he = hipEventCreateWithFlags(&c->side.join, evf);
+        if (he == hipSuccess) he = hipEventCreateWithFlags(&c->side.opt_fork, evf);
+        if (he == hipSuccess) he = hipEventCreateWithFlags(&c->side.opt_done, evf);
         c->overlap_optimizer = getenv("GALA_OVERLAP_OPTIMIZER") != nullptr;
         if (he != hipSuccess) { fail(c, GALA_EHIP, "side stream: %s", hipGetErrorString(he)); return bail(GALA_EHIP); }
     }

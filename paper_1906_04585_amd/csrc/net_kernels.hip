@@ -1052,31 +1052,29 @@ hipError_t launch_backward(const NetArgs &a, const HParams &hp, hipStream_t s, P
         GALA_TRY(igemm_launch(p, a.N, s, a.bf16));
         pt->mark("conv2_dgrad");
     }
-    GALA_TRY(publish());
-    // conv1 (the input needs no gradient)
+    // conv1 (the input needs no gradient) follows conv2's data gradient on the same stream: nothing runs beside it
+    // any more, and the side stream's last kernel ends long before it does, so neither hand-over is waited for
+    if (fork) GALA_TRY(hipEventRecord(side->join, w));
     {
         Conv1Wgrad p{};
         p.obs = a.obs; p.dz1 = a.b.dz1; p.ws = ws1; p.M = a.M; p.fps = fps1;
         p.tiles_m = 1; p.tiles_n = 1; p.splits = S1;
-        GALA_TRY(igemm_launch(p, a.N, w, a.bf16));
+        GALA_TRY(igemm_launch(p, a.N, s, a.bf16));
         pt->mark("conv1_wgrad");
     }
     {
-        // every weight gradient is out (same stream): conv1's partials, then each agent's statistics
         ReduceSeg none{nullptr, 0, 0, 0, 0, 0};
         ReduceSeg r1{ws1, S1, reduce_blocks(Conv1Wgrad::PART), SSQ_CONV1, Conv1Wgrad::PART, L.w1};
-        hipLaunchKernelGGL(reduce_grads_kernel, dim3(r1.blocks, a.N), dim3(256), 0, w, none, none, r1, a.b.g, L.d_pad,
+        hipLaunchKernelGGL(reduce_grads_kernel, dim3(r1.blocks, a.N), dim3(256), 0, s, none, none, r1, a.b.g, L.d_pad,
                            a.b.norm_part);
         GALA_TRY(hipGetLastError());
         pt->mark("conv1_wgrad_reduce");
-        hipLaunchKernelGGL(step_stats_kernel, dim3(a.N), dim3(256), 0, w, a.b.g, L.d_pad, L.fcb, a.b.norm_part, a.M,
+        // every weight gradient is out once the side stream is done too: each agent's statistics
+        if (fork) GALA_TRY(hipStreamWaitEvent(s, side->join, 0));
+        hipLaunchKernelGGL(step_stats_kernel, dim3(a.N), dim3(256), 0, s, a.b.g, L.d_pad, L.fcb, a.b.norm_part, a.M,
                            a.b.loss_part, hp.max_grad_norm, a.b.stats);
         GALA_TRY(hipGetLastError());
         pt->mark("step_stats");
-    }
-    if (fork) {                                             // the gradient is complete once both streams are
-        GALA_TRY(hipEventRecord(side->join, w));
-        GALA_TRY(hipStreamWaitEvent(s, side->join, 0));
     }
     return hipSuccess;
 }

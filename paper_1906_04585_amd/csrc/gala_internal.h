@@ -155,8 +155,8 @@ struct SideStream {
     hipEvent_t join = nullptr;
     hipEvent_t opt_fork = nullptr, opt_done = nullptr;   // the hidden layer's share of the optimizer pass (optional overlap)
 };
-// data gradients on `s`, weight gradients on the side stream; ends with every agent's loss terms, gradient norm
-// and clip factor in stats
+// data gradients and conv1's weight gradient on `s`, the other weight gradients on the side stream; ends with every
+// agent's loss terms, gradient norm and clip factor in stats
 hipError_t launch_backward(const NetArgs &a, const HParams &hp, hipStream_t s, PhaseTimer *pt, const SideStream *side);
 size_t workspace_floats(int N, int M, int F);
 

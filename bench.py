@@ -12,8 +12,8 @@ pool of four rollouts is cycled.  One JSON line is printed on stdout.
 The 32-agent workload (--config 4, the default) runs 1000 timed rounds and then a second pass of
 the same length in which the distance from consensus (Prop. 1) is taken after every round by
 gala_consensus_distance_noalloc into a device-side log (no host round trip inside the loop); the
-per-round values go to gpurun_out/consensus_distance_cfg4.csv and their first/last/largest
-values and the cost of logging to the JSON line.
+per-round values go to consensus_distance_cfg4.csv in the output directory (--out-dir) and their
+first/last/largest values and the cost of logging to the JSON line.
 """
 from __future__ import annotations
 
@@ -124,6 +124,7 @@ def main() -> int:
                     help="second pass of --steps rounds with the distance from consensus taken every round "
                          "(auto: on for --config 4 in the fused or split mode)")
     ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--out-dir", default="gpurun_out", help="where the per-round consensus log is written (relative to the repository)")
     ap.add_argument("--config", type=int, default=4, help="workload shape 1..5 (default: 32 agents)")
     ap.add_argument("--dtype", choices=["f32", "bf16"], default="f32",
                     help="matrix-instruction operand type of the conv/fc kernels (parameters stay fp32)")
@@ -214,7 +215,7 @@ def main() -> int:
         torch.cuda.synchronize()
         logged_ms = 1e3 * (time.perf_counter() - t0) / args.steps
         vals = log.cpu().numpy()
-        out_dir = os.path.join(ROOT, "gpurun_out")
+        out_dir = os.path.join(ROOT, args.out_dir)
         os.makedirs(out_dir, exist_ok=True)
         csv = os.path.join(out_dir, f"consensus_distance_cfg{args.config}.csv")
         with open(csv, "w") as fh:

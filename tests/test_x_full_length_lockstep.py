@@ -7,7 +7,8 @@ sides then take one learner step and one gossip round from identical inputs and 
 tensor, loss term, norm, clip factor, post-update parameter tensor and RMSprop tensor of every
 agent is compared.  The file sorts behind the other GPU tests so that a run that stops at the
 first failure has reached everything else first.  GALA_TEST_ROUNDS / GALA_TEST_ROUNDS_DELAY
-shorten (or lengthen) the runs."""
+shorten (or lengthen) the runs.  Progress lines go to the terminal past pytest's capture, so that a
+run of several minutes is never silent."""
 import os
 
 import pytest
@@ -21,7 +22,7 @@ pytestmark = pytest.mark.gpu
 HP = gs.HPARAMS
 
 
-def _lockstep(cfg_id, rounds, seen_delays=None):
+def _lockstep(cfg_id, rounds, capsys, seen_delays=None):
     from paper_1906_04585_amd import Gala
     cfg = gs.CONFIGS[cfg_id]
     net = gs.make_net(cfg["n_actions"])
@@ -52,19 +53,22 @@ def _lockstep(cfg_id, rounds, seen_delays=None):
         if seen_delays is not None:
             seen_delays |= set(gpu.get_peer_table(r)[1][:, 0].tolist())
         if r % 10 == 9:
-            print(f"cfg{cfg_id}: {r + 1} rounds agree (largest factors so far: kappa {kappa:.2f}, value head "
-                  f"{rho:.2f}; worst gradient error / factor {worst:.2e})", flush=True)
-    print(f"cfg{cfg_id}: all {rounds} rounds agree; largest conditioning factors applied: kappa {kappa:.2f}, "
-          f"value head {rho:.2f}; at most {most_marked} ReLU unit(s) per round decided in the kernel's precision", flush=True)
+            with capsys.disabled():
+                print(f"\ncfg{cfg_id}: {r + 1} rounds agree (largest factors so far: kappa {kappa:.2f}, value head "
+                      f"{rho:.2f}; worst gradient error / factor {worst:.2e})", end="", flush=True)
+    with capsys.disabled():
+        print(f"\ncfg{cfg_id}: all {rounds} rounds agree; largest conditioning factors applied: kappa {kappa:.2f}, "
+              f"value head {rho:.2f}; at most {most_marked} ReLU unit(s) per round decided in the kernel's precision",
+              flush=True)
 
 
 @pytest.mark.timeout(900)
-def test_config2_lockstep_100_rounds():
-    _lockstep(2, int(os.environ.get("GALA_TEST_ROUNDS", "100")))
+def test_config2_lockstep_100_rounds(capsys):
+    _lockstep(2, int(os.environ.get("GALA_TEST_ROUNDS", "100")), capsys)
 
 
 @pytest.mark.timeout(1200)
-def test_config3_delayed_gossip_lockstep_200_rounds():
+def test_config3_delayed_gossip_lockstep_200_rounds(capsys):
     seen = set()
-    _lockstep(3, int(os.environ.get("GALA_TEST_ROUNDS_DELAY", "200")), seen)
+    _lockstep(3, int(os.environ.get("GALA_TEST_ROUNDS_DELAY", "200")), capsys, seen)
     assert seen == {0, 1, 2}

@@ -19,6 +19,20 @@ static __device__ __forceinline__ float4 ldg4b(const void *base, unsigned boff)
 {
     return *reinterpret_cast<const float4 *>(static_cast<const char *>(base) + boff);
 }
+// Streams that nothing reads again soon (the hidden layer's weights in its data gradient, its weight gradient on
+// the way out) carry the non-temporal hint, so that they do not push out what the next kernels read.
+typedef float stream_f32x4 __attribute__((ext_vector_type(4)));
+static __device__ __forceinline__ float4 ldg4b_stream(const void *base, unsigned boff)
+{
+    const stream_f32x4 t =
+        __builtin_nontemporal_load(reinterpret_cast<const stream_f32x4 *>(static_cast<const char *>(base) + boff));
+    return make_float4(t.x, t.y, t.z, t.w);
+}
+static __device__ __forceinline__ void st4_stream(float *p, float4 v)
+{
+    const stream_f32x4 t = {v.x, v.y, v.z, v.w};
+    __builtin_nontemporal_store(t, reinterpret_cast<stream_f32x4 *>(p));
+}
 static __device__ __forceinline__ uint32_t ldg_u32b(const void *base, unsigned boff)
 {
     return *reinterpret_cast<const uint32_t *>(static_cast<const char *>(base) + boff);
@@ -276,7 +290,9 @@ struct FcDgrad : ProblemBase {
     __device__ void prep_a(CtxA &c, int m, int kl) const { c.off = m < M ? (unsigned)((m * FC + kl) * 4) : 0u; }
     __device__ float4 fetch_a(CtxA &c, int kt0, bool &) const { return ldg4b(a_ + kt0, c.off); }
     __device__ void prep_b(CtxB &c, int kl, int n) const { c.off = n < FLAT ? (unsigned)((kl * FLAT + n) * 4) : 0u; }
-    __device__ float4 fetch_b(CtxB &c, int kt0, bool &) const { return ldg4b(w_ + (long)kt0 * FLAT, c.off); }
+    // every weight is read by one workgroup, once (the forward pass left them in the last-level cache; with the
+    // hint they do not displace a3 and dz3: 93 -> 79 us)
+    __device__ float4 fetch_b(CtxB &c, int kt0, bool &) const { return ldg4b_stream(w_ + (long)kt0 * FLAT, c.off); }
     __device__ bool tile_full(int m0, int n0) const { return m0 + BM <= M && n0 + BN <= FLAT; }
     template <bool CHECK> __device__ float4 aux4(int m, int n) const
     {
@@ -341,7 +357,9 @@ struct FcWgrad : ProblemBase {
     __device__ bool tile_full(int, int n0) const { return n0 + BN <= FLAT; }
     template <bool CHECK> __device__ void store4(int m, int n, float4 v, float4, float4) const
     {
-        if (!CHECK || n < FLAT) st4(out_ + (long)m * FLAT + n, v);
+        // 6.4 MB per agent that only the optimizer reads, a whole backward pass later: 66 -> 61.5 us, and the
+        // hidden layer's weights stay cached for its data gradient
+        if (!CHECK || n < FLAT) st4_stream(out_ + (long)m * FLAT + n, v);
     }
 };
 

@@ -48,7 +48,10 @@ __device__ __forceinline__ void gram_body(const float *__restrict__ g, int N, lo
     float4 regs[NL];
     auto fetch = [&](long t) {
 #pragma unroll
-        for (int i = 0; i < NL; ++i) regs[i] = *reinterpret_cast<const float4 *>(src[i] + t * GRAM_COLS);
+        for (int i = 0; i < NL; ++i) {        // read once, whole lines: the non-temporal hint (70 -> 42 us from HBM)
+            const diag_f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const diag_f32x4 *>(src[i] + t * GRAM_COLS));
+            regs[i] = make_float4(v[0], v[1], v[2], v[3]);
+        }
     };
     auto lds_row = [&](int side, int row) { return smem + (side * GRAM_T + row) * GRAM_PITCH; };
     if (t0 < t1) fetch(t0);
@@ -214,7 +217,10 @@ __global__ __launch_bounds__(256) void update_sumsq_kernel(const float *__restri
     const float4 *v4 = reinterpret_cast<const float4 *>(v + agent * d_pad);
     float acc = 0.f;
     for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < d_pad / 4; i += (long)gridDim.x * 256) {
-        const float4 gg = g4[i], vv = v4[i];
+        // both arenas are read once: non-temporal (81 -> 73 us, and the parameters stay cached for what follows)
+        const diag_f32x4 gn = __builtin_nontemporal_load(reinterpret_cast<const diag_f32x4 *>(g4 + i));
+        const diag_f32x4 vn = __builtin_nontemporal_load(reinterpret_cast<const diag_f32x4 *>(v4 + i));
+        const float4 gg = make_float4(gn[0], gn[1], gn[2], gn[3]), vv = make_float4(vn[0], vn[1], vn[2], vn[3]);
         const float a = lr * (c * gg.x) / (sqrtf(vv.x) + eps), b = lr * (c * gg.y) / (sqrtf(vv.y) + eps);
         const float p = lr * (c * gg.z) / (sqrtf(vv.z) + eps), q = lr * (c * gg.w) / (sqrtf(vv.w) + eps);
         acc += (a * a + b * b) + (p * p + q * q);

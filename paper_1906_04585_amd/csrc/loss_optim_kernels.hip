@@ -281,7 +281,7 @@ __global__ __launch_bounds__(256) void grad_mean_kernel(const float *__restrict_
         float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll 8
         for (int i = 0; i < N; ++i) {
-            const float4 t = reinterpret_cast<const float4 *>(g)[(long)i * n4 + e];
+            const float4 t = stream_load4(g, (long)i * n4 + e);      // every gradient is read once
             a.x += t.x; a.y += t.y; a.z += t.z; a.w += t.w;
         }
         const float inv = 1.f / (float)N;

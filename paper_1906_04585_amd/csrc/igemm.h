@@ -141,6 +141,23 @@ static __device__ __forceinline__ gala_bf16x8 gala_cat(gala_s16x4 lo, gala_s16x4
     return __builtin_bit_cast(gala_bf16x8, v);
 }
 
+// Three 8-byte operand pieces side by side in six registers, and the two overlapping 16-byte windows of them.
+typedef int gala_i32x6 __attribute__((ext_vector_type(6)));
+typedef int gala_i32x2 __attribute__((ext_vector_type(2)));
+static __device__ __forceinline__ gala_i32x6 gala_win(gala_s16x4 p, gala_s16x4 q, gala_s16x4 r)
+{
+    const gala_i32x2 P = __builtin_bit_cast(gala_i32x2, p), Q = __builtin_bit_cast(gala_i32x2, q), R = __builtin_bit_cast(gala_i32x2, r);
+    return gala_i32x6{P.x, P.y, Q.x, Q.y, R.x, R.y};
+}
+static __device__ __forceinline__ gala_bf16x8 gala_win_lo(gala_i32x6 w)
+{
+    return __builtin_bit_cast(gala_bf16x8, __builtin_shufflevector(w, w, 0, 1, 2, 3));
+}
+static __device__ __forceinline__ gala_bf16x8 gala_win_hi(gala_i32x6 w)
+{
+    return __builtin_bit_cast(gala_bf16x8, __builtin_shufflevector(w, w, 2, 3, 4, 5));
+}
+
 // ds_read_b64_tr_b16: every lane gives the LDS address of four consecutive 16-bit values.  Within each
 // block of 16 lanes the 16 x 4 values addressed are taken as four rows of 16 (row r = what lanes 4r .. 4r + 3
 // address, in lane order) and arrive transposed: lane i receives column i of rows 0..3 as its four values.
@@ -192,9 +209,10 @@ static __device__ __forceinline__ void gala_pieces4(const float (&r)[4], unsigne
 //   b = b0 + b1 + b2 the six products a_p b_q with p + q <= 2 carry the product to 2^-24 of
 //   |a||b| (what the three left out add up to at most: half a unit of fp32 round-off of the
 //   product); each bf16 product is exact in fp32 and
-//   the accumulation is fp32, small pieces first.  Three 16x16x32 instructions per block and
-//   16 k, each adding two piece products, take 3/8 of the matrix time of the four fp32 MFMAs
-//   they replace.
+//   the accumulation is fp32.  Three 16x16x32 instructions per block and 16 k, each adding two piece
+//   products (a1 b0 + a0 b2, a0 b1 + a2 b0, a1 b1 + a0 b0: with the pieces of an operand kept side by side
+//   in the order 1, 0, 2 every instruction's operand is a window of consecutive registers), take 3/8 of the
+//   matrix time of the four fp32 MFMAs they replace.
 template <class P, int MODE>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MODE == 3 ? P::WAVES_SPLIT3 : P::WAVES))) void igemm_kernel(P p, int n_agents)
 {
@@ -558,28 +576,28 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MODE == 3 ?
                 // 16x16x32 instruction takes eight k per lane: fed with the same four k of two
                 // different pieces it adds two such products at once.
                 if constexpr (MODE == 3) {
-                    gala_bf16x8 a01[BI], a02[BI], b21[BJ], b10[BJ], b00[BJ];
+                    // pieces side by side in the order (1, 0, 2): the pairs (1, 0) and (0, 2) that the three
+                    // instructions take are windows of consecutive registers, no copies
+                    gala_i32x6 aw[BI], bw[BJ];
 #pragma unroll
-                    for (int i = 0; i < BI; ++i) { a01[i] = gala_cat(a[0][i], a[1][i]); a02[i] = gala_cat(a[0][i], a[2][i]); }
+                    for (int i = 0; i < BI; ++i) aw[i] = gala_win(a[1][i], a[0][i], a[2][i]);
 #pragma unroll
-                    for (int j = 0; j < BJ; ++j) {
-                        b21[j] = gala_cat(b[2][j], b[1][j]); b10[j] = gala_cat(b[1][j], b[0][j]); b00[j] = gala_cat(b[0][j], b[0][j]);
-                    }
+                    for (int j = 0; j < BJ; ++j) bw[j] = gala_win(b[1][j], b[0][j], b[2][j]);
 #pragma unroll
                     for (int i = 0; i < BI; ++i)
 #pragma unroll
-                        for (int j = 0; j < BJ; ++j)       // a0 b2 + a1 b1
-                            acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a01[i], b21[j], acc[i][j], 0, 0, 0);
+                        for (int j = 0; j < BJ; ++j)       // a1 b0 + a0 b2
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(gala_win_lo(aw[i]), gala_win_hi(bw[j]), acc[i][j], 0, 0, 0);
 #pragma unroll
                     for (int i = 0; i < BI; ++i)
 #pragma unroll
                         for (int j = 0; j < BJ; ++j)       // a0 b1 + a2 b0
-                            acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a02[i], b10[j], acc[i][j], 0, 0, 0);
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(gala_win_hi(aw[i]), gala_win_lo(bw[j]), acc[i][j], 0, 0, 0);
 #pragma unroll
                     for (int i = 0; i < BI; ++i)
 #pragma unroll
-                        for (int j = 0; j < BJ; ++j)       // a0 b0 + a1 b0
-                            acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a01[i], b00[j], acc[i][j], 0, 0, 0);
+                        for (int j = 0; j < BJ; ++j)       // a1 b1 + a0 b0
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(gala_win_lo(aw[i]), gala_win_lo(bw[j]), acc[i][j], 0, 0, 0);
                 } else if constexpr (MODE == 2) {
                     // a (b0 + b1 + b2): the two small products in one 16x16x32 instruction, then a b0
                     gala_bf16x8 aa[BI], b21[BJ];
